@@ -1,0 +1,113 @@
+"""Oracle: the ADPSGD recurrence (test infrastructure; plain numpy, float32).
+
+State x_i^k (one flat float32 vector per learner), i = 0..L-1.  One iteration
+(Algorithm 1 and Eq. 2 of the paper, W_{k+1} = W_k T_k - a_k g(Phi_k, xi_k)):
+
+  1. (order, partner, active) = schedule(seed, k)
+  2. every active learner evaluates its minibatch gradient at x_i^{k-tau}
+     (tau = 0: Algorithm 3, the local model before mixing; tau = 1: delay by
+     one, Eq. for Phi_k in Section III-D, with x^{-1} := x^0)
+  3. x_i^{k+1} = sum_j T_k[i, j] x_j^k - lr * g_i^k ; a straggler keeps x_i^k.
+
+Rounding order of step 3 in float32 (the paper states none; this is the
+formula evaluated left to right, every operation rounded once, no fused
+multiply-add):
+  PAIR  m = (x_i + x_j) * 0.5            (self-matched: m = x_i)
+  TRI   m = ((x_left + x_i) + x_right) * (1/3)
+  ALL   m = (((x_0 + x_1) + x_2) + ...) * (1/L)
+  x_i^{k+1} = m - (lr * g_i)
+"""
+import numpy as np
+from . import schedule as S
+from . import lstm
+
+
+def init_model(seed, P, scale):
+    """w_0[e] = (2 u01(seed, INIT, 0, e) - 1) * scale, rounded to float32."""
+    out = np.empty(P, dtype=np.float32)
+    for e in range(P):
+        out[e] = np.float32((2.0 * S.u01(seed, S.STREAM_INIT, 0, e) - 1.0) * float(np.float32(scale)))
+    return out
+
+
+def mix_update(x, g, mix, order, partner, active, lr):
+    """One application of step 3 to x [L][P] float32 with g [L][P] float32.
+    Returns the new [L][P] array; x is not modified."""
+    x = np.asarray(x, dtype=np.float32)
+    L = x.shape[0]
+    lr = np.float32(lr)
+    out = np.empty_like(x)
+    if mix == S.MIX_ALL:
+        s = x[0].copy()
+        for j in range(1, L):
+            s = s + x[j]
+        m_all = s * (np.float32(1.0) / np.float32(L))
+    pos = {order[p]: p for p in range(L)}
+    for i in range(L):
+        if not active[i]:
+            out[i] = x[i]
+            continue
+        if mix == S.MIX_ALL:
+            m = m_all
+        elif mix == S.MIX_PAIR:
+            j = partner[i]
+            m = x[i] if j == i else (x[i] + x[j]) * np.float32(0.5)
+        elif mix == S.MIX_TRI:
+            p = pos[i]
+            left, right = order[(p - 1) % L], order[(p + 1) % L]
+            m = ((x[left] + x[i]) + x[right]) * (np.float32(1.0) / np.float32(3.0))
+        else:
+            raise ValueError("mix")
+        out[i] = m - (lr * np.asarray(g[i], dtype=np.float32))
+    return out
+
+
+class Oracle:
+    """L learners, model-bearing (shape given) or model-free (flat_params)."""
+
+    def __init__(self, L, pattern, seed, shape=None, flat_params=0, mix=None, tau=None,
+                 straggler_p=0.0, w0=None, x0=None, bf16_gemm=False):
+        self.L, self.pattern, self.seed = L, pattern, seed
+        self.shape = shape
+        self.P = lstm.param_count(shape) if shape is not None else int(flat_params)
+        self.mix = mix if mix is not None else (S.MIX_ALL if pattern == S.D1D else S.MIX_PAIR)
+        self.tau = tau if tau is not None else (1 if pattern == S.D1D else 0)
+        self.straggler_p = straggler_p
+        self.bf16_gemm = bf16_gemm
+        if x0 is not None:
+            self.x = np.array(x0, dtype=np.float32).reshape(L, self.P)
+        else:
+            self.x = np.tile(np.asarray(w0, dtype=np.float32).reshape(1, self.P), (L, 1))
+        self.x_prev = self.x.copy()      # x^{-1} := x^0
+        self.k = 0
+        self.last_grads = None
+        self.last_losses = None
+        self.last_schedule = None
+
+    def gradient_point(self):
+        return self.x_prev if self.tau == 1 else self.x
+
+    def step(self, batches, lr, grads=None):
+        """batches: list of (feats, labels) per learner; or grads [L][P] given
+        directly in model-free mode."""
+        order, partner, active = S.schedule(self.pattern, self.seed, self.k, self.L, self.straggler_p)
+        self.last_schedule = (order, partner, active)
+        if grads is None:
+            at = self.gradient_point()
+            grads = np.zeros((self.L, self.P), dtype=np.float32)
+            losses = np.zeros(self.L, dtype=np.float32)
+            for i in range(self.L):
+                if active[i]:
+                    feats, labels = batches[i]
+                    losses[i], grads[i] = lstm.loss_and_grad(self.shape, at[i], feats, labels,
+                                                             np.float32, self.bf16_gemm)
+            self.last_losses = losses
+        self.last_grads = grads
+        new = mix_update(self.x, grads, self.mix, order, partner, active, lr)
+        self.x_prev = self.x
+        self.x = new
+        self.k += 1
+
+    def average(self):
+        """Output model of Algorithm 1: the learner average (float64 mean)."""
+        return self.x.astype(np.float64).mean(axis=0)
