@@ -1,0 +1,191 @@
+/*
+ * adpsgd.h -- C ABI of the MI355X (gfx950) ADPSGD hot-path library.
+ *
+ * One ADPSGD iteration over L learners held as replicas on ONE GPU, following
+ * the paper's model (Section II, Eq. 2)
+ *
+ *        W_{k+1} = W_k T_k - a_k g(Phi_k, xi_k),       Phi_k = W_{k-tau}
+ *
+ *   (a) every learner's minibatch gradient of the mean cross-entropy of a
+ *       stacked (bi)directional LSTM acoustic model (Section IV: LSTM layers,
+ *       optional linear bottleneck, softmax over context-dependent states,
+ *       segments of T frames with zero initial state);
+ *   (b) the mixing term W_k T_k for the fixed ring (Section III-B), the
+ *       randomly permuted ring (Section III-C, Fisher-Yates) or the
+ *       delay-by-one scheme (Section III-D: T = 11'/L, gradient one iterate behind);
+ *   (c) the fused mixing + SGD update  w <- (mixed model) - lr * g  (Algorithm 1).
+ *
+ * Conventions
+ *   - Every function returns ADPSGD_OK (0) or a negative ADPSGD_E* code; the
+ *     text of the last error of the calling thread is adpsgd_last_error().
+ *     No C++ exception crosses this boundary.
+ *   - "dev" pointers are HIP device pointers on the device that was current at
+ *     adpsgd_create; "host" pointers are ordinary host memory.
+ *   - The library allocates NO device memory.  The caller allocates one
+ *     workspace of adpsgd_workspace_bytes() bytes (256-byte aligned), hands it
+ *     to adpsgd_create and keeps it alive until adpsgd_destroy.  All state
+ *     (models, gradients, activations) lives inside it.
+ *   - All work is enqueued on the HIP stream given at create; calls return
+ *     without waiting unless stated.  Calls on one handle must not overlap.
+ *   - Flat parameter layout of one learner (fp32, row-major, rows = output
+ *     units, gate blocks ordered i,f,g,o), I_0 = input_dim, I_l = D*hidden:
+ *         for l in layers:  W_x[l] [D][4H][I_l], W_h[l] [D][4H][H], b[l] [D][4H]
+ *         (bottleneck > 0)  W_p [Bn][D*H], b_p [Bn]
+ *         W_o [C][F], b_o [C]                         F = Bn or D*H
+ *     input_dim, hidden, bottleneck and classes must be multiples of 4.
+ *   - Batch layout: features [T][B][I] fp32 (time-major), labels [T][B] int32
+ *     in [0, classes).
+ */
+#ifndef ADPSGD_H
+#define ADPSGD_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define ADPSGD_OK        0
+#define ADPSGD_EINVAL   (-1)   /* bad argument or unsupported combination        */
+#define ADPSGD_ENOMEM   (-2)   /* workspace too small or misaligned              */
+#define ADPSGD_EHIP     (-3)   /* a HIP call failed (text in adpsgd_last_error)  */
+
+#define ADPSGD_MAX_LEARNERS 128
+
+typedef struct adpsgd_handle* adpsgd_t;   /* opaque; owned by the library (host memory) */
+
+/* Communication pattern (Section III-B / III-C / III-D). */
+typedef enum { ADPSGD_FIXED_RING = 0, ADPSGD_RANDOM_RING = 1, ADPSGD_D1D = 2 } adpsgd_pattern;
+/* Mixing operator applied along that pattern.
+ *   PAIR  (x_i + x_j)/2 with the partner j of a perfect matching on the ring order
+ *   ALL   the global mean, T = 11'/L (allreduce, Section III-A / III-D)
+ *   DEFAULT = PAIR for the rings, ALL for delay-by-one.                         */
+typedef enum { ADPSGD_MIX_DEFAULT = -1, ADPSGD_MIX_PAIR = 0, ADPSGD_MIX_ALL = 2 } adpsgd_mix;
+/* Arithmetic of the GEMMs: fp32 operands, or bf16 operands (rounded to nearest
+ * even from the fp32 master) with fp32 accumulation.  State, gates, softmax
+ * and the update are fp32 in both.                                              */
+typedef enum { ADPSGD_FP32 = 0, ADPSGD_BF16_GEMM = 1 } adpsgd_precision;
+
+typedef struct {
+    int32_t input_dim;      /* I: feature dimension (260 in the paper)           */
+    int32_t hidden;         /* H: LSTM cells per direction                       */
+    int32_t layers;         /* stacked LSTM layers (>= 1)                        */
+    int32_t bidirectional;  /* 0: one direction, 1: two, outputs concatenated    */
+    int32_t bottleneck;     /* Bn: width of the linear projection, 0 = none      */
+    int32_t classes;        /* C: softmax outputs                                */
+    int32_t batch;          /* B: segments per learner minibatch                 */
+    int32_t frames;         /* T: frames per segment (21 in the paper)           */
+    int64_t flat_params;    /* > 0: model-free mode, a learner is a flat vector
+                               of this many floats and adpsgd_step is handed
+                               gradients instead of minibatches                  */
+} adpsgd_model_shape;
+
+typedef struct {
+    int32_t            L;            /* learners, 1..ADPSGD_MAX_LEARNERS          */
+    adpsgd_model_shape shape;
+    int32_t            pattern;      /* adpsgd_pattern                            */
+    int32_t            mix;          /* adpsgd_mix                                */
+    int32_t            tau;          /* staleness of the gradient's model: 0, 1,
+                                        or -1 = default (1 for D1D, else 0)       */
+    int32_t            precision;    /* adpsgd_precision                          */
+    uint64_t           seed;         /* seed of the schedule (and of init_scale)  */
+    float              straggler_p;  /* probability that a learner sits an
+                                        iteration out (0 = never); rings only     */
+    float              init_scale;   /* > 0: all learners start from the same
+                                        w_0 ~ U(-a, a) (Algorithm 1, input);
+                                        0: models start as zeros, set them with
+                                        adpsgd_set_params                         */
+} adpsgd_config;
+
+/* Bytes of device workspace a handle with this configuration needs.
+ * cfg, out: host.  EINVAL if the configuration is not supported.               */
+int adpsgd_workspace_bytes(const adpsgd_config* cfg, size_t* out);
+
+/* Build a handle inside the caller's workspace (Algorithm 1, "Input": every
+ * learner starts from the same w_0).  dev_workspace: device, 256-byte aligned,
+ * at least adpsgd_workspace_bytes; hip_stream: a hipStream_t (NULL = the null
+ * stream).  Synchronises the stream once.  *out is valid only on ADPSGD_OK.    */
+int adpsgd_create(const adpsgd_config* cfg, void* dev_workspace, size_t bytes,
+                  void* hip_stream, adpsgd_t* out);
+
+/* One iteration k -> k+1 (Algorithm 3 / Algorithm 4 on every learner at once):
+ * schedule, gradients at x^{k-tau}, mixing, update.  Asynchronous.
+ * batch_ptrs: host array of device pointers.
+ *   model mode: [2L], batch_ptrs[2i] = features of learner i ([T][B][I] fp32),
+ *               batch_ptrs[2i+1] = labels of learner i ([T][B] int32);
+ *   flat mode:  [L],  batch_ptrs[i] = gradient of learner i ([flat_params] fp32).
+ * The buffers are read during the call's stream work and never written.
+ * A straggler's model is left bit-unchanged.                                   */
+int adpsgd_step(adpsgd_t h, const void* const* batch_ptrs, float lr);
+
+/* Device pointer to learner i's current model x_i^k ([P] fp32), borrowed.  With
+ * tau = 1 the two model buffers swap every iteration: query again after each
+ * step.  NULL on a bad argument.                                               */
+float* adpsgd_params(adpsgd_t h, int i);
+
+/* Overwrite learner i's model (i = -1: every learner) with [P] floats read from
+ * dev_src; also resets the one-iteration-old copy used when tau = 1
+ * (x^{-1} := x^0).  Asynchronous device-to-device copy.                        */
+int adpsgd_set_params(adpsgd_t h, int i, const float* dev_src);
+
+/* Device pointer to the gradient learner i used in the last step ([P] fp32;
+ * model mode only), borrowed.  NULL on a bad argument.                         */
+float* adpsgd_grads(adpsgd_t h, int i);
+
+/* Mean cross-entropy of every learner's last minibatch, host_out [L].
+ * Waits for the stream.                                                        */
+int adpsgd_losses(adpsgd_t h, float* host_out);
+
+/* Number of parameters P of one learner.                                       */
+int64_t adpsgd_param_count(adpsgd_t h);
+
+/* Number of tensors in the flat layout (model mode), and tensor idx's place in
+ * it: offset (floats), rows, cols.  EINVAL when idx is out of range.           */
+int adpsgd_layout_count(adpsgd_t h);
+int adpsgd_layout(adpsgd_t h, int idx, int64_t* offset, int64_t* rows, int64_t* cols);
+
+/* The schedule of iteration k, a pure function of (config, k): ring order,
+ * matching partner (partner[i] == i: none) and active flag of each learner.
+ * order, partner, active: host int32 [L] (any may be NULL).                    */
+int adpsgd_schedule(adpsgd_t h, int64_t k, int32_t* order, int32_t* partner, int32_t* active);
+
+/* Same without a handle.  mix is not needed: the matching does not depend on it. */
+int adpsgd_schedule_of(int32_t pattern, uint64_t seed, float straggler_p, int32_t L, int64_t k,
+                       int32_t* order, int32_t* partner, int32_t* active);
+
+/* Iterations done so far.                                                      */
+int64_t adpsgd_iteration(adpsgd_t h);
+
+/* Output model of Algorithm 1: dev_out[P] = (1/L) sum_i x_i (fp32 sum in
+ * learner order).  Asynchronous.                                               */
+int adpsgd_average(adpsgd_t h, float* dev_out);
+
+/* Release the handle (host memory only; the workspace stays the caller's).     */
+void adpsgd_destroy(adpsgd_t h);
+
+/* Text of the calling thread's last error ("" if none).                        */
+const char* adpsgd_last_error(void);
+
+/* ---- single kernels exposed for unit tests and micro-benchmarks ------------ */
+
+/* C[g] = A[g] * B[g]' (+ bias) on MFMA for g = 0..groups-1 (the GEMMs of the
+ * LSTM gradient).  Element type: fp32 (precision 0) or bf16 (precision 1) for A
+ * and B; C is fp32, or the element type when c_is_elem != 0.
+ *   a_kmajor != 0: A is [M][K] (row stride lda); else A is stored [K][M].
+ *   b_kmajor != 0: B is [N][K] (row stride ldb); else B is stored [K][N].
+ * bias (fp32 [N], or NULL) is added to every row.  Strides are in elements.
+ * All pointers: device.  M, N, K >= 1; lda, ldb and the group strides must be
+ * multiples of 4.                                                              */
+int adpsgd_gemm(int precision, int a_kmajor, int b_kmajor, int c_is_elem,
+                int M, int N, int K,
+                const void* A, int64_t lda, int64_t strideA,
+                const void* B, int64_t ldb, int64_t strideB,
+                void* C, int64_t ldc, int64_t strideC,
+                const float* bias, int64_t strideBias,
+                int groups, void* hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ADPSGD_H */

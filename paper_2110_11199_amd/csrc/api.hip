@@ -1,0 +1,556 @@
+// C ABI of the ADPSGD library: configuration checks, workspace carving, the
+// host-side integer schedule and the orchestration of one iteration.
+#include <cmath>
+#include <cstdio>
+#include <cstring>
+#include <string>
+#include <vector>
+#include "../../include/adpsgd.h"
+#include "kernels.hpp"
+
+using namespace adpsgd;
+
+namespace {
+
+thread_local std::string g_err;
+
+int fail(int code, const std::string& msg) { g_err = msg; return code; }
+int hipfail(hipError_t e, const char* what) {
+    g_err = std::string(what) + ": " + hipGetErrorString(e);
+    return ADPSGD_EHIP;
+}
+#define HIPCHK(call, what) do { hipError_t e_ = (call); if (e_ != hipSuccess) return hipfail(e_, what); } while (0)
+
+// ---- counter-based generator of the schedule -----------------------------------
+// u64(seed, stream, k, idx) = mix(mix(mix(seed + GOLDEN*(stream+1)) + k) + idx), mix = the
+// SplitMix64 output function.  Streams: 1 ring permutation, 2 straggler mask, 3 initial model.
+const uint64_t kGolden = 0x9E3779B97F4A7C15ull;
+enum { kStreamPerm = 1, kStreamMask = 2, kStreamInit = 3 };
+
+inline uint64_t mix64(uint64_t z) {
+    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+    z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+    return z ^ (z >> 31);
+}
+inline uint64_t draw(uint64_t seed, uint64_t stream, uint64_t k, uint64_t idx) {
+    return mix64(mix64(mix64(seed + kGolden * (stream + 1)) + k) + idx);
+}
+inline double draw01(uint64_t seed, uint64_t stream, uint64_t k, uint64_t idx) {
+    return (double)(draw(seed, stream, k, idx) >> 11) * (1.0 / 9007199254740992.0);
+}
+
+// Ring order (identity, or a Fisher-Yates shuffle per iteration for the random
+// ring, Section III-C), straggler mask, and the matching along the ring order
+// whose phase alternates with k on a fixed order.
+void make_schedule(int pattern, uint64_t seed, float straggler_p, int L, int64_t k,
+                   int32_t* order, int32_t* partner, int32_t* active) {
+    for (int i = 0; i < L; ++i) order[i] = i;
+    if (pattern == ADPSGD_RANDOM_RING) {
+        for (int p = L - 1; p >= 1; --p) {
+            const int q = (int)(draw(seed, kStreamPerm, (uint64_t)k, (uint64_t)p) % (uint64_t)(p + 1));
+            const int32_t tmp = order[p]; order[p] = order[q]; order[q] = tmp;
+        }
+    }
+    for (int i = 0; i < L; ++i) {
+        active[i] = 1;
+        if (straggler_p > 0.f && draw01(seed, kStreamMask, (uint64_t)k, (uint64_t)i) < (double)straggler_p) active[i] = 0;
+        partner[i] = i;
+    }
+    const int phase = pattern == ADPSGD_RANDOM_RING ? 0 : (int)(k & 1);
+    for (int m = 0; m < L / 2; ++m) {
+        const int a = order[(2 * m + phase) % L], b = order[(2 * m + 1 + phase) % L];
+        if (a != b) { partner[a] = b; partner[b] = a; }
+    }
+    for (int i = 0; i < L; ++i) {
+        if (!active[i]) { const int j = partner[i]; partner[j] = j; partner[i] = i; }
+    }
+}
+
+struct Tensor { int64_t off, rows, cols; };
+
+struct Carver {
+    char* base; size_t used;
+    explicit Carver(void* b) : base((char*)b), used(0) {}
+    void* take(size_t bytes) {
+        void* p = base ? base + used : nullptr;
+        used += (size_t)round_up((int64_t)bytes, 256);
+        return p;
+    }
+};
+
+}  // namespace
+
+struct adpsgd_handle {
+    adpsgd_config cfg;
+    hipStream_t stream;
+    int L, D, H, T, B, I, C, Bn, layers, F, ldx;
+    int mix, tau, prec, esz;
+    bool flat;
+    int64_t P, Ppad, M;
+    int64_t k;
+    int cur;                               // index of the buffer holding x^k
+    std::vector<Tensor> tensors;           // flat layout
+    std::vector<int> ix_wx, ix_wh, ix_b;   // tensor index per layer
+    int ix_wp, ix_bp, ix_wo, ix_bo;
+    // workspace regions
+    float* params[2];
+    float* grads;
+    bf16_t* shadow;
+    void* x0; int32_t* labels;
+    void* ybuf;        // [layers][L][M][D*H]
+    float* gates;      // [layers][L][M][D*4H]
+    float* cbuf;       // [layers][L][D][M][H]
+    void* z; void* dz; float* logits; void* dlogits; float* dy; void* da; float* dc;
+    float* row_loss; float* loss;
+};
+
+namespace {
+
+int check_config(const adpsgd_config* c, std::string& why) {
+    if (!c) { why = "config is NULL"; return ADPSGD_EINVAL; }
+    if (c->L < 1 || c->L > ADPSGD_MAX_LEARNERS) { why = "L must be in 1..128"; return ADPSGD_EINVAL; }
+    if (c->pattern < 0 || c->pattern > 2) { why = "unknown pattern"; return ADPSGD_EINVAL; }
+    if (c->mix != ADPSGD_MIX_DEFAULT && c->mix != ADPSGD_MIX_PAIR && c->mix != ADPSGD_MIX_ALL) { why = "unknown mix"; return ADPSGD_EINVAL; }
+    if (c->tau < -1 || c->tau > 1) { why = "tau must be 0, 1 or -1"; return ADPSGD_EINVAL; }
+    if (c->precision != ADPSGD_FP32 && c->precision != ADPSGD_BF16_GEMM) { why = "unknown precision"; return ADPSGD_EINVAL; }
+    if (!(c->straggler_p >= 0.f && c->straggler_p < 1.f)) { why = "straggler_p must be in [0,1)"; return ADPSGD_EINVAL; }
+    const int tau = c->tau >= 0 ? c->tau : (c->pattern == ADPSGD_D1D ? 1 : 0);
+    const int mix = c->mix != ADPSGD_MIX_DEFAULT ? c->mix : (c->pattern == ADPSGD_D1D ? ADPSGD_MIX_ALL : ADPSGD_MIX_PAIR);
+    if (c->straggler_p > 0.f && (c->pattern == ADPSGD_D1D || tau != 0 || mix != ADPSGD_MIX_PAIR)) {
+        why = "stragglers need a ring pattern with pairwise mixing and tau = 0 (delay-by-one waits for every learner)";
+        return ADPSGD_EINVAL;
+    }
+    if (!(c->init_scale >= 0.f)) { why = "init_scale must be >= 0"; return ADPSGD_EINVAL; }
+    const adpsgd_model_shape& s = c->shape;
+    if (s.flat_params > 0) return ADPSGD_OK;
+    if (s.flat_params < 0) { why = "flat_params < 0"; return ADPSGD_EINVAL; }
+    if (s.input_dim < 4 || s.hidden < 4 || s.classes < 4 || s.layers < 1 || s.batch < 1 || s.frames < 1 || s.bottleneck < 0) {
+        why = "model shape out of range"; return ADPSGD_EINVAL;
+    }
+    if (s.input_dim % 4 || s.hidden % 4 || s.classes % 4 || s.bottleneck % 4) {
+        why = "input_dim, hidden, bottleneck and classes must be multiples of 4"; return ADPSGD_EINVAL;
+    }
+    if (s.bidirectional != 0 && s.bidirectional != 1) { why = "bidirectional must be 0 or 1"; return ADPSGD_EINVAL; }
+    return ADPSGD_OK;
+}
+
+// Fills the derived fields and the layout; carves the workspace when base != NULL.
+size_t plan(adpsgd_handle* h, void* base) {
+    const adpsgd_config& c = h->cfg;
+    const adpsgd_model_shape& s = c.shape;
+    h->L = c.L;
+    h->tau = c.tau >= 0 ? c.tau : (c.pattern == ADPSGD_D1D ? 1 : 0);
+    h->mix = c.mix != ADPSGD_MIX_DEFAULT ? c.mix : (c.pattern == ADPSGD_D1D ? ADPSGD_MIX_ALL : ADPSGD_MIX_PAIR);
+    h->prec = c.precision; h->esz = c.precision ? 2 : 4;
+    h->flat = s.flat_params > 0;
+    h->tensors.clear(); h->ix_wx.clear(); h->ix_wh.clear(); h->ix_b.clear();
+    h->ix_wp = h->ix_bp = h->ix_wo = h->ix_bo = -1;
+    if (h->flat) {
+        h->P = s.flat_params;
+        h->D = h->H = h->T = h->B = h->I = h->C = h->Bn = h->layers = h->F = h->ldx = 0; h->M = 0;
+    } else {
+        h->D = s.bidirectional ? 2 : 1; h->H = s.hidden; h->T = s.frames; h->B = s.batch; h->I = s.input_dim;
+        h->C = s.classes; h->Bn = s.bottleneck; h->layers = s.layers; h->M = (int64_t)h->T * h->B;
+        h->ldx = (int)round_up(h->I, 8);
+        int64_t off = 0;
+        const int64_t G4 = (int64_t)h->D * 4 * h->H;
+        for (int l = 0; l < h->layers; ++l) {
+            const int64_t Il = l == 0 ? h->I : (int64_t)h->D * h->H;
+            h->ix_wx.push_back((int)h->tensors.size()); h->tensors.push_back({off, G4, Il}); off += G4 * Il;
+            h->ix_wh.push_back((int)h->tensors.size()); h->tensors.push_back({off, G4, h->H}); off += G4 * h->H;
+            h->ix_b.push_back((int)h->tensors.size()); h->tensors.push_back({off, 1, G4}); off += G4;
+        }
+        int64_t F = (int64_t)h->D * h->H;
+        if (h->Bn > 0) {
+            h->ix_wp = (int)h->tensors.size(); h->tensors.push_back({off, h->Bn, F}); off += h->Bn * F;
+            h->ix_bp = (int)h->tensors.size(); h->tensors.push_back({off, 1, h->Bn}); off += h->Bn;
+            F = h->Bn;
+        }
+        h->F = (int)F;
+        h->ix_wo = (int)h->tensors.size(); h->tensors.push_back({off, h->C, F}); off += h->C * F;
+        h->ix_bo = (int)h->tensors.size(); h->tensors.push_back({off, 1, h->C}); off += h->C;
+        h->P = off;
+    }
+    h->Ppad = round_up(h->P, 64);
+    Carver w(base);
+    const size_t L = (size_t)h->L;
+    h->params[0] = (float*)w.take(L * h->Ppad * 4);
+    h->params[1] = h->tau == 1 ? (float*)w.take(L * h->Ppad * 4) : h->params[0];
+    if (!h->flat) {
+        const size_t M = (size_t)h->M, DH = (size_t)h->D * h->H, G4 = DH * 4, e = (size_t)h->esz;
+        h->grads = (float*)w.take(L * h->Ppad * 4);
+        h->shadow = h->prec ? (bf16_t*)w.take(L * h->Ppad * 2) : nullptr;
+        h->x0 = w.take(L * M * h->ldx * e);
+        h->labels = (int32_t*)w.take(L * M * 4);
+        h->ybuf = w.take((size_t)h->layers * L * M * DH * e);
+        h->gates = (float*)w.take((size_t)h->layers * L * M * G4 * 4);
+        h->cbuf = (float*)w.take((size_t)h->layers * L * M * DH * 4);
+        h->z = h->Bn ? w.take(L * M * h->Bn * e) : nullptr;
+        h->dz = h->Bn ? w.take(L * M * h->Bn * e) : nullptr;
+        h->logits = (float*)w.take(L * M * h->C * 4);
+        h->dlogits = w.take(L * M * h->C * e);
+        h->dy = (float*)w.take(L * M * DH * 4);
+        h->da = w.take(L * M * G4 * e);
+        h->dc = (float*)w.take(L * (size_t)h->B * DH * 4);
+        h->row_loss = (float*)w.take(L * M * 4);
+        h->loss = (float*)w.take(L * 4);
+    }
+    return w.used;
+}
+
+int gemm(adpsgd_handle* h, const GemmDesc& d, const char* what) {
+    HIPCHK(launch_gemm(d, h->stream), what);
+    return ADPSGD_OK;
+}
+
+// Gradient of every learner's minibatch loss at the models in `at` (A1-A8).
+int compute_gradients(adpsgd_handle* h, const float* at, const void* const* batch_ptrs) {
+    const int L = h->L, D = h->D, H = h->H, T = h->T, B = h->B, prec = h->prec;
+    const int64_t M = h->M, DH = (int64_t)D * H, G4 = DH * 4, Pp = h->Ppad;
+    const int esz = h->esz;
+    hipStream_t s = h->stream;
+    // weights as GEMM operands: the fp32 models themselves, or their bf16 copy
+    const char* wbase = (const char*)at;
+    if (prec) {
+        HIPCHK(launch_cast_bf16(at, h->shadow, (int64_t)L * Pp, s), "cast weights to bf16");
+        wbase = (const char*)h->shadow;
+    }
+    auto W = [&](int ix) { return (const void*)(wbase + h->tensors[ix].off * esz); };
+    auto Bias = [&](int ix) { return at + h->tensors[ix].off; };
+    auto Gr = [&](int ix) { return h->grads + h->tensors[ix].off; };
+
+    StageDesc st;
+    st.L = L; st.precision = prec; st.rows = M; st.I = h->I; st.ldx = h->ldx;
+    st.x0 = h->x0; st.sX0 = M * h->ldx; st.y = h->labels; st.sY = M;
+    for (int i = 0; i < L; ++i) {
+        st.feats[i] = (const float*)batch_ptrs[2 * i];
+        st.labels[i] = (const int32_t*)batch_ptrs[2 * i + 1];
+    }
+    HIPCHK(launch_stage(st, s), "stage minibatches");
+
+    auto Y = [&](int l) { return (void*)((char*)h->ybuf + (size_t)l * L * M * DH * esz); };
+    auto Gates = [&](int l) { return h->gates + (size_t)l * L * M * G4; };
+    auto Cb = [&](int l) { return h->cbuf + (size_t)l * L * M * DH; };
+
+    GemmDesc g;
+    // ---- forward ----
+    for (int l = 0; l < h->layers; ++l) {
+        const int64_t Il = l == 0 ? h->I : DH;
+        g = GemmDesc{};
+        g.precision = prec; g.a_kc = 1; g.b_kc = 1; g.c_elem = 0;
+        g.M = (int)M; g.N = (int)G4; g.K = (int)Il;
+        g.A = l == 0 ? h->x0 : Y(l - 1); g.lda = l == 0 ? h->ldx : DH; g.sAi = M * g.lda;
+        g.B = W(h->ix_wx[l]); g.ldb = Il; g.sBi = Pp;
+        g.C = Gates(l); g.ldc = G4; g.sCi = M * G4;
+        g.bias = Bias(h->ix_b[l]); g.sBiasI = Pp;
+        g.groupsI = L; g.groupsD = 1;
+        if (int rc = gemm(h, g, "input projection GEMM")) return rc;
+        RecDesc r{};
+        r.precision = prec; r.L = L; r.D = D; r.B = B; r.H = H; r.T = T;
+        r.gates = Gates(l); r.sGi = M * G4;
+        r.c = Cb(l); r.sCi = M * DH;
+        r.y = Y(l); r.sYi = M * DH;
+        r.wh = W(h->ix_wh[l]); r.sWi = Pp; r.sWd = (int64_t)4 * H * H;
+        for (int t = 0; t < T; ++t) {
+            r.step = t;
+            HIPCHK(launch_rec_forward(r, s), "recurrent forward step");
+        }
+    }
+    const void* top = Y(h->layers - 1);
+    const void* zin = top; int64_t ldz = DH;
+    if (h->Bn) {
+        g = GemmDesc{};
+        g.precision = prec; g.a_kc = 1; g.b_kc = 1; g.c_elem = 1;
+        g.M = (int)M; g.N = h->Bn; g.K = (int)DH;
+        g.A = top; g.lda = DH; g.sAi = M * DH;
+        g.B = W(h->ix_wp); g.ldb = DH; g.sBi = Pp;
+        g.C = h->z; g.ldc = h->Bn; g.sCi = M * h->Bn;
+        g.bias = Bias(h->ix_bp); g.sBiasI = Pp;
+        g.groupsI = L; g.groupsD = 1;
+        if (int rc = gemm(h, g, "bottleneck GEMM")) return rc;
+        zin = h->z; ldz = h->Bn;
+    }
+    const int F = h->F, C = h->C;
+    g = GemmDesc{};
+    g.precision = prec; g.a_kc = 1; g.b_kc = 1; g.c_elem = 0;
+    g.M = (int)M; g.N = C; g.K = F;
+    g.A = zin; g.lda = ldz; g.sAi = M * ldz;
+    g.B = W(h->ix_wo); g.ldb = F; g.sBi = Pp;
+    g.C = h->logits; g.ldc = C; g.sCi = M * C;
+    g.bias = Bias(h->ix_bo); g.sBiasI = Pp;
+    g.groupsI = L; g.groupsD = 1;
+    if (int rc = gemm(h, g, "output GEMM")) return rc;
+
+    SoftmaxDesc sm{};
+    sm.precision = prec; sm.L = L; sm.rows = M; sm.C = C;
+    sm.logits = h->logits; sm.sLi = M * C; sm.y = h->labels; sm.sYi = M;
+    sm.dlogits = h->dlogits; sm.sDi = M * C; sm.row_loss = h->row_loss; sm.loss = h->loss;
+    HIPCHK(launch_softmax_ce(sm, s), "softmax cross-entropy");
+
+    // ---- backward: output layer(s) ----
+    // dW_o = dlogits' z
+    g = GemmDesc{};
+    g.precision = prec; g.a_kc = 0; g.b_kc = 0; g.c_elem = 0;
+    g.M = C; g.N = F; g.K = (int)M;
+    g.A = h->dlogits; g.lda = C; g.sAi = M * C;
+    g.B = zin; g.ldb = ldz; g.sBi = M * ldz;
+    g.C = Gr(h->ix_wo); g.ldc = F; g.sCi = Pp;
+    g.groupsI = L; g.groupsD = 1;
+    if (int rc = gemm(h, g, "dW_o GEMM")) return rc;
+    HIPCHK(launch_colsum(prec, h->dlogits, C, M * C, M, C, Gr(h->ix_bo), Pp, L, s), "db_o");
+    // d(z) = dlogits W_o
+    g = GemmDesc{};
+    g.precision = prec; g.a_kc = 1; g.b_kc = 0; g.c_elem = h->Bn ? 1 : 0;
+    g.M = (int)M; g.N = F; g.K = C;
+    g.A = h->dlogits; g.lda = C; g.sAi = M * C;
+    g.B = W(h->ix_wo); g.ldb = F; g.sBi = Pp;
+    g.C = h->Bn ? h->dz : (void*)h->dy; g.ldc = F; g.sCi = M * F;
+    g.groupsI = L; g.groupsD = 1;
+    if (int rc = gemm(h, g, "dz GEMM")) return rc;
+    if (h->Bn) {
+        g = GemmDesc{};
+        g.precision = prec; g.a_kc = 0; g.b_kc = 0; g.c_elem = 0;
+        g.M = h->Bn; g.N = (int)DH; g.K = (int)M;
+        g.A = h->dz; g.lda = h->Bn; g.sAi = M * h->Bn;
+        g.B = top; g.ldb = DH; g.sBi = M * DH;
+        g.C = Gr(h->ix_wp); g.ldc = DH; g.sCi = Pp;
+        g.groupsI = L; g.groupsD = 1;
+        if (int rc = gemm(h, g, "dW_p GEMM")) return rc;
+        HIPCHK(launch_colsum(prec, h->dz, h->Bn, M * h->Bn, M, h->Bn, Gr(h->ix_bp), Pp, L, s), "db_p");
+        g = GemmDesc{};
+        g.precision = prec; g.a_kc = 1; g.b_kc = 0; g.c_elem = 0;
+        g.M = (int)M; g.N = (int)DH; g.K = h->Bn;
+        g.A = h->dz; g.lda = h->Bn; g.sAi = M * h->Bn;
+        g.B = W(h->ix_wp); g.ldb = DH; g.sBi = Pp;
+        g.C = h->dy; g.ldc = DH; g.sCi = M * DH;
+        g.groupsI = L; g.groupsD = 1;
+        if (int rc = gemm(h, g, "dY GEMM")) return rc;
+    }
+    // ---- backward through the LSTM layers ----
+    for (int l = h->layers - 1; l >= 0; --l) {
+        const int64_t Il = l == 0 ? h->I : DH;
+        const void* in = l == 0 ? h->x0 : Y(l - 1);
+        const int64_t ldin = l == 0 ? h->ldx : DH;
+        RecDesc r{};
+        r.precision = prec; r.L = L; r.D = D; r.B = B; r.H = H; r.T = T;
+        r.gates = Gates(l); r.sGi = M * G4;
+        r.c = Cb(l); r.sCi = M * DH;
+        r.y = Y(l); r.sYi = M * DH;
+        r.wh = W(h->ix_wh[l]); r.sWi = Pp; r.sWd = (int64_t)4 * H * H;
+        r.dy = h->dy; r.sDYi = M * DH;
+        r.da = h->da; r.sDAi = M * G4;
+        r.dc = h->dc; r.sDCi = (int64_t)B * DH;
+        for (int t = 0; t < T; ++t) {
+            r.step = t;
+            HIPCHK(launch_rec_backward(r, s), "recurrent backward step");
+        }
+        // dW_x = da' x  (both directions at once: rows of W_x are [D][4H])
+        g = GemmDesc{};
+        g.precision = prec; g.a_kc = 0; g.b_kc = 0; g.c_elem = 0;
+        g.M = (int)G4; g.N = (int)Il; g.K = (int)M;
+        g.A = h->da; g.lda = G4; g.sAi = M * G4;
+        g.B = in; g.ldb = ldin; g.sBi = M * ldin;
+        g.C = Gr(h->ix_wx[l]); g.ldc = Il; g.sCi = Pp;
+        g.groupsI = L; g.groupsD = 1;
+        if (int rc = gemm(h, g, "dW_x GEMM")) return rc;
+        // dW_h[d] = da_d' h_{t'}: frames with a predecessor only (T-1 of them)
+        if (T > 1) {
+            g = GemmDesc{};
+            g.precision = prec; g.a_kc = 0; g.b_kc = 0; g.c_elem = 0;
+            g.M = 4 * H; g.N = H; g.K = (int)((int64_t)(T - 1) * B);
+            // d = 0: da rows of frames 1..T-1 against h of frames 0..T-2
+            // d = 1: da rows of frames 0..T-2 (columns 4H..) against h of frames 1..T-1 (columns H..)
+            g.A = (const char*)h->da + (size_t)B * G4 * esz; g.lda = G4; g.sAi = M * G4;
+            g.sAd = (int64_t)4 * H - (int64_t)B * G4;
+            g.B = Y(l); g.ldb = DH; g.sBi = M * DH; g.sBd = (int64_t)B * DH + H;
+            g.C = Gr(h->ix_wh[l]); g.ldc = H; g.sCi = Pp; g.sCd = (int64_t)4 * H * H;
+            g.groupsI = L; g.groupsD = D;
+            if (int rc = gemm(h, g, "dW_h GEMM")) return rc;
+        } else {
+            for (int i = 0; i < L; ++i)
+                HIPCHK(hipMemsetAsync(Gr(h->ix_wh[l]) + (size_t)i * Pp, 0, (size_t)G4 * H * 4, s), "zero dW_h");
+        }
+        HIPCHK(launch_colsum(prec, h->da, G4, M * G4, M, (int)G4, Gr(h->ix_b[l]), Pp, L, s), "db");
+        if (l > 0) {
+            // dY_{l-1} = da W_x  (sum over both directions: K = D*4H)
+            g = GemmDesc{};
+            g.precision = prec; g.a_kc = 1; g.b_kc = 0; g.c_elem = 0;
+            g.M = (int)M; g.N = (int)DH; g.K = (int)G4;
+            g.A = h->da; g.lda = G4; g.sAi = M * G4;
+            g.B = W(h->ix_wx[l]); g.ldb = DH; g.sBi = Pp;
+            g.C = h->dy; g.ldc = DH; g.sCi = M * DH;
+            g.groupsI = L; g.groupsD = 1;
+            if (int rc = gemm(h, g, "dX GEMM")) return rc;
+        }
+    }
+    return ADPSGD_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int adpsgd_workspace_bytes(const adpsgd_config* cfg, size_t* out) {
+    std::string why;
+    if (int rc = check_config(cfg, why)) return fail(rc, why);
+    if (!out) return fail(ADPSGD_EINVAL, "out is NULL");
+    adpsgd_handle tmp{};
+    tmp.cfg = *cfg;
+    *out = plan(&tmp, nullptr);
+    return ADPSGD_OK;
+}
+
+int adpsgd_create(const adpsgd_config* cfg, void* dev_workspace, size_t bytes, void* hip_stream, adpsgd_t* out) {
+    std::string why;
+    if (int rc = check_config(cfg, why)) return fail(rc, why);
+    if (!out) return fail(ADPSGD_EINVAL, "out is NULL");
+    if (!dev_workspace || ((uintptr_t)dev_workspace % 256) != 0) return fail(ADPSGD_ENOMEM, "workspace is NULL or not 256-byte aligned");
+    adpsgd_handle* h = new adpsgd_handle{};
+    h->cfg = *cfg;
+    h->stream = (hipStream_t)hip_stream;
+    const size_t need = plan(h, dev_workspace);
+    if (bytes < need) {
+        delete h;
+        return fail(ADPSGD_ENOMEM, "workspace too small: need " + std::to_string(need) + " bytes");
+    }
+    h->k = 0; h->cur = 0;
+    hipStream_t s = h->stream;
+    const size_t slab = (size_t)h->L * h->Ppad * 4;
+    hipError_t e = hipMemsetAsync(h->params[0], 0, slab, s);
+    if (e == hipSuccess && h->tau == 1) e = hipMemsetAsync(h->params[1], 0, slab, s);
+    if (e == hipSuccess && !h->flat) e = hipMemsetAsync(h->grads, 0, slab, s);
+    if (e != hipSuccess) { delete h; return hipfail(e, "clear models"); }
+    if (cfg->init_scale > 0.f) {
+        // same w_0 on every learner (Algorithm 1, input)
+        std::vector<float> w0((size_t)h->P);
+        const double a = (double)cfg->init_scale;
+        for (int64_t i = 0; i < h->P; ++i)
+            w0[(size_t)i] = (float)((2.0 * draw01(cfg->seed, kStreamInit, 0, (uint64_t)i) - 1.0) * a);
+        for (int b = 0; b <= h->tau && e == hipSuccess; ++b)
+            for (int i = 0; i < h->L && e == hipSuccess; ++i)
+                e = hipMemcpyAsync(h->params[b] + (size_t)i * h->Ppad, w0.data(), (size_t)h->P * 4, hipMemcpyHostToDevice, s);
+        if (e == hipSuccess) e = hipStreamSynchronize(s);
+        if (e != hipSuccess) { delete h; return hipfail(e, "initial model upload"); }
+    } else {
+        e = hipStreamSynchronize(s);
+        if (e != hipSuccess) { delete h; return hipfail(e, "stream sync"); }
+    }
+    *out = h;
+    return ADPSGD_OK;
+}
+
+int adpsgd_step(adpsgd_t h, const void* const* batch_ptrs, float lr) {
+    if (!h || !batch_ptrs) return fail(ADPSGD_EINVAL, "NULL argument");
+    const int L = h->L;
+    int32_t order[ADPSGD_MAX_LEARNERS], partner[ADPSGD_MAX_LEARNERS], active[ADPSGD_MAX_LEARNERS];
+    make_schedule(h->cfg.pattern, h->cfg.seed, h->cfg.straggler_p, L, h->k, order, partner, active);
+    const int nptr = h->flat ? L : 2 * L;
+    for (int i = 0; i < nptr; ++i) {
+        const int li = h->flat ? i : i / 2;
+        if (!batch_ptrs[i] && (active[li] || !h->flat)) return fail(ADPSGD_EINVAL, "batch_ptrs[" + std::to_string(i) + "] is NULL");
+    }
+    float* xk = h->params[h->cur];
+    float* xnext = h->tau == 1 ? h->params[1 - h->cur] : xk;
+    UpdateDesc u{};
+    u.L = L; u.mix = h->mix; u.P = h->P; u.src = xk; u.dst = xnext; u.stride = h->Ppad; u.lr = lr;
+    if (h->flat) {
+        for (int i = 0; i < L; ++i) u.g[i] = (const float*)batch_ptrs[i];
+    } else {
+        // the gradient is evaluated at x^{k-tau}: the other buffer holds x^{k-1}
+        const float* at = h->tau == 1 ? h->params[1 - h->cur] : xk;
+        if (int rc = compute_gradients(h, at, batch_ptrs)) return rc;
+        for (int i = 0; i < L; ++i) u.g[i] = h->grads + (size_t)i * h->Ppad;
+    }
+    for (int i = 0; i < L; ++i) { u.partner[i] = (int16_t)partner[i]; u.active[i] = (int16_t)active[i]; }
+    HIPCHK(launch_update(u, h->stream), "mix + update");
+    if (h->tau == 1) h->cur = 1 - h->cur;
+    h->k += 1;
+    return ADPSGD_OK;
+}
+
+float* adpsgd_params(adpsgd_t h, int i) {
+    if (!h || i < 0 || i >= h->L) { g_err = "bad learner index"; return nullptr; }
+    return h->params[h->cur] + (size_t)i * h->Ppad;
+}
+
+int adpsgd_set_params(adpsgd_t h, int i, const float* dev_src) {
+    if (!h || !dev_src || i < -1 || i >= h->L) return fail(ADPSGD_EINVAL, "bad argument");
+    const int lo = i < 0 ? 0 : i, hi = i < 0 ? h->L : i + 1;
+    for (int b = 0; b <= h->tau; ++b)
+        for (int j = lo; j < hi; ++j)
+            HIPCHK(hipMemcpyAsync(h->params[b] + (size_t)j * h->Ppad, dev_src, (size_t)h->P * 4, hipMemcpyDeviceToDevice, h->stream), "set_params copy");
+    return ADPSGD_OK;
+}
+
+float* adpsgd_grads(adpsgd_t h, int i) {
+    if (!h || h->flat || i < 0 || i >= h->L) { g_err = "bad argument"; return nullptr; }
+    return h->grads + (size_t)i * h->Ppad;
+}
+
+int adpsgd_losses(adpsgd_t h, float* host_out) {
+    if (!h || !host_out || h->flat) return fail(ADPSGD_EINVAL, "bad argument");
+    HIPCHK(hipMemcpyAsync(host_out, h->loss, (size_t)h->L * 4, hipMemcpyDeviceToHost, h->stream), "loss copy");
+    HIPCHK(hipStreamSynchronize(h->stream), "stream sync");
+    return ADPSGD_OK;
+}
+
+int64_t adpsgd_param_count(adpsgd_t h) { return h ? h->P : -1; }
+
+int adpsgd_layout_count(adpsgd_t h) { return h ? (int)h->tensors.size() : -1; }
+
+int adpsgd_layout(adpsgd_t h, int idx, int64_t* offset, int64_t* rows, int64_t* cols) {
+    if (!h || idx < 0 || idx >= (int)h->tensors.size()) return fail(ADPSGD_EINVAL, "tensor index out of range");
+    if (offset) *offset = h->tensors[idx].off;
+    if (rows) *rows = h->tensors[idx].rows;
+    if (cols) *cols = h->tensors[idx].cols;
+    return ADPSGD_OK;
+}
+
+int adpsgd_schedule_of(int32_t pattern, uint64_t seed, float straggler_p, int32_t L, int64_t k,
+                       int32_t* order, int32_t* partner, int32_t* active) {
+    if (L < 1 || L > ADPSGD_MAX_LEARNERS || pattern < 0 || pattern > 2 || k < 0) return fail(ADPSGD_EINVAL, "bad argument");
+    int32_t o[ADPSGD_MAX_LEARNERS], p[ADPSGD_MAX_LEARNERS], a[ADPSGD_MAX_LEARNERS];
+    make_schedule(pattern, seed, straggler_p, L, k, o, p, a);
+    if (order) memcpy(order, o, (size_t)L * 4);
+    if (partner) memcpy(partner, p, (size_t)L * 4);
+    if (active) memcpy(active, a, (size_t)L * 4);
+    return ADPSGD_OK;
+}
+
+int adpsgd_schedule(adpsgd_t h, int64_t k, int32_t* order, int32_t* partner, int32_t* active) {
+    if (!h) return fail(ADPSGD_EINVAL, "NULL handle");
+    return adpsgd_schedule_of(h->cfg.pattern, h->cfg.seed, h->cfg.straggler_p, h->L, k, order, partner, active);
+}
+
+int64_t adpsgd_iteration(adpsgd_t h) { return h ? h->k : -1; }
+
+int adpsgd_average(adpsgd_t h, float* dev_out) {
+    if (!h || !dev_out) return fail(ADPSGD_EINVAL, "NULL argument");
+    HIPCHK(launch_average(h->params[h->cur], h->Ppad, h->L, h->P, dev_out, h->stream), "average");
+    return ADPSGD_OK;
+}
+
+void adpsgd_destroy(adpsgd_t h) { delete h; }
+
+const char* adpsgd_last_error(void) { return g_err.c_str(); }
+
+int adpsgd_gemm(int precision, int a_kmajor, int b_kmajor, int c_is_elem, int M, int N, int K,
+                const void* A, int64_t lda, int64_t strideA, const void* B, int64_t ldb, int64_t strideB,
+                void* C, int64_t ldc, int64_t strideC, const float* bias, int64_t strideBias,
+                int groups, void* hip_stream) {
+    if (!A || !B || !C || (precision != 0 && precision != 1)) return fail(ADPSGD_EINVAL, "bad argument");
+    GemmDesc g{};
+    g.precision = precision; g.a_kc = a_kmajor != 0; g.b_kc = b_kmajor != 0; g.c_elem = c_is_elem != 0;
+    g.M = M; g.N = N; g.K = K;
+    g.A = A; g.lda = lda; g.sAi = strideA;
+    g.B = B; g.ldb = ldb; g.sBi = strideB;
+    g.C = C; g.ldc = ldc; g.sCi = strideC;
+    g.bias = bias; g.sBiasI = strideBias;
+    g.groupsI = groups; g.groupsD = 1;
+    hipError_t e = launch_gemm(g, (hipStream_t)hip_stream);
+    if (e == hipErrorInvalidValue) return fail(ADPSGD_EINVAL, "GEMM operands violate the size/alignment rules");
+    if (e != hipSuccess) return hipfail(e, "gemm launch");
+    return ADPSGD_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,37 @@
+// Shared device/host helpers of the ADPSGD library (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace adpsgd {
+
+typedef uint16_t bf16_t;   // raw bfloat16 bits
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
+typedef __attribute__((ext_vector_type(16))) float f32x16_t;
+
+// fp32 -> bf16, round to nearest even (the bfloat16 format rule); NaN stays NaN.
+__host__ __device__ inline bf16_t f32_to_bf16(float f) {
+    uint32_t u = __builtin_bit_cast(uint32_t, f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (bf16_t)((u >> 16) | 0x40);
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (bf16_t)(u >> 16);
+}
+__host__ __device__ inline float bf16_to_f32(bf16_t h) {
+    return __builtin_bit_cast(float, (uint32_t)h << 16);
+}
+
+template <typename T> struct Elem;
+template <> struct Elem<float> {
+    __device__ static float from(float v) { return v; }
+    __device__ static float to(float v) { return v; }
+};
+template <> struct Elem<bf16_t> {
+    __device__ static bf16_t from(float v) { return f32_to_bf16(v); }
+    __device__ static float to(bf16_t v) { return bf16_to_f32(v); }
+};
+
+__device__ inline float sigmoidf_(float a) { return 1.0f / (1.0f + expf(-a)); }
+
+inline int64_t round_up(int64_t v, int64_t m) { return (v + m - 1) / m * m; }
+
+}  // namespace adpsgd

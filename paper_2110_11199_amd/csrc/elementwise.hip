@@ -1,0 +1,165 @@
+// Bandwidth-bound helper kernels of the LSTM gradient: staging/casting of the
+// minibatch and of the bf16 weight copy, softmax cross-entropy with its
+// gradient, and the column sums that give the bias gradients.
+#include "kernels.hpp"
+
+namespace adpsgd {
+
+struct StageArgs {
+    int64_t rows; int I, ldx;
+    void* x0; int64_t sX0; int32_t* y; int64_t sY;
+    const float* feats[128];
+    const int32_t* labels[128];
+};
+
+template <typename T>
+__global__ __launch_bounds__(256) void stage_kernel(StageArgs p) {
+    const int li = blockIdx.y;
+    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const int64_t n = p.rows * p.ldx;
+    if (idx < n) {
+        const int64_t r = idx / p.ldx;
+        const int c = (int)(idx % p.ldx);
+        const float v = c < p.I ? p.feats[li][r * p.I + c] : 0.f;
+        ((T*)p.x0)[li * p.sX0 + idx] = Elem<T>::from(v);
+    }
+    if (idx < p.rows) p.y[li * p.sY + idx] = p.labels[li][idx];
+}
+
+hipError_t launch_stage(const StageDesc& d, hipStream_t s) {
+    StageArgs a;
+    a.rows = d.rows; a.I = d.I; a.ldx = d.ldx; a.x0 = d.x0; a.sX0 = d.sX0; a.y = d.y; a.sY = d.sY;
+    for (int i = 0; i < 128; ++i) { a.feats[i] = i < d.L ? d.feats[i] : nullptr; a.labels[i] = i < d.L ? d.labels[i] : nullptr; }
+    dim3 grid((unsigned)((d.rows * d.ldx + 255) / 256), (unsigned)d.L);
+    if (d.precision == 0) hipLaunchKernelGGL(stage_kernel<float>, grid, dim3(256), 0, s, a);
+    else hipLaunchKernelGGL(stage_kernel<bf16_t>, grid, dim3(256), 0, s, a);
+    return hipGetLastError();
+}
+
+// n must be a multiple of 4 and both pointers 16-byte / 8-byte aligned.
+__global__ __launch_bounds__(256) void cast_bf16_kernel(const float4* src, uint2* dst, int64_t n4) {
+    int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const int64_t stride = (int64_t)gridDim.x * 256;
+    for (; i < n4; i += stride) {
+        const float4 v = src[i];
+        uint2 o;
+        o.x = (uint32_t)f32_to_bf16(v.x) | ((uint32_t)f32_to_bf16(v.y) << 16);
+        o.y = (uint32_t)f32_to_bf16(v.z) | ((uint32_t)f32_to_bf16(v.w) << 16);
+        dst[i] = o;
+    }
+}
+
+hipError_t launch_cast_bf16(const float* src, bf16_t* dst, int64_t n, hipStream_t s) {
+    if (n % 4 != 0 || (uintptr_t)src % 16 != 0 || (uintptr_t)dst % 8 != 0) return hipErrorInvalidValue;
+    const int64_t n4 = n / 4;
+    int64_t blocks = (n4 + 255) / 256;
+    if (blocks > 256 * 32) blocks = 256 * 32;
+    hipLaunchKernelGGL(cast_bf16_kernel, dim3((unsigned)blocks), dim3(256), 0, s, (const float4*)src, (uint2*)dst, n4);
+    return hipGetLastError();
+}
+
+// ---- softmax cross-entropy ---------------------------------------------------
+// One workgroup per frame (row of logits).  loss_row = -(z_y - max - log sum exp(z - max));
+// dlogits = (softmax - onehot) / rows   (mean over the B*T frames of the minibatch).
+__device__ inline void lse_merge_(float& m, float& s, float m2, float s2) {
+    const float mm = fmaxf(m, m2);
+    s = s * expf(m - mm) + s2 * expf(m2 - mm);
+    m = mm;
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void softmax_ce_kernel(SoftmaxDesc p) {
+    const int li = blockIdx.y;
+    const int64_t row = blockIdx.x;
+    const float* z = p.logits + li * p.sLi + row * p.C;
+    T* dz = (T*)p.dlogits + li * p.sDi + row * p.C;
+    int y = p.y[li * p.sYi + row];
+    y = y < 0 ? 0 : (y >= p.C ? p.C - 1 : y);      // labels outside [0, C) are clamped, never dereferenced
+    float m = -INFINITY, s = 0.f;
+    for (int c = threadIdx.x; c < p.C; c += 256) {
+        const float v = z[c];
+        if (v > m) { s = s * expf(m - v) + 1.f; m = v; }
+        else s += expf(v - m);
+    }
+    // wave reduction, then across the 4 waves through LDS
+    for (int off = 32; off > 0; off >>= 1) {
+        const float m2 = __shfl_xor(m, off), s2 = __shfl_xor(s, off);
+        if (m2 > -INFINITY || m > -INFINITY) lse_merge_(m, s, m2, s2);
+    }
+    __shared__ float sm[4], ss[4];
+    if ((threadIdx.x & 63) == 0) { sm[threadIdx.x >> 6] = m; ss[threadIdx.x >> 6] = s; }
+    __syncthreads();
+    m = sm[0]; s = ss[0];
+    for (int w = 1; w < 4; ++w) lse_merge_(m, s, sm[w], ss[w]);
+    const float inv = 1.f / s;
+    const float scale = 1.f / (float)p.rows;
+    for (int c = threadIdx.x; c < p.C; c += 256) {
+        float pr = expf(z[c] - m) * inv;
+        if (c == y) pr -= 1.f;
+        dz[c] = Elem<T>::from(pr * scale);
+    }
+    if (threadIdx.x == 0) p.row_loss[li * p.rows + row] = -((z[y] - m) - logf(s));
+}
+
+__global__ __launch_bounds__(256) void loss_reduce_kernel(const float* row_loss, int64_t rows, float* loss) {
+    const int li = blockIdx.x;
+    float s = 0.f;
+    for (int64_t r = threadIdx.x; r < rows; r += 256) s += row_loss[li * rows + r];
+    __shared__ float sh[256];
+    sh[threadIdx.x] = s;
+    __syncthreads();
+    for (int off = 128; off > 0; off >>= 1) {
+        if ((int)threadIdx.x < off) sh[threadIdx.x] += sh[threadIdx.x + off];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) loss[li] = sh[0] / (float)rows;
+}
+
+hipError_t launch_softmax_ce(const SoftmaxDesc& d, hipStream_t s) {
+    dim3 grid((unsigned)d.rows, (unsigned)d.L);
+    if (d.precision == 0) hipLaunchKernelGGL(softmax_ce_kernel<float>, grid, dim3(256), 0, s, d);
+    else hipLaunchKernelGGL(softmax_ce_kernel<bf16_t>, grid, dim3(256), 0, s, d);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(loss_reduce_kernel, dim3((unsigned)d.L), dim3(256), 0, s, d.row_loss, d.rows, d.loss);
+    return hipGetLastError();
+}
+
+// ---- column sums -----------------------------------------------------------------
+// Workgroup = 64 columns x 4 row slices; fixed summation order (deterministic).
+template <typename T>
+__global__ __launch_bounds__(256) void colsum_kernel(const T* in, int64_t ld, int64_t sIi, int64_t rows, int N,
+                                                     float* out, int64_t sOi) {
+    const int li = blockIdx.y;
+    const int col = blockIdx.x * 64 + (threadIdx.x & 63);
+    const int slice = threadIdx.x >> 6;
+    const T* src = in + li * sIi;
+    float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
+    if (col < N) {
+        int64_t r = slice;
+        for (; r + 12 < rows; r += 16) {
+            s0 += Elem<T>::to(src[r * ld + col]);
+            s1 += Elem<T>::to(src[(r + 4) * ld + col]);
+            s2 += Elem<T>::to(src[(r + 8) * ld + col]);
+            s3 += Elem<T>::to(src[(r + 12) * ld + col]);
+        }
+        for (; r < rows; r += 4) s0 += Elem<T>::to(src[r * ld + col]);
+    }
+    __shared__ float sh[4][64];
+    sh[slice][threadIdx.x & 63] = (s0 + s1) + (s2 + s3);
+    __syncthreads();
+    if (slice == 0 && col < N)
+        out[li * sOi + col] = (sh[0][threadIdx.x] + sh[1][threadIdx.x]) + (sh[2][threadIdx.x] + sh[3][threadIdx.x]);
+}
+
+hipError_t launch_colsum(int precision, const void* in, int64_t ld, int64_t sIi, int64_t rows, int N,
+                         float* out, int64_t sOi, int L, hipStream_t s) {
+    dim3 grid((unsigned)((N + 63) / 64), (unsigned)L);
+    if (precision == 0)
+        hipLaunchKernelGGL(colsum_kernel<float>, grid, dim3(256), 0, s, (const float*)in, ld, sIi, rows, N, out, sOi);
+    else
+        hipLaunchKernelGGL(colsum_kernel<bf16_t>, grid, dim3(256), 0, s, (const bf16_t*)in, ld, sIi, rows, N, out, sOi);
+    return hipGetLastError();
+}
+
+}  // namespace adpsgd

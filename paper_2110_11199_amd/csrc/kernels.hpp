@@ -1,0 +1,86 @@
+// Host-side launch interface of the HIP kernels (internal to the library).
+#pragma once
+#include "common.hpp"
+
+namespace adpsgd {
+
+// ---- grouped GEMM  C[z] = A[z] * B[z]' (+ bias) ------------------------------
+// Group z = i*groupsD + d; operand X of group z starts at X + i*sXi + d*sXd
+// (strides in elements).
+struct GemmDesc {
+    int precision;            // 0 fp32 operands, 1 bf16 operands
+    int a_kc, b_kc;           // operand stored K-contiguous ([rows][K]) or not ([K][rows])
+    int c_elem;               // C stored in the operand type instead of fp32
+    int M, N, K;
+    const void* A; int64_t lda, sAi, sAd;
+    const void* B; int64_t ldb, sBi, sBd;
+    void* C; int64_t ldc, sCi, sCd;
+    const float* bias; int64_t sBiasI, sBiasD;
+    int groupsI, groupsD;
+};
+// Returns hipSuccess, or hipErrorInvalidValue when the operands do not meet the
+// alignment rules (rows and strides multiples of 4 elements).
+hipError_t launch_gemm(const GemmDesc& d, hipStream_t s);
+
+// ---- fused mixing + SGD update ------------------------------------------------
+struct UpdateDesc {
+    int L;
+    int mix;                   // 0 pair, 2 all
+    int64_t P;                 // elements per learner
+    const float* src;          // x^k, learner i at src + i*stride
+    float* dst;                // x^{k+1}, learner i at dst + i*stride (may equal src)
+    int64_t stride;
+    const float* g[128];       // gradient of learner i
+    int16_t partner[128];
+    int16_t active[128];
+    float lr;
+};
+hipError_t launch_update(const UpdateDesc& d, hipStream_t s);
+hipError_t launch_average(const float* x, int64_t stride, int L, int64_t P, float* out, hipStream_t s);
+
+// ---- LSTM gradient pieces -------------------------------------------------------
+struct StageDesc {             // copy / cast the minibatches into the workspace
+    int L, precision;
+    int64_t rows;              // T*B
+    int I, ldx;                // feature dim and padded row stride of the staged copy
+    const float* feats[128];
+    const int32_t* labels[128];
+    void* x0; int64_t sX0;     // [L][rows][ldx] operand type
+    int32_t* y; int64_t sY;    // [L][rows]
+};
+hipError_t launch_stage(const StageDesc& d, hipStream_t s);
+hipError_t launch_cast_bf16(const float* src, bf16_t* dst, int64_t n, hipStream_t s);
+
+struct RecDesc {               // one time step of one layer, all learners and directions
+    int precision;
+    int L, D, B, H, T;
+    int step;                  // processing step 0..T-1 (frame = step, or T-1-step for d = 1)
+    // forward: gates buffer holds W_x x + b on entry, the activated gates on exit
+    float* gates; int64_t sGi;           // [L][T*B][D*4H] fp32
+    float* c; int64_t sCi;               // [L][D][T*B][H] fp32
+    void* y; int64_t sYi;                // [L][T*B][D*H] operand type (layer output)
+    const void* wh; int64_t sWi, sWd;    // W_h [D][4H][H] operand type, learner stride
+    // backward only
+    const float* dy; int64_t sDYi;       // [L][T*B][D*H] fp32, gradient w.r.t. the layer output
+    void* da; int64_t sDAi;              // [L][T*B][D*4H] operand type, gate pre-activation grads
+    float* dc; int64_t sDCi;             // [L][D][B][H] fp32 running dL/dc
+};
+hipError_t launch_rec_forward(const RecDesc& d, hipStream_t s);
+hipError_t launch_rec_backward(const RecDesc& d, hipStream_t s);
+
+struct SoftmaxDesc {
+    int precision, L;
+    int64_t rows; int C;
+    const float* logits; int64_t sLi;    // [L][rows][C]
+    const int32_t* y; int64_t sYi;
+    void* dlogits; int64_t sDi;          // [L][rows][C] operand type: (softmax - onehot)/rows
+    float* row_loss;                     // [L][rows]
+    float* loss;                         // [L]
+};
+hipError_t launch_softmax_ce(const SoftmaxDesc& d, hipStream_t s);
+
+// out[z][n] = sum_m in[z][m][n]   (bias gradients)
+hipError_t launch_colsum(int precision, const void* in, int64_t ld, int64_t sIi, int64_t rows, int N,
+                         float* out, int64_t sOi, int L, hipStream_t s);
+
+}  // namespace adpsgd

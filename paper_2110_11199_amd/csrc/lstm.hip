@@ -1,0 +1,187 @@
+// Per-time-step LSTM kernels: the recurrent GEMM h_{t'} W_h' on MFMA with the
+// gate non-linearities and the cell update fused into its epilogue (forward),
+// and the recurrent gradient GEMM da W_h with the cell backward fused into its
+// epilogue (backward through time).  One launch advances every learner and both
+// directions of one layer by one frame.
+//
+// LSTM cell (vanilla, gate blocks i,f,g,o):
+//   a = W_x x_t + b + W_h h_{t'}          i,f,o = sigmoid(a), g = tanh(a)
+//   c_t = f c_{t'} + i g                  h_t = o tanh(c_t)
+// with t' the previously processed frame (t-1 forward, t+1 backward direction)
+// and h = c = 0 before the first processed frame of a segment.
+#include "gemm_core.hpp"
+#include "kernels.hpp"
+
+namespace adpsgd {
+
+template <typename T, int WM, int WN, int VB>
+__global__ __launch_bounds__(256) void rec_forward_kernel(RecDesc p) {
+    typedef GemmCore<T, KcSrc<T>, GateSrc<T>, WM, WN, 1, 4, VB> Core;
+    __shared__ __attribute__((aligned(16))) char lds[Core::LDS_BYTES];
+    const int D = p.D, H = p.H, B = p.B;
+    const int li = blockIdx.y / D, d = blockIdx.y % D;
+    const int t = d == 0 ? p.step : p.T - 1 - p.step;
+    const int tp = d == 0 ? t - 1 : t + 1;
+    const int u0 = blockIdx.x * (32 * WN), b0 = blockIdx.z * (32 * WM);
+    const int64_t DH = (int64_t)D * H, G4 = (int64_t)D * 4 * H;
+
+    f32x16_t acc[1][4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) acc[0][j][e] = 0.f;
+
+    if (p.step > 0) {
+        KcSrc<T> a;
+        a.base = (const T*)p.y + li * p.sYi + ((int64_t)tp * B + b0) * DH + (int64_t)d * H;
+        a.ld = DH; a.R = B - b0;
+        GateSrc<T> b;
+        b.base = (const T*)p.wh + li * p.sWi + d * p.sWd;
+        b.ld = H; b.H = H; b.u0 = u0;
+        Core::run(acc, a, b, H, lds);
+    }
+
+    // tile column n = 128*wave_n + 32*gate + j holds gate `gate` of unit u0 + 32*wave_n + j
+    const int n0c = Core::acc_col(0);
+    const int u = u0 + 32 * (n0c >> 7) + (n0c & 31);
+    if (u >= H) return;
+    float* gates = p.gates + li * p.sGi;
+    float* cbuf = p.c + li * p.sCi + (int64_t)d * p.T * B * H;
+    T* y = (T*)p.y + li * p.sYi;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+        const int row = b0 + Core::acc_row(0, i);
+        if (row >= B) continue;
+        float* gp = gates + ((int64_t)t * B + row) * G4 + (int64_t)d * 4 * H + u;
+        const float ai = gp[0] + acc[0][0][i];
+        const float af = gp[H] + acc[0][1][i];
+        const float ag = gp[2 * (int64_t)H] + acc[0][2][i];
+        const float ao = gp[3 * (int64_t)H] + acc[0][3][i];
+        const float c_prev = p.step > 0 ? cbuf[((int64_t)tp * B + row) * H + u] : 0.f;
+        const float ig = sigmoidf_(ai), fg = sigmoidf_(af), gg = tanhf(ag), og = sigmoidf_(ao);
+        const float cc = fg * c_prev + ig * gg;
+        const float hh = og * tanhf(cc);
+        gp[0] = ig; gp[H] = fg; gp[2 * (int64_t)H] = gg; gp[3 * (int64_t)H] = og;
+        cbuf[((int64_t)t * B + row) * H + u] = cc;
+        y[((int64_t)t * B + row) * DH + (int64_t)d * H + u] = Elem<T>::from(hh);
+    }
+}
+
+// Backward through one frame: dh_t = dY_t + da_{t''} W_h (t'' = the frame
+// processed just before in backward order), then
+//   do = dh tanh(c_t)            dc = dc_rec + dh o (1 - tanh^2 c_t)
+//   di = dc g, dg = dc i, df = dc c_{t'}, dc_rec <- dc f
+//   da = (di i(1-i), df f(1-f), dg (1-g^2), do o(1-o))
+template <typename T, int WM, int WN, int FN, int VB>
+__global__ __launch_bounds__(256) void rec_backward_kernel(RecDesc p) {
+    typedef GemmCore<T, KcSrc<T>, McSrc<T>, WM, WN, 1, FN, VB> Core;
+    __shared__ __attribute__((aligned(16))) char lds[Core::LDS_BYTES];
+    const int D = p.D, H = p.H, B = p.B;
+    const int li = blockIdx.y / D, d = blockIdx.y % D;
+    const int t = d == 0 ? p.T - 1 - p.step : p.step;     // reverse of the forward processing order
+    const int tn = d == 0 ? t + 1 : t - 1;                 // frame handled by the previous launch
+    const int tp = d == 0 ? t - 1 : t + 1;                 // frame the forward pass processed before t
+    const bool has_prev = tp >= 0 && tp < p.T;
+    const int u0 = blockIdx.x * Core::BN, b0 = blockIdx.z * Core::BM;
+    const int64_t DH = (int64_t)D * H, G4 = (int64_t)D * 4 * H;
+
+    f32x16_t acc[1][FN];
+#pragma unroll
+    for (int j = 0; j < FN; ++j)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) acc[0][j][e] = 0.f;
+
+    if (p.step > 0) {
+        KcSrc<T> a;
+        a.base = (const T*)p.da + li * p.sDAi + ((int64_t)tn * B + b0) * G4 + (int64_t)d * 4 * H;
+        a.ld = G4; a.R = B - b0;
+        McSrc<T> b;
+        b.base = (const T*)p.wh + li * p.sWi + d * p.sWd + u0;
+        b.ld = H; b.R = H - u0;
+        Core::run(acc, a, b, 4 * H, lds);
+    }
+
+    const float* gates = p.gates + li * p.sGi;
+    const float* cbuf = p.c + li * p.sCi + (int64_t)d * p.T * B * H;
+    const float* dy = p.dy + li * p.sDYi;
+    float* dcb = p.dc + li * p.sDCi + (int64_t)d * B * H;
+    T* da = (T*)p.da + li * p.sDAi;
+#pragma unroll
+    for (int fn = 0; fn < FN; ++fn) {
+        const int u = u0 + Core::acc_col(fn);
+        if (u >= H) continue;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            const int row = b0 + Core::acc_row(0, i);
+            if (row >= B) continue;
+            const int64_t m = (int64_t)t * B + row;
+            const float dh = dy[m * DH + (int64_t)d * H + u] + acc[0][fn][i];
+            const float* gp = gates + m * G4 + (int64_t)d * 4 * H + u;
+            const float ig = gp[0], fg = gp[H], gg = gp[2 * (int64_t)H], og = gp[3 * (int64_t)H];
+            const float cc = cbuf[m * H + u];
+            const float c_prev = has_prev ? cbuf[((int64_t)tp * B + row) * H + u] : 0.f;
+            const float tc = tanhf(cc);
+            const float dc_rec = p.step > 0 ? dcb[(int64_t)row * H + u] : 0.f;
+            const float dov = dh * tc;
+            const float dcv = dc_rec + dh * og * (1.f - tc * tc);
+            const float di = dcv * gg, dg = dcv * ig, df = dcv * c_prev;
+            dcb[(int64_t)row * H + u] = dcv * fg;
+            T* dp = da + m * G4 + (int64_t)d * 4 * H + u;
+            dp[0] = Elem<T>::from(di * ig * (1.f - ig));
+            dp[H] = Elem<T>::from(df * fg * (1.f - fg));
+            dp[2 * (int64_t)H] = Elem<T>::from(dg * (1.f - gg * gg));
+            dp[3 * (int64_t)H] = Elem<T>::from(dov * og * (1.f - og));
+        }
+    }
+}
+
+template <typename T, int VB>
+static hipError_t fwd_t(const RecDesc& d, hipStream_t s) {
+    const unsigned groups = (unsigned)(d.L * d.D);
+    if (d.B > 64) {
+        dim3 grid((d.H + 31) / 32, groups, (d.B + 127) / 128);
+        hipLaunchKernelGGL((rec_forward_kernel<T, 4, 1, VB>), grid, dim3(256), 0, s, d);
+    } else if (d.B > 32) {
+        dim3 grid((d.H + 63) / 64, groups, (d.B + 63) / 64);
+        hipLaunchKernelGGL((rec_forward_kernel<T, 2, 2, VB>), grid, dim3(256), 0, s, d);
+    } else {
+        dim3 grid((d.H + 127) / 128, groups, (d.B + 31) / 32);
+        hipLaunchKernelGGL((rec_forward_kernel<T, 1, 4, VB>), grid, dim3(256), 0, s, d);
+    }
+    return hipGetLastError();
+}
+
+template <typename T, int VB>
+static hipError_t bwd_t(const RecDesc& d, hipStream_t s) {
+    const unsigned groups = (unsigned)(d.L * d.D);
+    if (d.B > 64) {
+        dim3 grid((d.H + 63) / 64, groups, (d.B + 127) / 128);
+        hipLaunchKernelGGL((rec_backward_kernel<T, 4, 1, 2, VB>), grid, dim3(256), 0, s, d);
+    } else if (d.B > 32) {
+        dim3 grid((d.H + 63) / 64, groups, (d.B + 63) / 64);
+        hipLaunchKernelGGL((rec_backward_kernel<T, 2, 2, 1, VB>), grid, dim3(256), 0, s, d);
+    } else {
+        dim3 grid((d.H + 127) / 128, groups, (d.B + 31) / 32);
+        hipLaunchKernelGGL((rec_backward_kernel<T, 1, 4, 1, VB>), grid, dim3(256), 0, s, d);
+    }
+    return hipGetLastError();
+}
+
+static bool rec_ok(const RecDesc& d) {
+    return d.L >= 1 && d.D >= 1 && d.D <= 2 && d.B >= 1 && d.H >= 4 && d.H % 4 == 0 && d.T >= 1 &&
+           d.step >= 0 && d.step < d.T;
+}
+
+hipError_t launch_rec_forward(const RecDesc& d, hipStream_t s) {
+    if (!rec_ok(d)) return hipErrorInvalidValue;
+    if (d.precision == 0) return fwd_t<float, 16>(d, s);
+    return d.H % 8 == 0 ? fwd_t<bf16_t, 16>(d, s) : fwd_t<bf16_t, 8>(d, s);
+}
+
+hipError_t launch_rec_backward(const RecDesc& d, hipStream_t s) {
+    if (!rec_ok(d)) return hipErrorInvalidValue;
+    if (d.precision == 0) return bwd_t<float, 16>(d, s);
+    return d.H % 8 == 0 ? bwd_t<bf16_t, 16>(d, s) : bwd_t<bf16_t, 8>(d, s);
+}
+
+}  // namespace adpsgd

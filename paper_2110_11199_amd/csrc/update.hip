@@ -1,0 +1,207 @@
+// Fused mixing + SGD update over the learners' flat fp32 vectors (Algorithm 1:
+// model averaging followed by the local update; Eq. 2 in matrix form).
+//
+// One streaming pass: every element of every active learner is read once (model
+// and gradient) and written once, 12 bytes per (active learner, element).
+// Pairwise mixing handles both members of a matched pair in the same thread, so
+// the update is safe in place.  Arithmetic order (each operation rounded once,
+// no fused multiply-add):
+//     pair: m = (x_i + x_j) * 0.5      all: m = (((x_0 + x_1) + ...) ) * (1/L)
+//     x_i <- m - (lr * g_i)
+#include "kernels.hpp"
+
+namespace adpsgd {
+
+struct PairArgs {
+    const float* src; float* dst; int64_t stride; int64_t P; float lr;
+    int nwork;
+    const float* g[128];
+    int16_t a[128], b[128];     // work item w mixes learners a[w], b[w] (a == b: no partner)
+};
+
+__device__ inline float sgd_(float m, float lr, float g) { return __fsub_rn(m, __fmul_rn(lr, g)); }
+
+__device__ inline float4 pair_new_(const float4& m, float lr, const float4& g) {
+    return make_float4(sgd_(m.x, lr, g.x), sgd_(m.y, lr, g.y), sgd_(m.z, lr, g.z), sgd_(m.w, lr, g.w));
+}
+__device__ inline float4 half_sum_(const float4& p, const float4& q) {
+    return make_float4(__fmul_rn(__fadd_rn(p.x, q.x), 0.5f), __fmul_rn(__fadd_rn(p.y, q.y), 0.5f),
+                       __fmul_rn(__fadd_rn(p.z, q.z), 0.5f), __fmul_rn(__fadd_rn(p.w, q.w), 0.5f));
+}
+
+constexpr int kUnroll = 4;
+
+template <bool VEC>
+__global__ __launch_bounds__(256) void pair_update_kernel(PairArgs p) {
+    const int w = blockIdx.y;
+    const int a = p.a[w], b = p.b[w];
+    const float* xa = p.src + a * p.stride;
+    const float* xb = p.src + b * p.stride;
+    float* oa = p.dst + a * p.stride;
+    float* ob = p.dst + b * p.stride;
+    const float* ga = p.g[a];
+    const float* gb = p.g[b];
+    const float lr = p.lr;
+    if constexpr (VEC) {
+        const int64_t n4 = p.P >> 2;
+        const int64_t base = (int64_t)blockIdx.x * (256 * kUnroll) + threadIdx.x;
+        if (a == b) {
+            float4 x[kUnroll], g[kUnroll];
+#pragma unroll
+            for (int u = 0; u < kUnroll; ++u) {
+                const int64_t e = base + u * 256;
+                if (e < n4) { x[u] = ((const float4*)xa)[e]; g[u] = ((const float4*)ga)[e]; }
+            }
+#pragma unroll
+            for (int u = 0; u < kUnroll; ++u) {
+                const int64_t e = base + u * 256;
+                if (e < n4) ((float4*)oa)[e] = pair_new_(x[u], lr, g[u]);
+            }
+        } else {
+            float4 x[kUnroll], y[kUnroll], g[kUnroll], h[kUnroll];
+#pragma unroll
+            for (int u = 0; u < kUnroll; ++u) {
+                const int64_t e = base + u * 256;
+                if (e < n4) {
+                    x[u] = ((const float4*)xa)[e]; y[u] = ((const float4*)xb)[e];
+                    g[u] = ((const float4*)ga)[e]; h[u] = ((const float4*)gb)[e];
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < kUnroll; ++u) {
+                const int64_t e = base + u * 256;
+                if (e < n4) {
+                    const float4 m = half_sum_(x[u], y[u]);
+                    ((float4*)oa)[e] = pair_new_(m, lr, g[u]);
+                    ((float4*)ob)[e] = pair_new_(m, lr, h[u]);
+                }
+            }
+        }
+        // tail (P % 4 elements), handled by the first block
+        if (blockIdx.x == 0 && threadIdx.x < (p.P & 3)) {
+            const int64_t e = (n4 << 2) + threadIdx.x;
+            if (a == b) oa[e] = sgd_(xa[e], lr, ga[e]);
+            else {
+                const float m = __fmul_rn(__fadd_rn(xa[e], xb[e]), 0.5f);
+                const float va = sgd_(m, lr, ga[e]), vb = sgd_(m, lr, gb[e]);
+                oa[e] = va; ob[e] = vb;
+            }
+        }
+    } else {
+        const int64_t base = (int64_t)blockIdx.x * (256 * kUnroll) + threadIdx.x;
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) {
+            const int64_t e = base + u * 256;
+            if (e >= p.P) continue;
+            if (a == b) oa[e] = sgd_(xa[e], lr, ga[e]);
+            else {
+                const float m = __fmul_rn(__fadd_rn(xa[e], xb[e]), 0.5f);
+                const float va = sgd_(m, lr, ga[e]), vb = sgd_(m, lr, gb[e]);
+                oa[e] = va; ob[e] = vb;
+            }
+        }
+    }
+}
+
+struct AllArgs {
+    const float* src; float* dst; int64_t stride; int64_t P; float lr; float inv_L; int L;
+    const float* g[128];
+};
+
+// One thread owns an element index of all learners: reads L models, forms the
+// mean once, reads L gradients, writes L models.
+template <bool VEC>
+__global__ __launch_bounds__(256) void all_update_kernel(AllArgs p) {
+    const int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if constexpr (VEC) {
+        const int64_t n4 = p.P >> 2;
+        if (e < n4) {
+            float4 s = ((const float4*)p.src)[e];
+#pragma unroll 8
+            for (int j = 1; j < p.L; ++j) {
+                const float4 v = ((const float4*)(p.src + j * p.stride))[e];
+                s.x = __fadd_rn(s.x, v.x); s.y = __fadd_rn(s.y, v.y); s.z = __fadd_rn(s.z, v.z); s.w = __fadd_rn(s.w, v.w);
+            }
+            const float4 m = make_float4(__fmul_rn(s.x, p.inv_L), __fmul_rn(s.y, p.inv_L), __fmul_rn(s.z, p.inv_L), __fmul_rn(s.w, p.inv_L));
+#pragma unroll 8
+            for (int i = 0; i < p.L; ++i) {
+                const float4 g = ((const float4*)p.g[i])[e];
+                ((float4*)(p.dst + i * p.stride))[e] = pair_new_(m, p.lr, g);
+            }
+        }
+        if (blockIdx.x == 0 && threadIdx.x < (p.P & 3)) {
+            const int64_t t = (n4 << 2) + threadIdx.x;
+            float s = p.src[t];
+            for (int j = 1; j < p.L; ++j) s = __fadd_rn(s, p.src[j * p.stride + t]);
+            const float m = __fmul_rn(s, p.inv_L);
+            for (int i = 0; i < p.L; ++i) p.dst[i * p.stride + t] = sgd_(m, p.lr, p.g[i][t]);
+        }
+    } else {
+        if (e < p.P) {
+            float s = p.src[e];
+            for (int j = 1; j < p.L; ++j) s = __fadd_rn(s, p.src[j * p.stride + e]);
+            const float m = __fmul_rn(s, p.inv_L);
+            for (int i = 0; i < p.L; ++i) p.dst[i * p.stride + e] = sgd_(m, p.lr, p.g[i][e]);
+        }
+    }
+}
+
+__global__ __launch_bounds__(256) void average_kernel(const float* x, int64_t stride, int L, int64_t P,
+                                                      float inv_L, float* out) {
+    const int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (e >= P) return;
+    float s = x[e];
+    for (int j = 1; j < L; ++j) s = __fadd_rn(s, x[j * stride + e]);
+    out[e] = __fmul_rn(s, inv_L);
+}
+
+hipError_t launch_update(const UpdateDesc& d, hipStream_t s) {
+    if (d.L < 1 || d.L > 128 || d.P < 1) return hipErrorInvalidValue;
+    bool vec = ((uintptr_t)d.src % 16 == 0) && ((uintptr_t)d.dst % 16 == 0) && (d.stride % 4 == 0);
+    for (int i = 0; i < d.L; ++i)
+        if ((uintptr_t)d.g[i] % 16 != 0) vec = false;
+    if (d.mix == 2) {
+        AllArgs a;
+        a.src = d.src; a.dst = d.dst; a.stride = d.stride; a.P = d.P; a.lr = d.lr; a.L = d.L;
+        a.inv_L = 1.0f / (float)d.L;
+        for (int i = 0; i < 128; ++i) a.g[i] = i < d.L ? d.g[i] : nullptr;
+        if (vec) {
+            const int64_t n4 = d.P >> 2;
+            const unsigned blocks = (unsigned)((n4 > 0 ? n4 : 1) + 255) / 256;
+            hipLaunchKernelGGL(all_update_kernel<true>, dim3(blocks), dim3(256), 0, s, a);
+        } else {
+            hipLaunchKernelGGL(all_update_kernel<false>, dim3((unsigned)((d.P + 255) / 256)), dim3(256), 0, s, a);
+        }
+        return hipGetLastError();
+    }
+    PairArgs a;
+    a.src = d.src; a.dst = d.dst; a.stride = d.stride; a.P = d.P; a.lr = d.lr;
+    for (int i = 0; i < 128; ++i) { a.g[i] = i < d.L ? d.g[i] : nullptr; a.a[i] = a.b[i] = 0; }
+    int n = 0;
+    for (int i = 0; i < d.L; ++i) {
+        if (!d.active[i]) continue;
+        const int j = d.partner[i];
+        if (j == i) { a.a[n] = a.b[n] = (int16_t)i; ++n; }
+        else if (i < j) { a.a[n] = (int16_t)i; a.b[n] = (int16_t)j; ++n; }
+    }
+    a.nwork = n;
+    if (n == 0) return hipSuccess;
+    if (vec) {
+        const int64_t n4 = d.P >> 2;
+        const int64_t per = 256 * kUnroll;
+        const unsigned blocks = (unsigned)(((n4 > 0 ? n4 : 1) + per - 1) / per);
+        hipLaunchKernelGGL(pair_update_kernel<true>, dim3(blocks, (unsigned)n), dim3(256), 0, s, a);
+    } else {
+        const int64_t per = 256 * kUnroll;
+        hipLaunchKernelGGL(pair_update_kernel<false>, dim3((unsigned)((d.P + per - 1) / per), (unsigned)n), dim3(256), 0, s, a);
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_average(const float* x, int64_t stride, int L, int64_t P, float* out, hipStream_t s) {
+    hipLaunchKernelGGL(average_kernel, dim3((unsigned)((P + 255) / 256)), dim3(256), 0, s, x, stride, L, P,
+                       1.0f / (float)L, out);
+    return hipGetLastError();
+}
+
+}  // namespace adpsgd

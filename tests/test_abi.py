@@ -1,0 +1,68 @@
+"""CPU-only checks of the C ABI: the library loads, exports what the header
+declares, validates configurations, and its host-side schedule (a second,
+independent implementation) is bit-identical to the oracle's."""
+import os
+import re
+import ctypes
+import pytest
+
+from oracle import schedule as S
+from paper_2110_11199_amd import binding as Bd
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    hdr = open(os.path.join(ROOT, "include", "adpsgd.h")).read()
+    hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
+    declared = set(re.findall(r"\b(adpsgd_[a-z_0-9]+)\s*\(", hdr))
+    assert len(declared) >= 15
+    lib = ctypes.CDLL(Bd.LIB_PATH)
+    for name in sorted(declared):
+        assert hasattr(lib, name), name
+    assert declared == set(Bd.EXPORTS)
+
+
+@pytest.mark.parametrize("pattern", [0, 1, 2])
+@pytest.mark.parametrize("L", [1, 2, 3, 4, 7, 8, 16, 64, 128])
+@pytest.mark.parametrize("p", [0.0, 0.1, 0.5])
+def test_schedule_is_bit_identical_to_the_oracle(pattern, L, p):
+    for seed in (0, 12345, 2**63 + 11, 2**64 - 1):
+        for k in (0, 1, 2, 3, 49, 1000003):
+            assert Bd.adpsgd_schedule_of(pattern, seed, p, L, k) == S.schedule(pattern, seed, k, L, p)
+
+
+def test_schedule_matches_stored_vectors():
+    with open(os.path.join(ROOT, "tests", "golden", "schedule_vectors.txt")) as fh:
+        rows = [ln.split() for ln in fh if ln.strip() and not ln.startswith("#")]
+    for row in rows:
+        pattern, seed, k, L, p = int(row[0]), int(row[1]), int(row[2]), int(row[3]), float(row[4])
+        o, pa, a = Bd.adpsgd_schedule_of(pattern, seed, p, L, k)
+        assert list(map(int, row[5:])) == o + pa + a
+
+
+def test_config_validation_and_workspace_size():
+    ok = Bd.make_config(4, Bd.FIXED_RING, input_dim=40, hidden=64, layers=1, classes=100, batch=4, frames=20)
+    n = Bd.adpsgd_workspace_bytes(ok)
+    assert n > 4 * 33380 * 4 * 2 and n % 256 == 0
+    flat = Bd.make_config(64, Bd.RANDOM_RING, flat_params=135_000_000, straggler_p=0.1)
+    assert Bd.adpsgd_workspace_bytes(flat) == 64 * 135_000_000 * 4
+    d1d = Bd.make_config(64, Bd.D1D, flat_params=1000)
+    assert Bd.adpsgd_workspace_bytes(d1d) == 2 * 64 * 1024 * 4          # two model buffers, padded stride
+    bad = [Bd.make_config(0, 0, flat_params=8), Bd.make_config(129, 0, flat_params=8),
+           Bd.make_config(4, 3, flat_params=8), Bd.make_config(4, Bd.D1D, flat_params=8, straggler_p=0.1),
+           Bd.make_config(4, 0, flat_params=8, tau=1, straggler_p=0.1),
+           Bd.make_config(4, 0, input_dim=39, hidden=64, layers=1, classes=100, batch=4, frames=20),
+           Bd.make_config(4, 0, input_dim=40, hidden=64, layers=0, classes=100, batch=4, frames=20),
+           Bd.make_config(4, 0, flat_params=8, precision=2), Bd.make_config(4, 0, flat_params=8, mix=1)]
+    for cfg in bad:
+        with pytest.raises(Bd.AdpsgdError) as ei:
+            Bd.adpsgd_workspace_bytes(cfg)
+        assert ei.value.code == Bd.EINVAL and Bd.adpsgd_last_error()
+
+
+def test_create_rejects_a_missing_workspace():
+    cfg = Bd.make_config(2, 0, flat_params=8)
+    with pytest.raises(Bd.AdpsgdError) as ei:
+        Bd.adpsgd_create(cfg, None, 0, None)
+    assert ei.value.code == Bd.ENOMEM

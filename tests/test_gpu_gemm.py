@@ -1,0 +1,75 @@
+"""GPU: the grouped MFMA GEMM against a float64 numpy product."""
+import numpy as np
+import pytest
+
+from tests.gpu_util import rel_err, to_bf16_bits, from_bf16_bits
+
+pytestmark = pytest.mark.gpu
+
+
+def _run(prec, a_k, b_k, c_elem, M, N, K, groups, bias, pad=0, seed=0):
+    import torch
+    from paper_2110_11199_amd import binding as Bd
+    r = np.random.default_rng(seed)
+    dev = torch.device("cuda:0")
+    r4 = lambda v: (v + 3) // 4 * 4
+    lda = r4(K if a_k else M) + pad
+    ldb = r4(K if b_k else N) + pad
+    ldc = N + pad
+    A = r.standard_normal((groups, M if a_k else K, lda)).astype(np.float32)
+    B = r.standard_normal((groups, N if b_k else K, ldb)).astype(np.float32)
+    bv = r.standard_normal((groups, N)).astype(np.float32) if bias else None
+    if prec:
+        A, B = from_bf16_bits(to_bf16_bits(A)), from_bf16_bits(to_bf16_bits(B))
+        dA = torch.from_numpy(to_bf16_bits(A).view(np.int16)).to(dev)
+        dB = torch.from_numpy(to_bf16_bits(B).view(np.int16)).to(dev)
+    else:
+        dA, dB = torch.from_numpy(A).to(dev), torch.from_numpy(B).to(dev)
+    cdt = torch.int16 if (prec and c_elem) else torch.float32
+    dC = torch.full((groups, M, ldc), 7, dtype=cdt, device=dev)
+    dbias = torch.from_numpy(bv).to(dev) if bias else None
+    Bd.adpsgd_gemm(prec, a_k, b_k, c_elem, M, N, K, dA.data_ptr(), lda, dA[0].numel(), dB.data_ptr(), ldb,
+                   dB[0].numel(), dC.data_ptr(), ldc, M * ldc, dbias.data_ptr() if bias else None, N, groups,
+                   torch.cuda.current_stream().cuda_stream)
+    torch.cuda.synchronize()
+    got = dC.cpu().numpy()
+    if prec and c_elem:
+        got = from_bf16_bits(got.view(np.uint16))
+    Am = A[:, :, :K] if a_k else A[:, :, :M].transpose(0, 2, 1)
+    Bm = B[:, :, :K] if b_k else B[:, :, :N].transpose(0, 2, 1)
+    ref = np.einsum("gmk,gnk->gmn", Am.astype(np.float64), Bm.astype(np.float64))
+    if bias:
+        ref += bv[:, None, :]
+    if pad:
+        assert (got[:, :, N:] == (from_bf16_bits(np.array([7], np.uint16))[0] if (prec and c_elem) else 7)).all()
+    return rel_err(got[:, :, :N], ref)
+
+
+LAYOUTS = [(1, 1), (1, 0), (0, 0), (0, 1)]
+
+
+@pytest.mark.parametrize("a_k,b_k", LAYOUTS)
+@pytest.mark.parametrize("M,N,K", [(128, 128, 64), (200, 136, 100), (80, 256, 40), (257, 129, 260), (4, 4, 4)])
+def test_gemm_fp32(a_k, b_k, M, N, K):
+    print("gemm fp32", a_k, b_k, M, N, K, flush=True)
+    assert _run(0, a_k, b_k, 0, M, N, K, 3, True, pad=4) < 2e-6
+    assert _run(0, a_k, b_k, 1, M, N, K, 1, False) < 2e-6
+
+
+@pytest.mark.parametrize("a_k,b_k", LAYOUTS)
+@pytest.mark.parametrize("M,N,K", [(128, 128, 64), (200, 136, 100), (80, 256, 40), (257, 132, 260), (4, 8, 12)])
+def test_gemm_bf16(a_k, b_k, M, N, K):
+    print("gemm bf16", a_k, b_k, M, N, K, flush=True)
+    # operands are exactly representable in bf16, so only the fp32 accumulation differs
+    assert _run(1, a_k, b_k, 0, M, N, K, 3, True, pad=8) < 2e-6
+    assert _run(1, a_k, b_k, 0, M, N, K, 2, False, pad=4) < 2e-6      # 8-byte aligned rows only
+    assert _run(1, a_k, b_k, 1, M, N, K, 1, True) < 6e-3             # bf16 output rounding
+
+
+def test_gemm_rejects_misaligned_rows():
+    import torch
+    from paper_2110_11199_amd import binding as Bd
+    t = torch.zeros(64 * 66, device="cuda:0")
+    with pytest.raises(Bd.AdpsgdError) as ei:
+        Bd.adpsgd_gemm(0, 1, 1, 0, 8, 8, 8, t.data_ptr(), 10, 0, t.data_ptr(), 8, 0, t.data_ptr(), 8, 0, None, 0, 1, None)
+    assert ei.value.code == Bd.EINVAL

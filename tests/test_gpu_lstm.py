@@ -1,0 +1,127 @@
+"""GPU: LSTM gradient and full ADPSGD iterations against the CPU oracle.
+
+Tolerances (per tensor, max|diff| / max|ref|): 1e-4 with fp32 GEMM operands,
+2e-2 with bf16 GEMM operands; the schedule is compared exactly."""
+import numpy as np
+import pytest
+
+from oracle import lstm, schedule as S, adpsgd as A
+from oracle.lstm import Shape
+from paper_2110_11199_amd import synth
+from tests.gpu_util import rel_err
+
+pytestmark = pytest.mark.gpu
+
+TOL = {0: 1e-4, 1: 2e-2}
+
+
+def _engine(shape, L, pattern, prec, seed=0, **kw):
+    from paper_2110_11199_amd import binding as Bd
+    cfg = Bd.make_config(L, pattern, seed=seed, input_dim=shape.input_dim, hidden=shape.hidden,
+                         layers=shape.layers, bidirectional=shape.bidirectional, bottleneck=shape.bottleneck,
+                         classes=shape.classes, batch=shape.batch, frames=shape.frames, precision=prec, **kw)
+    return Bd.Adpsgd(cfg)
+
+
+def _batches(shape, L, k, seed=0):
+    return [(synth.features(seed, k, i, shape.frames, shape.batch, shape.input_dim),
+             synth.labels(seed, k, i, shape.frames, shape.batch, shape.classes)) for i in range(L)]
+
+
+def _to_dev(batches):
+    import torch
+    return [(torch.from_numpy(f).cuda(), torch.from_numpy(y).cuda()) for f, y in batches]
+
+
+def _per_tensor_err(shape, got, ref):
+    worst = 0.0
+    for name, off, r, c in lstm.layout(shape)[0]:
+        worst = max(worst, rel_err(got[off:off + r * c], ref[off:off + r * c]))
+    return worst
+
+
+SHAPES = [
+    Shape(40, 64, 1, 0, 0, 100, 4, 20),       # the tiny benchmark shape
+    Shape(12, 32, 2, 1, 0, 52, 5, 7),         # bidirectional, ragged batch
+    Shape(24, 36, 2, 1, 16, 40, 33, 3),       # bottleneck, hidden not a multiple of 8/32, batch 33
+    Shape(20, 64, 1, 1, 0, 300, 70, 4),       # batch 70 (64-row tiles + tail), several class tiles
+    Shape(16, 32, 3, 0, 8, 36, 130, 2),       # batch 130 (128-row tiles + tail), unidirectional
+    Shape(8, 8, 1, 1, 4, 8, 2, 1),            # one frame: no recurrence
+]
+
+
+@pytest.mark.parametrize("prec", [0, 1])
+@pytest.mark.parametrize("shape", SHAPES)
+def test_gradient_matches_oracle(shape, prec):
+    import torch
+    print("lstm grad", shape, prec, flush=True)
+    L = 2
+    P = lstm.param_count(shape)
+    w0 = synth.initial_model(1, P, 0.2)
+    eng = _engine(shape, L, S.FIXED_RING, prec)
+    assert eng.P == P
+    from paper_2110_11199_amd import binding as Bd
+    assert [(o, r, c) for _, o, r, c in lstm.layout(shape)[0]] == Bd.adpsgd_layout(eng.h)
+    eng.set_params(-1, torch.from_numpy(w0).cuda())
+    b = _batches(shape, L, 0)
+    eng.step(_to_dev(b), 0.0)
+    losses = eng.losses()
+    for i in range(L):
+        loss, g = lstm.loss_and_grad(shape, w0, b[i][0], b[i][1], np.float32)
+        got = eng.grads(i).cpu().numpy()
+        assert np.isfinite(got).all()
+        assert _per_tensor_err(shape, got, g) < TOL[prec], (i, _per_tensor_err(shape, got, g))
+        assert abs(losses[i] - loss) < TOL[prec] * abs(loss)
+    eng.close()
+
+
+def _run_recurrence(shape, L, pattern, prec, steps, lr, seed=0, scale=0.1, **kw):
+    import torch
+    P = lstm.param_count(shape)
+    w0 = synth.initial_model(seed, P, scale)
+    eng = _engine(shape, L, pattern, prec, seed=seed, **kw)
+    eng.set_params(-1, torch.from_numpy(w0).cuda())
+    ora = A.Oracle(L, pattern, seed, shape=shape, w0=w0, straggler_p=kw.get("straggler_p", 0.0))
+    for k in range(steps):
+        b = _batches(shape, L, k, seed)
+        eng.step(_to_dev(b), lr)
+        ora.step(b, lr)
+        assert eng.schedule(k) == tuple(ora.last_schedule)
+        active = ora.last_schedule[2]
+        for i in range(L):
+            got_x = eng.params(i).cpu().numpy()
+            if active[i]:
+                got_g = eng.grads(i).cpu().numpy()
+                assert _per_tensor_err(shape, got_g, ora.last_grads[i]) < TOL[prec], (k, i)
+            assert _per_tensor_err(shape, got_x, ora.x[i]) < TOL[prec], (k, i)
+    eng.close()
+    return ora
+
+
+def test_tiny_config_five_steps_fixed_ring():
+    print("cfg1 recurrence", flush=True)
+    wl = synth.WORKLOADS["cfg1"]
+    shape = Shape(wl.input_dim, wl.hidden, wl.layers, wl.bidirectional, wl.bottleneck, wl.classes, wl.batch, wl.frames)
+    _run_recurrence(shape, wl.L, wl.pattern, 0, wl.steps, wl.lr, scale=wl.init_scale)
+
+
+def test_random_ring_with_stragglers_small_model():
+    print("random ring + stragglers", flush=True)
+    _run_recurrence(Shape(12, 16, 1, 1, 0, 20, 3, 4), 6, S.RANDOM_RING, 0, 5, 0.2, seed=4, straggler_p=0.3)
+
+
+@pytest.mark.parametrize("prec", [0, 1])
+def test_delay_by_one_small_model(prec):
+    print("d1d small", prec, flush=True)
+    ora = _run_recurrence(Shape(12, 16, 2, 1, 8, 20, 3, 4), 4, S.D1D, prec, 4, 0.3, seed=2, scale=0.3)
+    assert ora.tau == 1
+
+
+def test_library_initial_model_matches_generator_spec():
+    import torch
+    shape = Shape(8, 8, 1, 0, 0, 8, 2, 2)
+    eng = _engine(shape, 3, S.FIXED_RING, 0, seed=77, init_scale=0.1)
+    ref = A.init_model(77, eng.P, 0.1)
+    for i in range(3):
+        assert (eng.params(i).cpu().numpy() == ref).all()      # same w_0 on every learner
+    eng.close()

@@ -1,0 +1,79 @@
+"""GPU: the fused mixing + SGD update in model-free mode, bit-exact against the oracle."""
+import numpy as np
+import pytest
+
+from oracle import schedule as S
+from oracle import adpsgd as A
+
+pytestmark = pytest.mark.gpu
+
+
+def _run(L, P, pattern, steps, p=0.0, mix=None, tau=None, seed=3, lr=0.1):
+    import torch
+    from paper_2110_11199_amd import binding as Bd
+    r = np.random.default_rng(seed)
+    x0 = r.uniform(-0.05, 0.05, (L, P)).astype(np.float32)
+    x0[0, : min(P, 3)] = [1e-39, -0.0, 3e38][: min(P, 3)]        # a denormal, a signed zero, a huge value
+    g = (r.standard_normal((L, P)) * 1e-3).astype(np.float32)
+    cfg = Bd.make_config(L, pattern, seed=seed, flat_params=P, straggler_p=p,
+                         mix=Bd.MIX_DEFAULT if mix is None else mix, tau=-1 if tau is None else tau)
+    eng = Bd.Adpsgd(cfg)
+    for i in range(L):
+        eng.set_params(i, torch.from_numpy(x0[i]).cuda())
+    gd = [torch.from_numpy(g[i]).cuda() for i in range(L)]
+    ora = A.Oracle(L, pattern, seed, flat_params=P, x0=x0, straggler_p=p, mix=mix, tau=tau)
+    for k in range(steps):
+        eng.step(gd, lr)
+        ora.step(None, lr, grads=g)
+        assert eng.schedule(k) == tuple(ora.last_schedule)
+        got = np.stack([eng.params(i).cpu().numpy() for i in range(L)])
+        assert (got.view(np.uint32) == ora.x.view(np.uint32)).all(), (k, np.abs(got - ora.x).max())
+    eng.close()
+
+
+@pytest.mark.parametrize("P", [1, 3, 4, 1023, 4096, 100003, 1 << 20])
+def test_pairwise_random_ring_with_stragglers(P):
+    print("update pair P", P, flush=True)
+    _run(8, P, S.RANDOM_RING, 6, p=0.3)
+
+
+@pytest.mark.parametrize("L", [1, 2, 3, 5, 64])
+def test_pairwise_fixed_ring(L):
+    print("update fixed L", L, flush=True)
+    _run(L, 70001, S.FIXED_RING, 4)
+
+
+@pytest.mark.parametrize("L,P", [(1, 5), (4, 70001), (16, 4096), (128, 1000)])
+def test_delay_by_one_global_mean(L, P):
+    print("update d1d", L, P, flush=True)
+    _run(L, P, S.D1D, 4)
+
+
+def test_delay_by_one_with_pairwise_mixing_and_ring_with_global_mean():
+    _run(6, 5001, S.D1D, 4, mix=S.MIX_PAIR)
+    _run(6, 5001, S.FIXED_RING, 3, mix=S.MIX_ALL, tau=0)
+
+
+def test_all_stragglers_is_identity_and_average_is_learner_mean():
+    import torch
+    from paper_2110_11199_amd import binding as Bd
+    L, P = 4, 1001
+    r = np.random.default_rng(0)
+    x0 = r.uniform(-1, 1, (L, P)).astype(np.float32)
+    cfg = Bd.make_config(L, S.RANDOM_RING, flat_params=P, straggler_p=0.999)
+    eng = Bd.Adpsgd(cfg)
+    for i in range(L):
+        eng.set_params(i, torch.from_numpy(x0[i]).cuda())
+    gd = [torch.ones(P, device="cuda") for _ in range(L)]
+    ks = [k for k in range(50) if sum(S.schedule(S.RANDOM_RING, 0, k, L, 0.999)[2]) == 0]
+    assert len(ks) > 40
+    eng.step(gd, 0.1)
+    if 0 in ks:
+        got = np.stack([eng.params(i).cpu().numpy() for i in range(L)])
+        assert (got.view(np.uint32) == x0.view(np.uint32)).all()
+    cur = np.stack([eng.params(i).cpu().numpy() for i in range(L)])
+    s = cur[0].copy()
+    for j in range(1, L):
+        s = s + cur[j]
+    assert (eng.average().cpu().numpy() == s * (np.float32(1) / np.float32(L))).all()
+    eng.close()
