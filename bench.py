@@ -1,0 +1,199 @@
+#!/usr/bin/env python3
+"""Benchmark of the ADPSGD hot path on one MI355X.
+
+A step is one ADPSGD iteration over all L learners of a workload: minibatch
+staging, BLSTM forward/backward of every learner, mixing and SGD update.  The
+default workload is the largest model configuration ("cfg4": 16 learners,
+delay-by-one, 6-layer BLSTM with 1024 cells per direction, 256-wide linear
+bottleneck, 32000 classes, 128 segments x 21 frames per learner, bf16 GEMM
+operands), the only one that exercises every kernel of the path.  A second,
+short leg times the model-free mixing/update stress workload ("cfg5") for the
+HBM part of the metric.  Inputs are seeded synthetic data, resident in HBM
+before the timed region.
+
+Prints ONE JSON line.  `roofline` describes the kernel that dominates the step
+(the time-batched MFMA GEMM): algorithmic flops / its GPU time measured with HIP
+events on the library's stream over the timed steps.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+METRIC = "frames/sec & learner-steps/sec (1 MI355X); mix/update HBM GB/s"
+PEAK_TFLOPS = {"bf16": 2500.0, "f32": 157.3}
+PEAK_HBM_GBS = 8000.0
+
+
+def _config(Bd, wl, seed):
+    if wl.flat_params:
+        return Bd.make_config(wl.L, wl.pattern, seed=seed, flat_params=wl.flat_params, straggler_p=wl.straggler_p)
+    return Bd.make_config(wl.L, wl.pattern, seed=seed, input_dim=wl.input_dim, hidden=wl.hidden, layers=wl.layers,
+                          bidirectional=wl.bidirectional, bottleneck=wl.bottleneck, classes=wl.classes,
+                          batch=wl.batch, frames=wl.frames, precision=wl.precision)
+
+
+def run_model(wl, steps, warmup, seed=0):
+    import torch
+    from paper_2110_11199_amd import binding as Bd, synth
+    eng = Bd.Adpsgd(_config(Bd, wl, seed))
+    w0 = synth.initial_model(seed, eng.P, wl.init_scale)
+    eng.set_params(-1, torch.from_numpy(w0).cuda())
+    cdf = synth.zipf_cdf(wl.classes) if wl.label_dist == "zipf" else None
+    batches = []
+    for k in range(warmup + steps):          # a fresh minibatch per (learner, step), staged before timing
+        batches.append([tuple(torch.from_numpy(a).cuda() for a in synth.batch(wl, seed, k, i, cdf))
+                        for i in range(wl.L)])
+    for k in range(warmup):
+        eng.step(batches[k], wl.lr)
+    Bd.adpsgd_set_profiling(eng.h, 1)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for k in range(steps):
+        eng.step(batches[warmup + k], wl.lr)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    prof = Bd.adpsgd_profile(eng.h)
+    losses = eng.losses()
+    eng.close()
+    del eng
+    torch.cuda.empty_cache()
+    return dt, prof, float(losses.mean())
+
+
+def run_flat(wl, steps, warmup, seed=0):
+    import torch
+    from paper_2110_11199_amd import binding as Bd
+    eng = Bd.Adpsgd(_config(Bd, wl, seed))
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(seed)
+    grads = []
+    for i in range(wl.L):                     # x_i^0 ~ U(-0.05, 0.05) per learner, g_i ~ N(0, 1e-3^2), drawn once
+        x = torch.empty(eng.P, device="cuda").uniform_(-0.05, 0.05, generator=gen)
+        eng.set_params(i, x)
+        grads.append(torch.empty(eng.P, device="cuda").normal_(0.0, 1e-3, generator=gen))
+    del x
+    for k in range(warmup):
+        eng.step(grads, wl.lr)
+    Bd.adpsgd_set_profiling(eng.h, 1)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for k in range(steps):
+        eng.step(grads, wl.lr)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    prof = Bd.adpsgd_profile(eng.h)
+    active = sum(sum(eng.schedule(warmup + k)[2]) for k in range(steps))
+    eng.close()
+    del eng, grads
+    torch.cuda.empty_cache()
+    return dt, prof, active
+
+
+def cpu_baseline(wl, seed=0):
+    """The numpy oracle, as it stands, on one learner's minibatch of the workload."""
+    import numpy as np
+    from paper_2110_11199_amd import synth
+    from oracle import lstm
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    shape = lstm.Shape(wl.input_dim, wl.hidden, wl.layers, wl.bidirectional, wl.bottleneck, wl.classes,
+                       wl.batch, wl.frames)
+    w0 = synth.initial_model(seed, lstm.param_count(shape), wl.init_scale)
+    cdf = synth.zipf_cdf(wl.classes) if wl.label_dist == "zipf" else None
+    f, y = synth.batch(wl, seed, 0, 0, cdf)
+    t0 = time.perf_counter()
+    lstm.loss_and_grad(shape, w0, f, y, np.float32)
+    dt = time.perf_counter() - t0
+    return {"value": wl.batch * wl.frames / dt, "unit": "frames/s", "cores": int(cores), "kind": "oracle",
+            "sample": "gradient of 1 of the %d learner minibatches of one %s iteration (%.1f s); the mixing/update "
+                      "part of the oracle is elementwise and under 1%% of that" % (wl.L, wl.name, dt)}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--workload", default="cfg4", choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5"])
+    ap.add_argument("--mix-steps", type=int, default=20, help="timed steps of the cfg5 mixing/update leg (0 = skip)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (L learners are replicas resident on one MI355X); "
+              "--gpus %d is not supported" % args.gpus, file=sys.stderr)
+        sys.exit(2)
+    from paper_2110_11199_amd import synth
+    wl = synth.WORKLOADS[args.workload]
+    out = {"metric": METRIC, "unit": "frames/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+           "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "data": "synthetic"}
+
+    def update_roofline(prof, steps):
+        u = prof["mix_update"]
+        gbs = u["work"] / (u["ms"] * 1e-3) / 1e9 if u["ms"] > 0 else 0.0
+        return {"bound": "hbm", "achieved": gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": gbs / PEAK_HBM_GBS,
+                "traffic": None, "kernel": "pair_update_kernel/all_update_kernel",
+                "avg_launch_ms": u["ms"] / max(u["launches"], 1), "bytes_per_launch": u["work"] / max(u["launches"], 1)}
+
+    if wl.flat_params:
+        dt, prof, active = run_flat(wl, args.steps, args.warmup)
+        ms = dt / args.steps * 1e3
+        out.update({"value": 0.0, "ms_per_step": ms, "dtype": "f32",
+                    "learner_steps_per_s": active / dt,
+                    "config": {"workload": wl.name, "L": wl.L, "flat_params": wl.flat_params, "pattern": "random ring",
+                               "straggler_p": wl.straggler_p, "note": "model-free: no frames"},
+                    "roofline": update_roofline(prof, args.steps)})
+        out["mix_update_GBps"] = out["roofline"]["achieved"]
+    else:
+        dt, prof, loss = run_model(wl, args.steps, args.warmup)
+        ms = dt / args.steps * 1e3
+        frames = wl.L * wl.batch * wl.frames
+        dtype = "bf16" if wl.precision else "f32"
+        g = prof["batched_gemm"]
+        tf = g["work"] / (g["ms"] * 1e-3) / 1e12 if g["ms"] > 0 else 0.0
+        rec_ms = prof["recurrent_fwd"]["ms"] + prof["recurrent_bwd"]["ms"]
+        rec_work = prof["recurrent_fwd"]["work"] + prof["recurrent_bwd"]["work"]
+        rec_tf = rec_work / (rec_ms * 1e-3) / 1e12 if rec_ms > 0 else 0.0
+        peak = PEAK_TFLOPS[dtype]
+        out.update({
+            "value": frames / (ms * 1e-3), "ms_per_step": ms, "dtype": dtype,
+            "learner_steps_per_s": wl.L / (ms * 1e-3),
+            "config": {"workload": wl.name, "L": wl.L, "pattern": ["fixed ring", "random ring", "delay-by-one"][wl.pattern],
+                       "layers": wl.layers, "hidden_per_direction": wl.hidden, "bidirectional": bool(wl.bidirectional),
+                       "bottleneck": wl.bottleneck, "classes": wl.classes, "input_dim": wl.input_dim,
+                       "batch_per_learner": wl.batch, "frames": wl.frames, "frames_per_step": frames},
+            "mean_loss_last_step": loss,
+            "phases_ms_per_step": {k: v["ms"] / args.steps for k, v in prof.items()},
+            "roofline": {"bound": "mfma", "achieved": tf, "peak": peak, "unit": "TFLOP/s", "frac": tf / peak,
+                         "traffic": None, "kernel": "gemm_kernel (time-batched GEMMs)",
+                         "launches_per_step": g["launches"] / args.steps,
+                         "avg_launch_ms": g["ms"] / max(g["launches"], 1),
+                         "flops_per_launch": g["work"] / max(g["launches"], 1)},
+            "roofline_recurrent": {"bound": "hbm-or-mfma", "achieved": rec_tf, "peak": peak, "unit": "TFLOP/s",
+                                   "frac": rec_tf / peak, "kernel": "rec_forward_kernel + rec_backward_kernel",
+                                   "avg_launch_ms": rec_ms / max(prof["recurrent_fwd"]["launches"] + prof["recurrent_bwd"]["launches"], 1)},
+            "roofline_update": update_roofline(prof, args.steps),
+        })
+        if args.mix_steps > 0:
+            w5 = synth.WORKLOADS["cfg5"]
+            dt5, prof5, active5 = run_flat(w5, args.mix_steps, 2)
+            r5 = update_roofline(prof5, args.mix_steps)
+            r5.update({"workload": "cfg5", "steps": args.mix_steps, "ms_per_step": dt5 / args.mix_steps * 1e3,
+                       "learner_steps_per_s": active5 / dt5})
+            out["mix_update"] = r5
+            out["mix_update_GBps"] = r5["achieved"]
+        if not args.no_cpu_baseline:
+            out["cpu_baseline"] = cpu_baseline(wl)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -161,6 +161,21 @@ int64_t adpsgd_iteration(adpsgd_t h);
  * learner order).  Asynchronous.                                               */
 int adpsgd_average(adpsgd_t h, float* dev_out);
 
+/* Per-phase GPU time of a step, taken with HIP events recorded on the handle's
+ * stream at every change of phase (no host synchronisation inside the step).
+ * Phases: 0 minibatch staging + bf16 weight copy, 1 time-batched GEMMs,
+ * 2 recurrent forward steps, 3 recurrent backward steps, 4 softmax
+ * cross-entropy, 5 bias-gradient column sums, 6 mixing + update.
+ * adpsgd_profile waits for the stream, reports the totals over all steps since
+ * profiling was switched on or last read, and starts a new total:
+ * host_ms[7] GPU milliseconds, host_launches[7] kernel launches, host_work[7]
+ * algorithmic work (flops 2*M*N*K summed for phases 1-3; bytes, 12 per active
+ * learner and element, for phase 6; 0 elsewhere).  Any pointer may be NULL.
+ * Each change of phase costs one HIP event; they are kept until destroy.        */
+#define ADPSGD_PHASES 7
+int adpsgd_set_profiling(adpsgd_t h, int enable);
+int adpsgd_profile(adpsgd_t h, float* host_ms, int32_t* host_launches, double* host_work);
+
 /* Release the handle (host memory only; the workspace stays the caller's).     */
 void adpsgd_destroy(adpsgd_t h);
 

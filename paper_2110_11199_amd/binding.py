@@ -9,6 +9,8 @@ import ctypes as C
 import os
 
 import numpy as np
+import torch  # noqa: F401  -- first: the library must bind to the HIP runtime that PyTorch has loaded,
+#                              or its device pointers and streams would belong to another runtime instance
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libadpsgd.so")
@@ -56,6 +58,8 @@ _lib.adpsgd_schedule_of.argtypes = [C.c_int32, C.c_uint64, C.c_float, C.c_int32,
 _lib.adpsgd_iteration.argtypes = [_vp]
 _lib.adpsgd_iteration.restype = _i64
 _lib.adpsgd_average.argtypes = [_vp, _vp]
+_lib.adpsgd_set_profiling.argtypes = [_vp, C.c_int]
+_lib.adpsgd_profile.argtypes = [_vp, C.POINTER(C.c_float), _i32p, C.POINTER(C.c_double)]
 _lib.adpsgd_destroy.argtypes = [_vp]
 _lib.adpsgd_destroy.restype = None
 _lib.adpsgd_last_error.restype = C.c_char_p
@@ -65,7 +69,8 @@ _lib.adpsgd_gemm.argtypes = [C.c_int] * 7 + [_vp, _i64, _i64, _vp, _i64, _i64, _
 EXPORTS = ["adpsgd_workspace_bytes", "adpsgd_create", "adpsgd_step", "adpsgd_params", "adpsgd_set_params",
            "adpsgd_grads", "adpsgd_losses", "adpsgd_param_count", "adpsgd_layout_count", "adpsgd_layout",
            "adpsgd_schedule", "adpsgd_schedule_of", "adpsgd_iteration", "adpsgd_average", "adpsgd_destroy",
-           "adpsgd_last_error", "adpsgd_gemm"]
+           "adpsgd_last_error", "adpsgd_gemm", "adpsgd_set_profiling", "adpsgd_profile"]
+PHASES = ["stage_cast", "batched_gemm", "recurrent_fwd", "recurrent_bwd", "softmax_ce", "bias_colsum", "mix_update"]
 
 
 class AdpsgdError(RuntimeError):
@@ -156,6 +161,17 @@ def adpsgd_iteration(h):
 
 def adpsgd_average(h, dev_out_ptr):
     _check(_lib.adpsgd_average(h, dev_out_ptr))
+
+
+def adpsgd_set_profiling(h, enable):
+    _check(_lib.adpsgd_set_profiling(h, int(enable)))
+
+
+def adpsgd_profile(h):
+    n = len(PHASES)
+    ms, cnt, work = (C.c_float * n)(), (C.c_int32 * n)(), (C.c_double * n)()
+    _check(_lib.adpsgd_profile(h, ms, cnt, work))
+    return {PHASES[i]: {"ms": ms[i], "launches": cnt[i], "work": work[i]} for i in range(n)}
 
 
 def adpsgd_destroy(h):

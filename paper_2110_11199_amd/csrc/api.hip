@@ -80,7 +80,17 @@ struct Carver {
 
 }  // namespace
 
+struct Profiler {
+    bool on = false;
+    std::vector<hipEvent_t> ev;        // ev[j] opens segment j; ev[j+1] closes it
+    std::vector<int> seg_phase;
+    int cur = -1;
+    int launches[ADPSGD_PHASES];
+    double work[ADPSGD_PHASES];
+};
+
 struct adpsgd_handle {
+    Profiler prof;
     adpsgd_config cfg;
     hipStream_t stream;
     int L, D, H, T, B, I, C, Bn, layers, F, ldx;
@@ -198,7 +208,32 @@ size_t plan(adpsgd_handle* h, void* base) {
     return w.used;
 }
 
+// Marks the start of work belonging to `phase` (-1: end of the step).
+int mark(adpsgd_handle* h, int phase, int launches = 0, double work = 0.0) {
+    Profiler& p = h->prof;
+    if (!p.on) return ADPSGD_OK;
+    if (phase >= 0) { p.launches[phase] += launches; p.work[phase] += work; }
+    if (phase == p.cur) return ADPSGD_OK;
+    const size_t need = p.seg_phase.size() + 1;     // events recorded so far + this one
+    while (p.ev.size() < need) {
+        hipEvent_t e;
+        HIPCHK(hipEventCreate(&e), "event create");
+        p.ev.push_back(e);
+    }
+    HIPCHK(hipEventRecord(p.ev[need - 1], h->stream), "event record");
+    p.seg_phase.push_back(phase);                    // phase of the segment this event opens
+    p.cur = phase;
+    return ADPSGD_OK;
+}
+
+void prof_reset(adpsgd_handle* h) {
+    Profiler& p = h->prof;
+    p.seg_phase.clear(); p.cur = -1;
+    for (int i = 0; i < ADPSGD_PHASES; ++i) { p.launches[i] = 0; p.work[i] = 0.0; }
+}
+
 int gemm(adpsgd_handle* h, const GemmDesc& d, const char* what) {
+    if (int rc = mark(h, 1, 1, 2.0 * d.M * d.N * d.K * d.groupsI * d.groupsD)) return rc;
     HIPCHK(launch_gemm(d, h->stream), what);
     return ADPSGD_OK;
 }
@@ -211,6 +246,7 @@ int compute_gradients(adpsgd_handle* h, const float* at, const void* const* batc
     hipStream_t s = h->stream;
     // weights as GEMM operands: the fp32 models themselves, or their bf16 copy
     const char* wbase = (const char*)at;
+    if (int rc = mark(h, 0, prec ? 2 : 1)) return rc;
     if (prec) {
         HIPCHK(launch_cast_bf16(at, h->shadow, (int64_t)L * Pp, s), "cast weights to bf16");
         wbase = (const char*)h->shadow;
@@ -251,6 +287,7 @@ int compute_gradients(adpsgd_handle* h, const float* at, const void* const* batc
         r.c = Cb(l); r.sCi = M * DH;
         r.y = Y(l); r.sYi = M * DH;
         r.wh = W(h->ix_wh[l]); r.sWi = Pp; r.sWd = (int64_t)4 * H * H;
+        if (int rc = mark(h, 2, T, 2.0 * B * H * 4 * H * (T - 1) * L * D)) return rc;
         for (int t = 0; t < T; ++t) {
             r.step = t;
             HIPCHK(launch_rec_forward(r, s), "recurrent forward step");
@@ -285,6 +322,7 @@ int compute_gradients(adpsgd_handle* h, const float* at, const void* const* batc
     sm.precision = prec; sm.L = L; sm.rows = M; sm.C = C;
     sm.logits = h->logits; sm.sLi = M * C; sm.y = h->labels; sm.sYi = M;
     sm.dlogits = h->dlogits; sm.sDi = M * C; sm.row_loss = h->row_loss; sm.loss = h->loss;
+    if (int rc = mark(h, 4, 2)) return rc;
     HIPCHK(launch_softmax_ce(sm, s), "softmax cross-entropy");
 
     // ---- backward: output layer(s) ----
@@ -297,6 +335,7 @@ int compute_gradients(adpsgd_handle* h, const float* at, const void* const* batc
     g.C = Gr(h->ix_wo); g.ldc = F; g.sCi = Pp;
     g.groupsI = L; g.groupsD = 1;
     if (int rc = gemm(h, g, "dW_o GEMM")) return rc;
+    if (int rc = mark(h, 5, 1)) return rc;
     HIPCHK(launch_colsum(prec, h->dlogits, C, M * C, M, C, Gr(h->ix_bo), Pp, L, s), "db_o");
     // d(z) = dlogits W_o
     g = GemmDesc{};
@@ -316,6 +355,7 @@ int compute_gradients(adpsgd_handle* h, const float* at, const void* const* batc
         g.C = Gr(h->ix_wp); g.ldc = DH; g.sCi = Pp;
         g.groupsI = L; g.groupsD = 1;
         if (int rc = gemm(h, g, "dW_p GEMM")) return rc;
+        if (int rc = mark(h, 5, 1)) return rc;
         HIPCHK(launch_colsum(prec, h->dz, h->Bn, M * h->Bn, M, h->Bn, Gr(h->ix_bp), Pp, L, s), "db_p");
         g = GemmDesc{};
         g.precision = prec; g.a_kc = 1; g.b_kc = 0; g.c_elem = 0;
@@ -340,6 +380,7 @@ int compute_gradients(adpsgd_handle* h, const float* at, const void* const* batc
         r.dy = h->dy; r.sDYi = M * DH;
         r.da = h->da; r.sDAi = M * G4;
         r.dc = h->dc; r.sDCi = (int64_t)B * DH;
+        if (int rc = mark(h, 3, T, 2.0 * B * H * 4 * H * (T - 1) * L * D)) return rc;
         for (int t = 0; t < T; ++t) {
             r.step = t;
             HIPCHK(launch_rec_backward(r, s), "recurrent backward step");
@@ -367,9 +408,11 @@ int compute_gradients(adpsgd_handle* h, const float* at, const void* const* batc
             g.groupsI = L; g.groupsD = D;
             if (int rc = gemm(h, g, "dW_h GEMM")) return rc;
         } else {
+            if (int rc = mark(h, 5, L)) return rc;
             for (int i = 0; i < L; ++i)
                 HIPCHK(hipMemsetAsync(Gr(h->ix_wh[l]) + (size_t)i * Pp, 0, (size_t)G4 * H * 4, s), "zero dW_h");
         }
+        if (int rc = mark(h, 5, 1)) return rc;
         HIPCHK(launch_colsum(prec, h->da, G4, M * G4, M, (int)G4, Gr(h->ix_b[l]), Pp, L, s), "db");
         if (l > 0) {
             // dY_{l-1} = da W_x  (sum over both directions: K = D*4H)
@@ -462,7 +505,13 @@ int adpsgd_step(adpsgd_t h, const void* const* batch_ptrs, float lr) {
         for (int i = 0; i < L; ++i) u.g[i] = h->grads + (size_t)i * h->Ppad;
     }
     for (int i = 0; i < L; ++i) { u.partner[i] = (int16_t)partner[i]; u.active[i] = (int16_t)active[i]; }
+    {
+        int nact = 0;
+        for (int i = 0; i < L; ++i) nact += active[i];
+        if (int rc = mark(h, 6, 1, 12.0 * (double)h->P * nact)) return rc;
+    }
     HIPCHK(launch_update(u, h->stream), "mix + update");
+    if (int rc = mark(h, -1)) return rc;
     if (h->tau == 1) h->cur = 1 - h->cur;
     h->k += 1;
     return ADPSGD_OK;
@@ -530,7 +579,39 @@ int adpsgd_average(adpsgd_t h, float* dev_out) {
     return ADPSGD_OK;
 }
 
-void adpsgd_destroy(adpsgd_t h) { delete h; }
+int adpsgd_set_profiling(adpsgd_t h, int enable) {
+    if (!h) return fail(ADPSGD_EINVAL, "NULL handle");
+    h->prof.on = enable != 0;
+    prof_reset(h);
+    return ADPSGD_OK;
+}
+
+int adpsgd_profile(adpsgd_t h, float* host_ms, int32_t* host_launches, double* host_work) {
+    if (!h) return fail(ADPSGD_EINVAL, "NULL handle");
+    Profiler& p = h->prof;
+    HIPCHK(hipStreamSynchronize(h->stream), "stream sync");
+    float ms[ADPSGD_PHASES] = {0};
+    for (size_t j = 0; j + 1 < p.seg_phase.size(); ++j) {
+        const int ph = p.seg_phase[j];
+        if (ph < 0) continue;
+        float t = 0.f;
+        HIPCHK(hipEventElapsedTime(&t, p.ev[j], p.ev[j + 1]), "event elapsed");
+        ms[ph] += t;
+    }
+    for (int i = 0; i < ADPSGD_PHASES; ++i) {
+        if (host_ms) host_ms[i] = ms[i];
+        if (host_launches) host_launches[i] = p.launches[i];
+        if (host_work) host_work[i] = p.work[i];
+    }
+    prof_reset(h);
+    return ADPSGD_OK;
+}
+
+void adpsgd_destroy(adpsgd_t h) {
+    if (!h) return;
+    for (hipEvent_t e : h->prof.ev) (void)hipEventDestroy(e);
+    delete h;
+}
 
 const char* adpsgd_last_error(void) { return g_err.c_str(); }
 
