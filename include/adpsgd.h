@@ -200,6 +200,10 @@ int adpsgd_gemm(int precision, int a_kmajor, int b_kmajor, int c_is_elem,
                 const float* bias, int64_t strideBias,
                 int groups, void* hip_stream);
 
+/* Tuning knob for benchmarks: force the GEMM tile configuration of this process
+ * (0..5, see csrc/gemm.hip); -1 restores the automatic choice.  Not thread-safe. */
+int adpsgd_gemm_set_variant(int variant);
+
 #ifdef __cplusplus
 }
 #endif

@@ -69,7 +69,8 @@ _lib.adpsgd_gemm.argtypes = [C.c_int] * 7 + [_vp, _i64, _i64, _vp, _i64, _i64, _
 EXPORTS = ["adpsgd_workspace_bytes", "adpsgd_create", "adpsgd_step", "adpsgd_params", "adpsgd_set_params",
            "adpsgd_grads", "adpsgd_losses", "adpsgd_param_count", "adpsgd_layout_count", "adpsgd_layout",
            "adpsgd_schedule", "adpsgd_schedule_of", "adpsgd_iteration", "adpsgd_average", "adpsgd_destroy",
-           "adpsgd_last_error", "adpsgd_gemm", "adpsgd_set_profiling", "adpsgd_profile"]
+           "adpsgd_last_error", "adpsgd_gemm", "adpsgd_set_profiling", "adpsgd_profile",
+           "adpsgd_gemm_set_variant"]
 PHASES = ["stage_cast", "batched_gemm", "recurrent_fwd", "recurrent_bwd", "softmax_ce", "bias_colsum", "mix_update"]
 
 
@@ -172,6 +173,10 @@ def adpsgd_profile(h):
     ms, cnt, work = (C.c_float * n)(), (C.c_int32 * n)(), (C.c_double * n)()
     _check(_lib.adpsgd_profile(h, ms, cnt, work))
     return {PHASES[i]: {"ms": ms[i], "launches": cnt[i], "work": work[i]} for i in range(n)}
+
+
+def adpsgd_gemm_set_variant(v):
+    _check(_lib.adpsgd_gemm_set_variant(int(v)))
 
 
 def adpsgd_destroy(h):

@@ -634,4 +634,10 @@ int adpsgd_gemm(int precision, int a_kmajor, int b_kmajor, int c_is_elem, int M,
     return ADPSGD_OK;
 }
 
+int adpsgd_gemm_set_variant(int variant) {
+    if (variant < -1 || variant > 10) return fail(ADPSGD_EINVAL, "variant must be -1..10");
+    set_gemm_variant(variant);
+    return ADPSGD_OK;
+}
+
 }  // extern "C"

@@ -1,20 +1,32 @@
 // Grouped MFMA GEMM kernels: the time-batched GEMMs of the LSTM gradient
 // (input projections, output layers, weight gradients, input gradients).
+#include <cstdlib>
 #include <type_traits>
 #include "gemm_core.hpp"
+#include "gemm_dma.hpp"
 #include "kernels.hpp"
 
 namespace adpsgd {
 
-template <typename T, bool AKC, bool BKC, bool CELEM, int VB>
-__global__ __launch_bounds__(256) void gemm_kernel(GemmDesc p) {
+// Workgroup ids are handed to the 8 XCDs round-robin; this maps them back so that each
+// XCD (its own L2) works on a contiguous range of tiles.
+__device__ inline int xcd_contiguous_id(int bid, int nb) {
+    const int q = nb >> 3, r = nb & 7;
+    const int xcd = bid & 7, local = bid >> 3;
+    const int start = xcd < r ? xcd * (q + 1) : r * (q + 1) + (xcd - r) * q;
+    return start + local;
+}
+
+template <typename T, bool AKC, bool BKC, int WM, int WN, int FM, int FN, int VB, int SB>
+__global__ __launch_bounds__(64 * WM * WN, (WM * WN == 4 && FM * FN == 8) ? 2 : 1) void gemm_kernel(GemmDesc p) {
     typedef typename std::conditional<AKC, KcSrc<T>, McSrc<T>>::type ASrc;
     typedef typename std::conditional<BKC, KcSrc<T>, McSrc<T>>::type BSrc;
-    typedef GemmCore<T, ASrc, BSrc, 2, 2, 2, 2, VB> Core;
+    typedef GemmCore<T, ASrc, BSrc, WM, WN, FM, FN, VB, SB> Core;
     __shared__ __attribute__((aligned(16))) char lds[Core::LDS_BYTES];
 
     const int tiles_m = (p.M + Core::BM - 1) / Core::BM;
-    const int tm = blockIdx.x % tiles_m, tn = blockIdx.x / tiles_m;
+    const int id = xcd_contiguous_id(blockIdx.x, gridDim.x);
+    const int tm = id % tiles_m, tn = id / tiles_m;
     const int gi = blockIdx.y / p.groupsD, gd = blockIdx.y % p.groupsD;
     const int m0 = tm * Core::BM, n0 = tn * Core::BN;
     const T* A = (const T*)p.A + gi * p.sAi + gd * p.sAd;
@@ -26,57 +38,153 @@ __global__ __launch_bounds__(256) void gemm_kernel(GemmDesc p) {
     if constexpr (BKC) { b.base = B + (int64_t)n0 * p.ldb; } else { b.base = B + n0; }
     b.ld = p.ldb; b.R = p.N - n0;
 
-    f32x16_t acc[2][2];
+    f32x16_t acc[FM][FN];
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+    for (int i = 0; i < FM; ++i)
 #pragma unroll
-        for (int j = 0; j < 2; ++j)
+        for (int j = 0; j < FN; ++j)
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
     Core::run(acc, a, b, p.K, lds);
 
     const float* bias = p.bias ? p.bias + gi * p.sBiasI + gd * p.sBiasD : nullptr;
     const int64_t coff = gi * p.sCi + gd * p.sCd;
+    const bool celem = p.c_elem != 0;
 #pragma unroll
-    for (int fn = 0; fn < 2; ++fn) {
+    for (int fn = 0; fn < FN; ++fn) {
         const int col = n0 + Core::acc_col(fn);
         if (col >= p.N) continue;
         const float bv = bias ? bias[col] : 0.f;
 #pragma unroll
-        for (int fm = 0; fm < 2; ++fm) {
+        for (int fm = 0; fm < FM; ++fm) {
 #pragma unroll
             for (int i = 0; i < 16; ++i) {
                 const int row = m0 + Core::acc_row(fm, i);
                 if (row >= p.M) continue;
                 const float v = acc[fm][fn][i] + bv;
+#ifdef ADPSGD_DBG_NOEPI
+                if (v != 123456.75f) continue;
+#endif
                 const int64_t o = coff + (int64_t)row * p.ldc + col;
-                if constexpr (CELEM) ((T*)p.C)[o] = Elem<T>::from(v);
+                if (celem) ((T*)p.C)[o] = Elem<T>::from(v);
                 else ((float*)p.C)[o] = v;
             }
         }
     }
 }
 
-template <typename T, bool AKC, bool BKC, bool CELEM, int VB>
-static hipError_t launch_t(const GemmDesc& d, hipStream_t s) {
-    const int tiles_m = (d.M + 127) / 128, tiles_n = (d.N + 127) / 128;
+// Same tile bookkeeping with the direct-to-LDS main loop (both operands K-contiguous,
+// 16-byte aligned rows, K a multiple of the stage length).
+template <typename T, int WM, int WN, int FM, int FN, int SB, int NS, int MINB>
+__global__ __launch_bounds__(64 * WM * WN, MINB) void gemm_dma_kernel(GemmDesc p) {
+    typedef GemmDma<T, KcSrc<T>, KcSrc<T>, WM, WN, FM, FN, SB, NS> Core;
+    __shared__ __attribute__((aligned(1024))) char lds[Core::LDS_BYTES];
+
+    const int tiles_m = (p.M + Core::BM - 1) / Core::BM;
+    const int id = xcd_contiguous_id(blockIdx.x, gridDim.x);
+    const int tm = id % tiles_m, tn = id / tiles_m;
+    const int gi = blockIdx.y / p.groupsD, gd = blockIdx.y % p.groupsD;
+    const int m0 = tm * Core::BM, n0 = tn * Core::BN;
+#ifdef ADPSGD_DBG_TIMING
+    const long long ts = wall_clock64();
+#endif
+    KcSrc<T> a, b;
+    a.base = (const T*)p.A + gi * p.sAi + gd * p.sAd + (int64_t)m0 * p.lda; a.ld = p.lda; a.R = p.M - m0;
+    b.base = (const T*)p.B + gi * p.sBi + gd * p.sBd + (int64_t)n0 * p.ldb; b.ld = p.ldb; b.R = p.N - n0;
+
+    f32x16_t acc[FM][FN];
+#pragma unroll
+    for (int i = 0; i < FM; ++i)
+#pragma unroll
+        for (int j = 0; j < FN; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+    
+#ifdef ADPSGD_DBG_TIMING
+    const long long t0 = wall_clock64();
+#endif
+    Core::run(acc, a, b, p.K, lds);
+#ifdef ADPSGD_DBG_TIMING
+    const long long t1 = wall_clock64();
+#endif
+
+
+    const float* bias = p.bias ? p.bias + gi * p.sBiasI + gd * p.sBiasD : nullptr;
+    const int64_t coff = gi * p.sCi + gd * p.sCd;
+    const bool celem = p.c_elem != 0;
+#pragma unroll
+    for (int fn = 0; fn < FN; ++fn) {
+        const int col = n0 + Core::acc_col(fn);
+        if (col >= p.N) continue;
+        const float bv = bias ? bias[col] : 0.f;
+#pragma unroll
+        for (int fm = 0; fm < FM; ++fm) {
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                const int row = m0 + Core::acc_row(fm, i);
+                if (row >= p.M) continue;
+                const float v = acc[fm][fn][i] + bv;
+#ifdef ADPSGD_DBG_NOEPI
+                if (v != 123456.75f) continue;
+#endif
+                const int64_t o = coff + (int64_t)row * p.ldc + col;
+                if (celem) ((T*)p.C)[o] = Elem<T>::from(v);
+                else ((float*)p.C)[o] = v;
+            }
+        }
+    }
+#ifdef ADPSGD_DBG_TIMING
+    if (threadIdx.x == 0 && p.dbg) {
+        long long* d = p.dbg + ((int64_t)blockIdx.y * gridDim.x + blockIdx.x) * 4;
+        d[0] = ts; d[1] = t0; d[2] = t1; d[3] = wall_clock64();
+    }
+#endif
+}
+
+template <typename T, int WM, int WN, int FM, int FN, int SB, int NS, int MINB>
+static hipError_t launch_dma(const GemmDesc& d, hipStream_t s) {
+    constexpr int BM = 32 * FM * WM, BN = 32 * FN * WN;
+    const int tiles_m = (d.M + BM - 1) / BM, tiles_n = (d.N + BN - 1) / BN;
     dim3 grid((unsigned)(tiles_m * tiles_n), (unsigned)(d.groupsI * d.groupsD));
-    hipLaunchKernelGGL((gemm_kernel<T, AKC, BKC, CELEM, VB>), grid, dim3(256), 0, s, d);
+    hipLaunchKernelGGL((gemm_dma_kernel<T, WM, WN, FM, FN, SB, NS, MINB>), grid, dim3(64 * WM * WN), 0, s, d);
     return hipGetLastError();
 }
 
-template <typename T, int VB>
+template <typename T, bool AKC, bool BKC, int WM, int WN, int FM, int FN, int VB, int SB>
+static hipError_t launch_t(const GemmDesc& d, hipStream_t s) {
+    constexpr int BM = 32 * FM * WM, BN = 32 * FN * WN;
+    const int tiles_m = (d.M + BM - 1) / BM, tiles_n = (d.N + BN - 1) / BN;
+    dim3 grid((unsigned)(tiles_m * tiles_n), (unsigned)(d.groupsI * d.groupsD));
+    hipLaunchKernelGGL((gemm_kernel<T, AKC, BKC, WM, WN, FM, FN, VB, SB>), grid, dim3(64 * WM * WN), 0, s, d);
+    return hipGetLastError();
+}
+
+template <typename T, int WM, int WN, int FM, int FN, int VB, int SB>
 static hipError_t launch_layout(const GemmDesc& d, hipStream_t s) {
-    const int key = (d.a_kc ? 4 : 0) | (d.b_kc ? 2 : 0) | (d.c_elem ? 1 : 0);
+    const int key = (d.a_kc ? 2 : 0) | (d.b_kc ? 1 : 0);
     switch (key) {
-        case 0: return launch_t<T, false, false, false, VB>(d, s);
-        case 1: return launch_t<T, false, false, true, VB>(d, s);
-        case 2: return launch_t<T, false, true, false, VB>(d, s);
-        case 3: return launch_t<T, false, true, true, VB>(d, s);
-        case 4: return launch_t<T, true, false, false, VB>(d, s);
-        case 5: return launch_t<T, true, false, true, VB>(d, s);
-        case 6: return launch_t<T, true, true, false, VB>(d, s);
-        default: return launch_t<T, true, true, true, VB>(d, s);
+        case 0: return launch_t<T, false, false, WM, WN, FM, FN, VB, SB>(d, s);
+        case 1: return launch_t<T, false, true, WM, WN, FM, FN, VB, SB>(d, s);
+        case 2: return launch_t<T, true, false, WM, WN, FM, FN, VB, SB>(d, s);
+        default: return launch_t<T, true, true, WM, WN, FM, FN, VB, SB>(d, s);
+    }
+}
+
+static int g_variant = -1;   // tuning knob: forces a tile configuration (-1 = automatic)
+void set_gemm_variant(int v) { g_variant = v; }
+
+// Tile configurations.  0: 128x128 tile, 4 waves, 64-byte stages (also the only one with
+// 8-byte operand loads); 1: same with 128-byte stages; 2/3: 256x128, 4 waves (wave tile
+// 128x64), 64/128-byte stages; 4/5: 256x256, 8 waves (wave tile 128x64), 64/128-byte stages.
+template <typename T>
+static hipError_t launch_variant(int v, const GemmDesc& d, hipStream_t s) {
+    switch (v) {
+        case 1: return launch_layout<T, 2, 2, 2, 2, 16, 128>(d, s);
+        case 2: return launch_layout<T, 2, 2, 4, 2, 16, 64>(d, s);
+        case 3: return launch_layout<T, 2, 2, 4, 2, 16, 128>(d, s);
+        case 4: return launch_layout<T, 2, 4, 4, 2, 16, 64>(d, s);
+        case 5: return launch_layout<T, 2, 4, 4, 2, 16, 128>(d, s);
+        default: return launch_layout<T, 2, 2, 2, 2, 16, 64>(d, s);
     }
 }
 
@@ -91,11 +199,29 @@ hipError_t launch_gemm(const GemmDesc& d, hipStream_t s) {
     const int quad = 4 * esz;    // every operand must allow loads of 4 elements
     if (!aligned_to(d.A, d.lda, d.sAi, d.sAd, esz, quad) || !aligned_to(d.B, d.ldb, d.sBi, d.sBd, esz, quad))
         return hipErrorInvalidValue;
-    if (d.precision == 0) return launch_layout<float, 16>(d, s);
+    if (d.precision == 0) return launch_variant<float>(g_variant >= 0 && g_variant <= 5 ? g_variant : 0, d, s);
     bool wide = true;
     if (d.a_kc && !aligned_to(d.A, d.lda, d.sAi, d.sAd, esz, 16)) wide = false;
     if (d.b_kc && !aligned_to(d.B, d.ldb, d.sBi, d.sBd, esz, 16)) wide = false;
-    return wide ? launch_layout<bf16_t, 16>(d, s) : launch_layout<bf16_t, 8>(d, s);
+    if (!wide) return launch_layout<bf16_t, 2, 2, 2, 2, 8, 64>(d, s);
+    int v = g_variant;
+    if (v < 0) {
+        // 256x256 tiles once they fill the 256 CUs (they halve the operand bytes loaded per flop);
+        // direct-to-LDS loads when both operands are K-contiguous and K is a multiple of the stage.
+        const int64_t big_tiles = (int64_t)((d.M + 255) / 256) * ((d.N + 255) / 256) * d.groupsI * d.groupsD;
+        if (big_tiles >= 256) v = (d.a_kc && d.b_kc && d.K % 64 == 0) ? 10 : 5;
+        else v = 0;
+    }
+    if (v >= 6 && d.a_kc && d.b_kc && d.K % 64 == 0) {
+        switch (v) {
+            case 6: return launch_dma<bf16_t, 2, 4, 4, 2, 64, 4, 1>(d, s);
+            case 7: return launch_dma<bf16_t, 2, 4, 2, 2, 64, 3, 2>(d, s);
+            case 8: return launch_dma<bf16_t, 4, 2, 2, 2, 64, 3, 2>(d, s);
+            case 9: return launch_dma<bf16_t, 2, 2, 2, 2, 64, 4, 2>(d, s);
+            default: return launch_dma<bf16_t, 2, 4, 4, 2, 128, 2, 1>(d, s);
+        }
+    }
+    return launch_variant<bf16_t>(v > 5 ? 5 : v, d, s);
 }
 
 }  // namespace adpsgd

@@ -2,14 +2,14 @@
 //
 // C[m][n] = sum_k A(m,k) * B(n,k).  A workgroup of WM x WN waves owns a
 // (32*FM*WM) x (32*FN*WN) tile of C; each wave owns FM x FN MFMA 32x32 tiles.
-// K is consumed in stages of 64 bytes per operand row (32 bf16 / 16 fp32),
+// K is consumed in stages of SB = 64 or 128 bytes per operand row,
 // double-buffered in LDS with a register prefetch of the next stage.
 //
 // An operand comes from global memory in one of two storage orders:
 //   "kc"  K contiguous:  element (r,k) at row(r)[k]         (rows may be gathered)
 //   "mc"  rows contiguous: element (r,k) at base[k*ld + r]  (transposed on the way
 //         into LDS, so that C = A'*B and C = A*B need no transposed copies)
-// LDS layouts: kc tiles are row-major with an 80-byte row stride (16-byte
+// LDS layouts: kc tiles are row-major with a row stride of SB+16 bytes (16-byte
 // fragment reads hit distinct banks); mc tiles are stored as planes of
 // 4-element k-granules, plane q holding k = 4q..4q+3 of every row, so that the
 // transposing store is contiguous per lane and fragment reads are contiguous
@@ -26,13 +26,15 @@
 
 namespace adpsgd {
 
-constexpr int kStageBytes = 64;       // bytes of K per operand row per LDS stage
-constexpr int kKcStride = 80;         // LDS row stride of a kc tile
+// SB (template parameter below) = bytes of K per operand row per LDS stage: 64 or 128.
+// LDS row stride of a kc tile = SB + 16.
 
 template <typename T> struct KcSrc {  // K-contiguous rows base + r*ld, r < R
     static constexpr bool kc = true;
     const T* base; int64_t ld; int R;
     __device__ const T* row(int r) const { return r < R ? base + (int64_t)r * ld : nullptr; }
+    __device__ const T* row_nocheck(int r) const { return base + (int64_t)r * ld; }
+    __device__ bool full(int rows) const { return R >= rows; }
 };
 
 // Rows of a [4][H] gate-blocked matrix gathered so that tile row n holds gate
@@ -45,31 +47,37 @@ template <typename T> struct GateSrc {
         int gate = (n & 127) >> 5;
         return u < H ? base + ((int64_t)gate * H + u) * ld : nullptr;
     }
+    __device__ const T* row_nocheck(int n) const {
+        return base + ((int64_t)((n & 127) >> 5) * H + u0 + 32 * (n >> 7) + (n & 31)) * ld;
+    }
+    __device__ bool full(int rows) const { return u0 + rows / 4 <= H; }
 };
 
 template <typename T> struct McSrc {  // element (r,k) at base[k*ld + r], r < R
     static constexpr bool kc = false;
     const T* base; int64_t ld; int R;
+    __device__ bool full(int rows) const { return R >= rows; }
 };
 
-template <typename T, int ROWS, bool KC> struct LdsTile;
+template <typename T, int ROWS, int SB, bool KC> struct LdsTile;
 
-template <typename T, int ROWS> struct LdsTile<T, ROWS, true> {
-    static constexpr int BYTES = ROWS * kKcStride;
+template <typename T, int ROWS, int SB> struct LdsTile<T, ROWS, SB, true> {
+    static constexpr int STRIDE = SB + 16;
+    static constexpr int BYTES = ROWS * STRIDE;
     __device__ static uint4 frag(const char* lds, int row, int ch) {
-        return *(const uint4*)(lds + row * kKcStride + ch * 16);
+        return *(const uint4*)(lds + row * STRIDE + ch * 16);
     }
 };
-template <int ROWS> struct LdsTile<bf16_t, ROWS, false> {
-    static constexpr int BYTES = ROWS * kStageBytes;
+template <int ROWS, int SB> struct LdsTile<bf16_t, ROWS, SB, false> {
+    static constexpr int BYTES = ROWS * SB;
     __device__ static uint4 frag(const char* lds, int row, int ch) {
         uint2 lo = *(const uint2*)(lds + (2 * ch) * (ROWS * 8) + row * 8);
         uint2 hi = *(const uint2*)(lds + (2 * ch + 1) * (ROWS * 8) + row * 8);
         return make_uint4(lo.x, lo.y, hi.x, hi.y);
     }
 };
-template <int ROWS> struct LdsTile<float, ROWS, false> {
-    static constexpr int BYTES = ROWS * kStageBytes;
+template <int ROWS, int SB> struct LdsTile<float, ROWS, SB, false> {
+    static constexpr int BYTES = ROWS * SB;
     __device__ static uint4 frag(const char* lds, int row, int ch) {
         return *(const uint4*)(lds + ch * (ROWS * 16) + row * 16);
     }
@@ -77,14 +85,32 @@ template <int ROWS> struct LdsTile<float, ROWS, false> {
 
 // ---- global -> register -> LDS loaders -------------------------------------
 
-template <typename T, int ROWS, int VB, int NT> struct KcLoader {
+template <typename T, int ROWS, int VB, int NT, int SB> struct KcLoader {
+    static constexpr int STRIDE = SB + 16;
     static constexpr int EPV = VB / (int)sizeof(T);          // elements per vector load
-    static constexpr int CPR = kStageBytes / VB;             // vectors per tile row
+    static constexpr int CPR = SB / VB;                      // vectors per tile row
     static constexpr int CHUNKS = ROWS * CPR;
     static constexpr int PER = (CHUNKS + NT - 1) / NT;
     static constexpr int WORDS = VB / 4;
     uint32_t regs[PER][WORDS];
 
+    // Whole stage inside the matrix (all tile rows valid, k0 + stage <= K): no guards, no branches.
+    template <class Src> __device__ void load_full(const Src& src, int k0, int tid) {
+#pragma unroll
+        for (int j = 0; j < PER; ++j) {
+            const int c = tid + j * NT;
+            if (CHUNKS % NT != 0 && c >= CHUNKS) continue;
+            const int row = c / CPR, kc = c % CPR;
+            const T* p = src.row_nocheck(row) + k0 + kc * EPV;
+            if constexpr (VB == 16) {
+                const uint4 v = *(const uint4*)p;
+                regs[j][0] = v.x; regs[j][1] = v.y; regs[j][2] = v.z; regs[j][3] = v.w;
+            } else {
+                const uint2 v = *(const uint2*)p;
+                regs[j][0] = v.x; regs[j][1] = v.y;
+            }
+        }
+    }
     template <class Src> __device__ void load(const Src& src, int k0, int K, int tid) {
 #pragma unroll
         for (int j = 0; j < PER; ++j) {
@@ -121,21 +147,40 @@ template <typename T, int ROWS, int VB, int NT> struct KcLoader {
             int c = tid + j * NT;
             if (CHUNKS % NT != 0 && c >= CHUNKS) continue;
             int row = c / CPR, kc = c % CPR;
-            char* dst = lds + row * kKcStride + kc * VB;
+            char* dst = lds + row * STRIDE + kc * VB;
             if constexpr (VB == 16) *(uint4*)dst = make_uint4(regs[j][0], regs[j][1], regs[j][2], regs[j][3]);
             else *(uint2*)dst = make_uint2(regs[j][0], regs[j][1]);
         }
     }
 };
 
-template <typename T, int ROWS, int NT> struct McLoader {
-    static constexpr int KT = kStageBytes / (int)sizeof(T);   // k per stage
+template <typename T, int ROWS, int NT, int SB> struct McLoader {
+    static constexpr int KT = SB / (int)sizeof(T);            // k per stage
     static constexpr int RQ = ROWS / 4;
     static constexpr int SUBS = (KT / 4) * RQ;                // 4(k) x 4(r) sub-blocks
     static constexpr int PER = (SUBS + NT - 1) / NT;
     static constexpr int WORDS = (int)sizeof(T);              // 32-bit words per 4 elements
     uint32_t regs[PER][4][WORDS];
 
+    template <class Src> __device__ void load_full(const Src& src, int k0, int tid) {
+#pragma unroll
+        for (int j = 0; j < PER; ++j) {
+            const int s = tid + j * NT;
+            if (SUBS % NT != 0 && s >= SUBS) continue;
+            const int kq = s / RQ, r = (s % RQ) * 4;
+            const T* p = src.base + (int64_t)(k0 + kq * 4) * src.ld + r;
+#pragma unroll
+            for (int jj = 0; jj < 4; ++jj) {
+                if constexpr (sizeof(T) == 4) {
+                    const uint4 v = *(const uint4*)(p + jj * src.ld);
+                    regs[j][jj][0] = v.x; regs[j][jj][1] = v.y; regs[j][jj][2] = v.z; regs[j][jj][3] = v.w;
+                } else {
+                    const uint2 v = *(const uint2*)(p + jj * src.ld);
+                    regs[j][jj][0] = v.x; regs[j][jj][1] = v.y;
+                }
+            }
+        }
+    }
     template <class Src> __device__ void load(const Src& src, int k0, int K, int tid) {
 #pragma unroll
         for (int j = 0; j < PER; ++j) {
@@ -200,9 +245,9 @@ template <typename T, int ROWS, int NT> struct McLoader {
     }
 };
 
-template <typename T, int ROWS, int VB, int NT, bool KC> struct LoaderSel;
-template <typename T, int ROWS, int VB, int NT> struct LoaderSel<T, ROWS, VB, NT, true> { typedef KcLoader<T, ROWS, VB, NT> type; };
-template <typename T, int ROWS, int VB, int NT> struct LoaderSel<T, ROWS, VB, NT, false> { typedef McLoader<T, ROWS, NT> type; };
+template <typename T, int ROWS, int VB, int NT, int SB, bool KC> struct LoaderSel;
+template <typename T, int ROWS, int VB, int NT, int SB> struct LoaderSel<T, ROWS, VB, NT, SB, true> { typedef KcLoader<T, ROWS, VB, NT, SB> type; };
+template <typename T, int ROWS, int VB, int NT, int SB> struct LoaderSel<T, ROWS, VB, NT, SB, false> { typedef McLoader<T, ROWS, NT, SB> type; };
 
 template <typename T> __device__ inline void mma_chunk(f32x16_t& acc, const uint4& a, const uint4& b);
 template <> __device__ inline void mma_chunk<bf16_t>(f32x16_t& acc, const uint4& a, const uint4& b) {
@@ -215,12 +260,12 @@ template <> __device__ inline void mma_chunk<float>(f32x16_t& acc, const uint4& 
     acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__builtin_bit_cast(float, a.w), __builtin_bit_cast(float, b.w), acc, 0, 0, 0);
 }
 
-template <typename T, class ASrc, class BSrc, int WM, int WN, int FM, int FN, int VB>
+template <typename T, class ASrc, class BSrc, int WM, int WN, int FM, int FN, int VB, int SB = 64>
 struct GemmCore {
     static constexpr int BM = 32 * FM * WM, BN = 32 * FN * WN, NT = 64 * WM * WN;
-    static constexpr int KT = kStageBytes / (int)sizeof(T);
-    typedef LdsTile<T, BM, ASrc::kc> ATile;
-    typedef LdsTile<T, BN, BSrc::kc> BTile;
+    static constexpr int KT = SB / (int)sizeof(T);
+    typedef LdsTile<T, BM, SB, ASrc::kc> ATile;
+    typedef LdsTile<T, BN, SB, BSrc::kc> BTile;
     static constexpr int STAGE_BYTES = ATile::BYTES + BTile::BYTES;
     static constexpr int LDS_BYTES = 2 * STAGE_BYTES;
 
@@ -230,12 +275,14 @@ struct GemmCore {
         const int lane = tid & 63, wave = tid >> 6;
         const int wave_m = wave / WN, wave_n = wave % WN;
         const int r = lane & 31, g = lane >> 5;
-        typename LoaderSel<T, BM, VB, NT, ASrc::kc>::type la;
-        typename LoaderSel<T, BN, VB, NT, BSrc::kc>::type lb;
+        typename LoaderSel<T, BM, VB, NT, SB, ASrc::kc>::type la;
+        typename LoaderSel<T, BN, VB, NT, SB, BSrc::kc>::type lb;
         const int nk = (K + KT - 1) / KT;
         if (nk <= 0) return;
-        la.load(a, 0, K, tid);
-        lb.load(b, 0, K, tid);
+        // stages that lie wholly inside both operands are loaded without guards
+        const int nk_full = (a.full(BM) && b.full(BN)) ? K / KT : 0;
+        if (nk_full > 0) { la.load_full(a, 0, tid); lb.load_full(b, 0, tid); }
+        else { la.load(a, 0, K, tid); lb.load(b, 0, K, tid); }
         la.store(lds, tid);
         lb.store(lds + ATile::BYTES, tid);
         __syncthreads();
@@ -243,12 +290,19 @@ struct GemmCore {
             char* cur = lds + (kt & 1) * STAGE_BYTES;
             char* nxt = lds + ((kt + 1) & 1) * STAGE_BYTES;
             const bool more = kt + 1 < nk;
-            if (more) {
+#ifdef ADPSGD_DBG_NOLOAD
+            if (false) {
+#else
+            if (kt + 1 < nk_full) {
+#endif
+                la.load_full(a, (kt + 1) * KT, tid);
+                lb.load_full(b, (kt + 1) * KT, tid);
+            } else if (more) {
                 la.load(a, (kt + 1) * KT, K, tid);
                 lb.load(b, (kt + 1) * KT, K, tid);
             }
 #pragma unroll
-            for (int c = 0; c < 2; ++c) {
+            for (int c = 0; c < SB / 32; ++c) {
                 const int ch = 2 * c + g;
                 uint4 af[FM], bfr[FN];
 #pragma unroll
@@ -260,11 +314,15 @@ struct GemmCore {
 #pragma unroll
                     for (int fn = 0; fn < FN; ++fn) mma_chunk<T>(acc[fm][fn], af[fm], bfr[fn]);
             }
+#ifndef ADPSGD_DBG_NOSTORE
             if (more) {
                 la.store(nxt, tid);
                 lb.store(nxt + ATile::BYTES, tid);
             }
+#endif
+#ifndef ADPSGD_DBG_NOBARRIER
             __syncthreads();
+#endif
         }
     }
 

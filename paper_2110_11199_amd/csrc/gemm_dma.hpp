@@ -1,0 +1,143 @@
+// MFMA GEMM main loop fed by direct global->LDS loads (gfx950 global_load_lds_dwordx4):
+// no staging registers, no LDS store instructions, NS LDS stages in flight.
+//
+// Same contract as GemmCore (gemm_core.hpp): C[m][n] = sum_k A(m,k) B(n,k) for a
+// (32*FM*WM) x (32*FN*WN) workgroup tile, both operands K-contiguous in memory,
+// K a multiple of the stage length.  Rows past the end of an operand are clamped to
+// its last row (their products land in accumulator rows/columns the caller discards),
+// so no guard and no zero fill is needed.
+//
+// A wave-wide direct load writes lane l's 16 bytes to LDS at base + 16*l, i.e. 1 KB
+// contiguous per instruction.  A tile is therefore stored row-major WITHOUT padding
+// (row = SB bytes) and bank conflicts are avoided by a swizzle applied on the global
+// side: the 16-byte slot s of row r holds chunk s ^ swz(r) of that row, with
+// swz(r) = (r / (256/SB)) mod (SB/16), so that any 16 rows read at one chunk index hit 16
+// different 16-byte bank groups.
+#pragma once
+#include "gemm_core.hpp"
+
+namespace adpsgd {
+
+typedef __attribute__((address_space(3))) void lds_void_t;
+typedef __attribute__((address_space(1))) const void glb_void_t;
+
+// One wave-wide direct load: lane l's 16 bytes at gptr land in LDS at lds_addr + 16*l.
+// Issued through inline asm so that the compiler's wait-count insertion does not see it
+// (it would drain all loads before every LDS read); the main loop places its own waits.
+__device__ inline void dma16_(const void* gptr, uint32_t lds_addr_uniform) {
+    asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off"
+                 :: "v"(gptr), "s"(lds_addr_uniform) : "memory", "m0");
+}
+__device__ inline uint32_t lds_addr_(const void* p) {
+    return (uint32_t)(uintptr_t)(lds_void_t*)p;
+}
+
+template <int SB> __device__ inline int swz_(int r) { return (r / (256 / SB)) & (SB / 16 - 1); }
+
+template <typename T, class ASrc, class BSrc, int WM, int WN, int FM, int FN, int SB, int NS>
+struct GemmDma {
+    static constexpr int BM = 32 * FM * WM, BN = 32 * FN * WN, NT = 64 * WM * WN;
+    static constexpr int KT = SB / (int)sizeof(T);
+    static constexpr int CPR = SB / 16;                       // 16-byte chunks per tile row
+    static constexpr int A_BYTES = BM * SB, B_BYTES = BN * SB;
+    static constexpr int STAGE_BYTES = A_BYTES + B_BYTES;
+    static constexpr int LDS_BYTES = NS * STAGE_BYTES;
+    static constexpr int LA = BM * CPR / NT, LB = BN * CPR / NT;   // loads per thread per stage
+    static_assert((BM * CPR) % NT == 0 && (BN * CPR) % NT == 0, "tile must divide over the workgroup");
+    static_assert(ASrc::kc && BSrc::kc, "direct loads need K-contiguous operands");
+
+    template <int ROWS, int L, class Src>
+    __device__ static void issue(const Src& src, int k0, char* lds_tile, int tid) {
+        const int wave_base = (tid & ~63);
+#pragma unroll
+        for (int j = 0; j < L; ++j) {
+            const int c = tid + j * NT;
+            int row = c / CPR;
+            const int slot = c % CPR;
+            const int chunk = slot ^ swz_<SB>(row);
+            row = row < src.R ? row : src.R - 1;
+            const T* p = src.row_nocheck(row) + k0 + chunk * (16 / (int)sizeof(T));
+            // wave-uniform destination; lane l lands at dst + 16*l
+            const uint32_t dst = __builtin_amdgcn_readfirstlane(lds_addr_(lds_tile) + (uint32_t)(wave_base + j * NT) * 16u);
+            dma16_(p, dst);
+        }
+    }
+
+    __device__ static uint4 frag(const char* tile, int row, int ch) {
+        return *(const uint4*)(tile + row * SB + ((ch ^ swz_<SB>(row)) * 16));
+    }
+
+    template <int N> __device__ static void wait_vm() {
+        if constexpr (N == 0) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        else if constexpr (N == 2) asm volatile("s_waitcnt vmcnt(2)" ::: "memory");
+        else if constexpr (N == 3) asm volatile("s_waitcnt vmcnt(3)" ::: "memory");
+        else if constexpr (N == 4) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
+        else if constexpr (N == 6) asm volatile("s_waitcnt vmcnt(6)" ::: "memory");
+        else if constexpr (N == 8) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+        else if constexpr (N == 9) asm volatile("s_waitcnt vmcnt(9)" ::: "memory");
+        else if constexpr (N == 12) asm volatile("s_waitcnt vmcnt(12)" ::: "memory");
+        else if constexpr (N == 16) asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
+        else if constexpr (N == 18) asm volatile("s_waitcnt vmcnt(18)" ::: "memory");
+        else if constexpr (N == 24) asm volatile("s_waitcnt vmcnt(24)" ::: "memory");
+        else static_assert(N < 0, "add the immediate");
+    }
+
+    // K must be a multiple of KT (checked by the host).  acc must be initialised.
+    __device__ static void run(f32x16_t (&acc)[FM][FN], const ASrc& a, const BSrc& b, int K, char* lds) {
+        constexpr int LPT = LA + LB;
+        const int tid = threadIdx.x;
+        const int lane = tid & 63, wave = tid >> 6;
+        const int wave_m = wave / WN, wave_n = wave % WN;
+        const int r = lane & 31, g = lane >> 5;
+        const int nk = K / KT;
+#pragma unroll
+        for (int s = 0; s < NS - 1; ++s) {
+            if (s < nk) {
+                issue<BM, LA>(a, s * KT, lds + s * STAGE_BYTES, tid);
+                issue<BN, LB>(b, s * KT, lds + s * STAGE_BYTES + A_BYTES, tid);
+            }
+        }
+        for (int kt = 0; kt < nk; ++kt) {
+            // tiles issued after kt and still allowed in flight: min(NS-2, nk-1-kt)
+            const int later = nk - 1 - kt;
+            if (later >= NS - 2) wait_vm<(NS - 2) * LPT>();
+            else if (NS > 3 && later == 1) wait_vm<LPT>();
+            else wait_vm<0>();
+            __builtin_amdgcn_s_barrier();      // every wave's share of tile kt has landed; stage (kt-1)%NS is free
+            const int nt = kt + NS - 1;
+            if (nt < nk) {
+                char* st = lds + (nt % NS) * STAGE_BYTES;
+                issue<BM, LA>(a, nt * KT, st, tid);
+                issue<BN, LB>(b, nt * KT, st + A_BYTES, tid);
+            }
+            const char* cur = lds + (kt % NS) * STAGE_BYTES;
+#ifdef ADPSGD_DBG_NOMMA
+            if (K > 0) continue;
+#endif
+#pragma unroll
+            for (int c = 0; c < SB / 32; ++c) {
+                const int ch = 2 * c + g;
+                uint4 af[FM], bfr[FN];
+#pragma unroll
+                for (int fm = 0; fm < FM; ++fm) af[fm] = frag(cur, (wave_m * FM + fm) * 32 + r, ch);
+#pragma unroll
+                for (int fn = 0; fn < FN; ++fn) bfr[fn] = frag(cur + A_BYTES, (wave_n * FN + fn) * 32 + r, ch);
+#pragma unroll
+                for (int fm = 0; fm < FM; ++fm)
+#pragma unroll
+                    for (int fn = 0; fn < FN; ++fn) mma_chunk<T>(acc[fm][fn], af[fm], bfr[fn]);
+            }
+        }
+    }
+
+    __device__ static int acc_row(int fm, int i) {
+        const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+        return ((wave / WN) * FM + fm) * 32 + 8 * (i >> 2) + 4 * (lane >> 5) + (i & 3);
+    }
+    __device__ static int acc_col(int fn) {
+        const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+        return ((wave % WN) * FN + fn) * 32 + (lane & 31);
+    }
+};
+
+}  // namespace adpsgd

@@ -17,10 +17,14 @@ struct GemmDesc {
     void* C; int64_t ldc, sCi, sCd;
     const float* bias; int64_t sBiasI, sBiasD;
     int groupsI, groupsD;
+#ifdef ADPSGD_DBG_TIMING
+    long long* dbg;
+#endif
 };
 // Returns hipSuccess, or hipErrorInvalidValue when the operands do not meet the
 // alignment rules (rows and strides multiples of 4 elements).
 hipError_t launch_gemm(const GemmDesc& d, hipStream_t s);
+void set_gemm_variant(int v);
 
 // ---- fused mixing + SGD update ------------------------------------------------
 struct UpdateDesc {
