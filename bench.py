@@ -126,12 +126,16 @@ def main():
     ap.add_argument("--workload", default="cfg4", choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5"])
     ap.add_argument("--mix-steps", type=int, default=20, help="timed steps of the cfg5 mixing/update leg (0 = skip)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--tune", type=int, default=None, help="forwarded to adpsgd_gemm_set_variant (tuning only)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (L learners are replicas resident on one MI355X); "
               "--gpus %d is not supported" % args.gpus, file=sys.stderr)
         sys.exit(2)
     from paper_2110_11199_amd import synth
+    if args.tune is not None:
+        from paper_2110_11199_amd import binding as _Bd
+        _Bd.adpsgd_gemm_set_variant(args.tune)
     wl = synth.WORKLOADS[args.workload]
     out = {"metric": METRIC, "unit": "frames/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
            "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "data": "synthetic"}

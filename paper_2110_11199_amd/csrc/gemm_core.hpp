@@ -34,6 +34,7 @@ template <typename T> struct KcSrc {  // K-contiguous rows base + r*ld, r < R
     const T* base; int64_t ld; int R;
     __device__ const T* row(int r) const { return r < R ? base + (int64_t)r * ld : nullptr; }
     __device__ const T* row_nocheck(int r) const { return base + (int64_t)r * ld; }
+    __device__ const T* row_clamped(int r) const { return base + (int64_t)(r < R ? r : R - 1) * ld; }
     __device__ bool full(int rows) const { return R >= rows; }
 };
 
@@ -49,6 +50,11 @@ template <typename T> struct GateSrc {
     }
     __device__ const T* row_nocheck(int n) const {
         return base + ((int64_t)((n & 127) >> 5) * H + u0 + 32 * (n >> 7) + (n & 31)) * ld;
+    }
+    __device__ const T* row_clamped(int n) const {
+        int u = u0 + 32 * (n >> 7) + (n & 31);
+        u = u < H ? u : H - 1;
+        return base + ((int64_t)((n & 127) >> 5) * H + u) * ld;
     }
     __device__ bool full(int rows) const { return u0 + rows / 4 <= H; }
 };

@@ -52,11 +52,10 @@ struct GemmDma {
 #pragma unroll
         for (int j = 0; j < L; ++j) {
             const int c = tid + j * NT;
-            int row = c / CPR;
+            const int row = c / CPR;
             const int slot = c % CPR;
             const int chunk = slot ^ swz_<SB>(row);
-            row = row < src.R ? row : src.R - 1;
-            const T* p = src.row_nocheck(row) + k0 + chunk * (16 / (int)sizeof(T));
+            const T* p = src.row_clamped(row) + k0 + chunk * (16 / (int)sizeof(T));
             // wave-uniform destination; lane l lands at dst + 16*l
             const uint32_t dst = __builtin_amdgcn_readfirstlane(lds_addr_(lds_tile) + (uint32_t)(wave_base + j * NT) * 16u);
             dma16_(p, dst);
@@ -75,6 +74,9 @@ struct GemmDma {
         else if constexpr (N == 6) asm volatile("s_waitcnt vmcnt(6)" ::: "memory");
         else if constexpr (N == 8) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
         else if constexpr (N == 9) asm volatile("s_waitcnt vmcnt(9)" ::: "memory");
+        else if constexpr (N == 10) asm volatile("s_waitcnt vmcnt(10)" ::: "memory");
+        else if constexpr (N == 5) asm volatile("s_waitcnt vmcnt(5)" ::: "memory");
+        else if constexpr (N == 20) asm volatile("s_waitcnt vmcnt(20)" ::: "memory");
         else if constexpr (N == 12) asm volatile("s_waitcnt vmcnt(12)" ::: "memory");
         else if constexpr (N == 16) asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
         else if constexpr (N == 18) asm volatile("s_waitcnt vmcnt(18)" ::: "memory");

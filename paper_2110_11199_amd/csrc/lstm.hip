@@ -9,38 +9,51 @@
 //   c_t = f c_{t'} + i g                  h_t = o tanh(c_t)
 // with t' the previously processed frame (t-1 forward, t+1 backward direction)
 // and h = c = 0 before the first processed frame of a segment.
+//
+// Each launch re-streams every learner's W_h from HBM (weights are not shared
+// between learners), so these kernels are bound by HBM bandwidth and latency, not
+// by MFMA: the bf16 versions feed LDS with direct global->LDS loads several stages
+// ahead; the backward one reads a transposed bf16 copy of W_h so that both of its
+// operands are K-contiguous.
 #include "gemm_core.hpp"
+#include "gemm_dma.hpp"
 #include "kernels.hpp"
 
 namespace adpsgd {
 
-template <typename T, int WM, int WN, int VB>
-__global__ __launch_bounds__(256) void rec_forward_kernel(RecDesc p) {
-    typedef GemmCore<T, KcSrc<T>, GateSrc<T>, WM, WN, 1, 4, VB> Core;
-    __shared__ __attribute__((aligned(16))) char lds[Core::LDS_BYTES];
+// ---- epilogues -------------------------------------------------------------------
+
+// Inputs of the forward epilogue, loaded BEFORE the recurrent GEMM so that their HBM
+// latency hides behind it: the four pre-activations W_x x + b and c_{t'} of the 16
+// (batch row, unit) positions a lane owns.
+struct FwdInputs { float a[4][16]; float c_prev[16]; };
+
+template <typename T, class Core>
+__device__ inline void forward_prefetch(const RecDesc& p, FwdInputs& in, int li, int d, int t, int tp, int u0, int b0) {
     const int D = p.D, H = p.H, B = p.B;
-    const int li = blockIdx.y / D, d = blockIdx.y % D;
-    const int t = d == 0 ? p.step : p.T - 1 - p.step;
-    const int tp = d == 0 ? t - 1 : t + 1;
-    const int u0 = blockIdx.x * (32 * WN), b0 = blockIdx.z * (32 * WM);
-    const int64_t DH = (int64_t)D * H, G4 = (int64_t)D * 4 * H;
-
-    f32x16_t acc[1][4];
+    const int64_t G4 = (int64_t)D * 4 * H;
+    const int n0c = Core::acc_col(0);
+    const int u = u0 + 32 * (n0c >> 7) + (n0c & 31);
+    const float* gates = p.gates + li * p.sGi;
+    const float* cbuf = p.c + li * p.sCi + (int64_t)d * p.T * B * H;
 #pragma unroll
-    for (int j = 0; j < 4; ++j)
+    for (int i = 0; i < 16; ++i) {
+        const int row = b0 + Core::acc_row(0, i);
+        const bool ok = row < B && u < H;
+        const float* gp = gates + ((int64_t)t * B + (ok ? row : 0)) * G4 + (int64_t)d * 4 * H + (ok ? u : 0);
 #pragma unroll
-        for (int e = 0; e < 16; ++e) acc[0][j][e] = 0.f;
-
-    if (p.step > 0) {
-        KcSrc<T> a;
-        a.base = (const T*)p.y + li * p.sYi + ((int64_t)tp * B + b0) * DH + (int64_t)d * H;
-        a.ld = DH; a.R = B - b0;
-        GateSrc<T> b;
-        b.base = (const T*)p.wh + li * p.sWi + d * p.sWd;
-        b.ld = H; b.H = H; b.u0 = u0;
-        Core::run(acc, a, b, H, lds);
+        for (int g = 0; g < 4; ++g) in.a[g][i] = ok ? gp[(int64_t)g * H] : 0.f;
+        in.c_prev[i] = (ok && p.step > 0) ? cbuf[((int64_t)tp * B + row) * H + u] : 0.f;
     }
+}
 
+// acc[0][gate][i]: gate pre-activation contributions h W_h' for unit u (per lane) and
+// batch rows Core::acc_row(0, i).
+template <typename T, class Core>
+__device__ inline void forward_epilogue(const RecDesc& p, f32x16_t (&acc)[1][4], const FwdInputs& in, int li, int d,
+                                        int t, int u0, int b0) {
+    const int D = p.D, H = p.H, B = p.B;
+    const int64_t DH = (int64_t)D * H, G4 = (int64_t)D * 4 * H;
     // tile column n = 128*wave_n + 32*gate + j holds gate `gate` of unit u0 + 32*wave_n + j
     const int n0c = Core::acc_col(0);
     const int u = u0 + 32 * (n0c >> 7) + (n0c & 31);
@@ -53,13 +66,11 @@ __global__ __launch_bounds__(256) void rec_forward_kernel(RecDesc p) {
         const int row = b0 + Core::acc_row(0, i);
         if (row >= B) continue;
         float* gp = gates + ((int64_t)t * B + row) * G4 + (int64_t)d * 4 * H + u;
-        const float ai = gp[0] + acc[0][0][i];
-        const float af = gp[H] + acc[0][1][i];
-        const float ag = gp[2 * (int64_t)H] + acc[0][2][i];
-        const float ao = gp[3 * (int64_t)H] + acc[0][3][i];
-        const float c_prev = p.step > 0 ? cbuf[((int64_t)tp * B + row) * H + u] : 0.f;
-        const float ig = sigmoidf_(ai), fg = sigmoidf_(af), gg = tanhf(ag), og = sigmoidf_(ao);
-        const float cc = fg * c_prev + ig * gg;
+        const float ig = sigmoidf_(in.a[0][i] + acc[0][0][i]);
+        const float fg = sigmoidf_(in.a[1][i] + acc[0][1][i]);
+        const float gg = tanhf(in.a[2][i] + acc[0][2][i]);
+        const float og = sigmoidf_(in.a[3][i] + acc[0][3][i]);
+        const float cc = fg * in.c_prev[i] + ig * gg;
         const float hh = og * tanhf(cc);
         gp[0] = ig; gp[H] = fg; gp[2 * (int64_t)H] = gg; gp[3 * (int64_t)H] = og;
         cbuf[((int64_t)t * B + row) * H + u] = cc;
@@ -68,39 +79,16 @@ __global__ __launch_bounds__(256) void rec_forward_kernel(RecDesc p) {
 }
 
 // Backward through one frame: dh_t = dY_t + da_{t''} W_h (t'' = the frame
-// processed just before in backward order), then
+// processed just before in backward order; acc holds that product), then
 //   do = dh tanh(c_t)            dc = dc_rec + dh o (1 - tanh^2 c_t)
 //   di = dc g, dg = dc i, df = dc c_{t'}, dc_rec <- dc f
 //   da = (di i(1-i), df f(1-f), dg (1-g^2), do o(1-o))
-template <typename T, int WM, int WN, int FN, int VB>
-__global__ __launch_bounds__(256) void rec_backward_kernel(RecDesc p) {
-    typedef GemmCore<T, KcSrc<T>, McSrc<T>, WM, WN, 1, FN, VB> Core;
-    __shared__ __attribute__((aligned(16))) char lds[Core::LDS_BYTES];
+template <typename T, class Core, int FN>
+__device__ inline void backward_epilogue(const RecDesc& p, f32x16_t (&acc)[1][FN], int li, int d, int t, int tp,
+                                         int u0, int b0) {
     const int D = p.D, H = p.H, B = p.B;
-    const int li = blockIdx.y / D, d = blockIdx.y % D;
-    const int t = d == 0 ? p.T - 1 - p.step : p.step;     // reverse of the forward processing order
-    const int tn = d == 0 ? t + 1 : t - 1;                 // frame handled by the previous launch
-    const int tp = d == 0 ? t - 1 : t + 1;                 // frame the forward pass processed before t
-    const bool has_prev = tp >= 0 && tp < p.T;
-    const int u0 = blockIdx.x * Core::BN, b0 = blockIdx.z * Core::BM;
     const int64_t DH = (int64_t)D * H, G4 = (int64_t)D * 4 * H;
-
-    f32x16_t acc[1][FN];
-#pragma unroll
-    for (int j = 0; j < FN; ++j)
-#pragma unroll
-        for (int e = 0; e < 16; ++e) acc[0][j][e] = 0.f;
-
-    if (p.step > 0) {
-        KcSrc<T> a;
-        a.base = (const T*)p.da + li * p.sDAi + ((int64_t)tn * B + b0) * G4 + (int64_t)d * 4 * H;
-        a.ld = G4; a.R = B - b0;
-        McSrc<T> b;
-        b.base = (const T*)p.wh + li * p.sWi + d * p.sWd + u0;
-        b.ld = H; b.R = H - u0;
-        Core::run(acc, a, b, 4 * H, lds);
-    }
-
+    const bool has_prev = tp >= 0 && tp < p.T;
     const float* gates = p.gates + li * p.sGi;
     const float* cbuf = p.c + li * p.sCi + (int64_t)d * p.T * B * H;
     const float* dy = p.dy + li * p.sDYi;
@@ -134,6 +122,119 @@ __global__ __launch_bounds__(256) void rec_backward_kernel(RecDesc p) {
         }
     }
 }
+
+template <int FN> __device__ inline void zero_acc(f32x16_t (&acc)[1][FN]) {
+#pragma unroll
+    for (int j = 0; j < FN; ++j)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) acc[0][j][e] = 0.f;
+}
+
+// ---- register-staged versions (any operand type, any shape) ---------------------------
+
+template <typename T, int WM, int WN, int VB>
+__global__ __launch_bounds__(256) void rec_forward_kernel(RecDesc p) {
+    typedef GemmCore<T, KcSrc<T>, GateSrc<T>, WM, WN, 1, 4, VB> Core;
+    __shared__ __attribute__((aligned(16))) char lds[Core::LDS_BYTES];
+    const int D = p.D, H = p.H, B = p.B;
+    const int li = blockIdx.y / D, d = blockIdx.y % D;
+    const int t = d == 0 ? p.step : p.T - 1 - p.step;
+    const int tp = d == 0 ? t - 1 : t + 1;
+    const int u0 = blockIdx.x * (32 * WN), b0 = blockIdx.z * (32 * WM);
+    f32x16_t acc[1][4];
+    zero_acc<4>(acc);
+    FwdInputs in;
+    forward_prefetch<T, Core>(p, in, li, d, t, tp, u0, b0);
+    if (p.step > 0) {
+        KcSrc<T> a;
+        a.base = (const T*)p.y + li * p.sYi + ((int64_t)tp * B + b0) * ((int64_t)D * H) + (int64_t)d * H;
+        a.ld = (int64_t)D * H; a.R = B - b0;
+        GateSrc<T> b;
+        b.base = (const T*)p.wh + li * p.sWi + d * p.sWd;
+        b.ld = H; b.H = H; b.u0 = u0;
+        Core::run(acc, a, b, H, lds);
+    }
+    forward_epilogue<T, Core>(p, acc, in, li, d, t, u0, b0);
+}
+
+template <typename T, int WM, int WN, int FN, int VB>
+__global__ __launch_bounds__(256) void rec_backward_kernel(RecDesc p) {
+    typedef GemmCore<T, KcSrc<T>, McSrc<T>, WM, WN, 1, FN, VB> Core;
+    __shared__ __attribute__((aligned(16))) char lds[Core::LDS_BYTES];
+    const int D = p.D, H = p.H, B = p.B;
+    const int li = blockIdx.y / D, d = blockIdx.y % D;
+    const int t = d == 0 ? p.T - 1 - p.step : p.step;     // reverse of the forward processing order
+    const int tn = d == 0 ? t + 1 : t - 1;                 // frame handled by the previous launch
+    const int tp = d == 0 ? t - 1 : t + 1;                 // frame the forward pass processed before t
+    const int u0 = blockIdx.x * Core::BN, b0 = blockIdx.z * Core::BM;
+    const int64_t G4 = (int64_t)D * 4 * H;
+    f32x16_t acc[1][FN];
+    zero_acc<FN>(acc);
+    if (p.step > 0) {
+        KcSrc<T> a;
+        a.base = (const T*)p.da + li * p.sDAi + ((int64_t)tn * B + b0) * G4 + (int64_t)d * 4 * H;
+        a.ld = G4; a.R = B - b0;
+        McSrc<T> b;
+        b.base = (const T*)p.wh + li * p.sWi + d * p.sWd + u0;
+        b.ld = H; b.R = H - u0;
+        Core::run(acc, a, b, 4 * H, lds);
+    }
+    backward_epilogue<T, Core, FN>(p, acc, li, d, t, tp, u0, b0);
+}
+
+// ---- direct-to-LDS versions (bf16, H a multiple of the stage, 16-byte aligned rows) -----
+
+template <typename T, int WM, int WN, int SB, int NS>
+__global__ __launch_bounds__(256) void rec_forward_dma_kernel(RecDesc p) {
+    typedef GemmDma<T, KcSrc<T>, GateSrc<T>, WM, WN, 1, 4, SB, NS> Core;
+    __shared__ __attribute__((aligned(1024))) char lds[Core::LDS_BYTES];
+    const int D = p.D, H = p.H, B = p.B;
+    const int li = blockIdx.y / D, d = blockIdx.y % D;
+    const int t = d == 0 ? p.step : p.T - 1 - p.step;
+    const int tp = d == 0 ? t - 1 : t + 1;
+    const int u0 = blockIdx.x * (32 * WN), b0 = blockIdx.z * (32 * WM);
+    f32x16_t acc[1][4];
+    zero_acc<4>(acc);
+    FwdInputs in;
+    forward_prefetch<T, Core>(p, in, li, d, t, tp, u0, b0);
+    if (p.step > 0) {
+        KcSrc<T> a;
+        a.base = (const T*)p.y + li * p.sYi + ((int64_t)tp * B + b0) * ((int64_t)D * H) + (int64_t)d * H;
+        a.ld = (int64_t)D * H; a.R = B - b0;
+        GateSrc<T> b;
+        b.base = (const T*)p.wh + li * p.sWi + d * p.sWd;
+        b.ld = H; b.H = H; b.u0 = u0;
+        Core::run(acc, a, b, H, lds);
+    }
+    forward_epilogue<T, Core>(p, acc, in, li, d, t, u0, b0);
+}
+
+// B operand = transposed copy of W_h: whT [D][H][4H], row u contiguous over the 4H gate rows.
+template <typename T, int WM, int WN, int FN, int SB, int NS>
+__global__ __launch_bounds__(256) void rec_backward_dma_kernel(RecDesc p) {
+    typedef GemmDma<T, KcSrc<T>, KcSrc<T>, WM, WN, 1, FN, SB, NS> Core;
+    __shared__ __attribute__((aligned(1024))) char lds[Core::LDS_BYTES];
+    const int D = p.D, H = p.H, B = p.B;
+    const int li = blockIdx.y / D, d = blockIdx.y % D;
+    const int t = d == 0 ? p.T - 1 - p.step : p.step;
+    const int tn = d == 0 ? t + 1 : t - 1;
+    const int tp = d == 0 ? t - 1 : t + 1;
+    const int u0 = blockIdx.x * Core::BN, b0 = blockIdx.z * Core::BM;
+    const int64_t G4 = (int64_t)D * 4 * H;
+    f32x16_t acc[1][FN];
+    zero_acc<FN>(acc);
+    if (p.step > 0) {
+        KcSrc<T> a, b;
+        a.base = (const T*)p.da + li * p.sDAi + ((int64_t)tn * B + b0) * G4 + (int64_t)d * 4 * H;
+        a.ld = G4; a.R = B - b0;
+        b.base = (const T*)p.whT + li * p.sWTi + d * p.sWTd + (int64_t)u0 * 4 * H;
+        b.ld = (int64_t)4 * H; b.R = H - u0;
+        Core::run(acc, a, b, 4 * H, lds);
+    }
+    backward_epilogue<T, Core, FN>(p, acc, li, d, t, tp, u0, b0);
+}
+
+// ---- launchers ----------------------------------------------------------------------
 
 template <typename T, int VB>
 static hipError_t fwd_t(const RecDesc& d, hipStream_t s) {
@@ -172,15 +273,44 @@ static bool rec_ok(const RecDesc& d) {
            d.step >= 0 && d.step < d.T;
 }
 
+static int g_rec_dma = 1;    // tuning knob: 0 disables the direct-to-LDS kernels
+void set_rec_dma(int on) { g_rec_dma = on; }
+
+static bool dma_ok(const RecDesc& d) {
+    return g_rec_dma && d.precision == 1 && d.H % 64 == 0 && d.B > 32;
+}
+
 hipError_t launch_rec_forward(const RecDesc& d, hipStream_t s) {
     if (!rec_ok(d)) return hipErrorInvalidValue;
     if (d.precision == 0) return fwd_t<float, 16>(d, s);
+    if (dma_ok(d)) {
+        const unsigned groups = (unsigned)(d.L * d.D);
+        if (d.B > 64) {
+            dim3 grid((d.H + 31) / 32, groups, (d.B + 127) / 128);
+            hipLaunchKernelGGL((rec_forward_dma_kernel<bf16_t, 4, 1, 128, 4>), grid, dim3(256), 0, s, d);
+        } else {
+            dim3 grid((d.H + 63) / 64, groups, (d.B + 63) / 64);
+            hipLaunchKernelGGL((rec_forward_dma_kernel<bf16_t, 2, 2, 128, 3>), grid, dim3(256), 0, s, d);
+        }
+        return hipGetLastError();
+    }
     return d.H % 8 == 0 ? fwd_t<bf16_t, 16>(d, s) : fwd_t<bf16_t, 8>(d, s);
 }
 
 hipError_t launch_rec_backward(const RecDesc& d, hipStream_t s) {
     if (!rec_ok(d)) return hipErrorInvalidValue;
     if (d.precision == 0) return bwd_t<float, 16>(d, s);
+    if (dma_ok(d) && d.whT != nullptr) {
+        const unsigned groups = (unsigned)(d.L * d.D);
+        if (d.B > 64) {
+            dim3 grid((d.H + 127) / 128, groups, (d.B + 127) / 128);
+            hipLaunchKernelGGL((rec_backward_dma_kernel<bf16_t, 4, 1, 4, 128, 4>), grid, dim3(256), 0, s, d);
+        } else {
+            dim3 grid((d.H + 127) / 128, groups, (d.B + 63) / 64);
+            hipLaunchKernelGGL((rec_backward_dma_kernel<bf16_t, 2, 2, 2, 128, 4>), grid, dim3(256), 0, s, d);
+        }
+        return hipGetLastError();
+    }
     return d.H % 8 == 0 ? bwd_t<bf16_t, 16>(d, s) : bwd_t<bf16_t, 8>(d, s);
 }
 

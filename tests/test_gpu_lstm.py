@@ -51,6 +51,8 @@ SHAPES = [
     Shape(20, 64, 1, 1, 0, 300, 70, 4),       # batch 70 (64-row tiles + tail), several class tiles
     Shape(16, 32, 3, 0, 8, 36, 130, 2),       # batch 130 (128-row tiles + tail), unidirectional
     Shape(8, 8, 1, 1, 4, 8, 2, 1),            # one frame: no recurrence
+    Shape(24, 192, 2, 1, 16, 64, 130, 3),     # hidden 192: ragged unit tiles of the direct-to-LDS kernels, batch 130
+    Shape(16, 128, 1, 1, 0, 40, 48, 4),       # batch 48: the 64-row recurrent tile configuration
 ]
 
 
