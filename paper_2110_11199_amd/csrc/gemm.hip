@@ -17,6 +17,62 @@ __device__ inline int xcd_contiguous_id(int bid, int nb) {
     return start + local;
 }
 
+// Epilogue shared by the GEMM kernels: C tile = acc (+ bias), fp32 or operand type.
+// Every store reads its data straight from an accumulator register (the bias is added
+// and the bf16 conversion done in place first): reusing one temporary register for all
+// stores makes the compiler wait for each store to complete before the next one.
+template <typename T, class Core, int FM, int FN>
+__device__ inline void store_tile(f32x16_t (&acc)[FM][FN], const GemmDesc& p, int m0, int n0, int gi, int gd) {
+    const float* bias = p.bias ? p.bias + gi * p.sBiasI + gd * p.sBiasD : nullptr;
+    const int64_t coff = gi * p.sCi + gd * p.sCd;
+    const int lane = threadIdx.x & 63;
+#pragma unroll
+    for (int fn = 0; fn < FN; ++fn) {
+        const int col = n0 + Core::acc_col(fn);
+        if (col >= p.N) continue;
+        const float bv = bias ? bias[col] : 0.f;
+#pragma unroll
+        for (int fm = 0; fm < FM; ++fm) {
+            const int row0 = m0 + Core::acc_row(fm, 0);          // rows of this lane: row0 + 8*(i/4) + i%4
+            const int64_t o = coff + (int64_t)row0 * p.ldc + col;
+            if (p.c_elem) {
+                T* c = (T*)p.C + o;
+                if constexpr (sizeof(T) == 2) {
+                    uint32_t hb[16];                     // one register per value: see the comment above
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) hb[i] = f32_to_bf16(acc[fm][fn][i] + bv);
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) {
+                        const int r = 8 * (i >> 2) + (i & 3);
+                        if (row0 + r < p.M) c[(int64_t)r * p.ldc] = (bf16_t)hb[i];
+                    }
+                } else {
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) acc[fm][fn][i] += bv;
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) {
+                        const int r = 8 * (i >> 2) + (i & 3);
+                        if (row0 + r < p.M) c[(int64_t)r * p.ldc] = acc[fm][fn][i];
+                    }
+                }
+            } else {
+                float* c = (float*)p.C + o;
+#pragma unroll
+                for (int i = 0; i < 16; ++i) acc[fm][fn][i] += bv;
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    const int r = 8 * (i >> 2) + (i & 3);
+#ifdef ADPSGD_DBG_NOEPI
+                    if (acc[fm][fn][i] != 123456.75f) continue;
+#endif
+                    if (row0 + r < p.M) c[(int64_t)r * p.ldc] = acc[fm][fn][i];
+                }
+            }
+        }
+    }
+    (void)lane;
+}
+
 template <typename T, bool AKC, bool BKC, int WM, int WN, int FM, int FN, int VB, int SB>
 __global__ __launch_bounds__(64 * WM * WN, (WM * WN == 4 && FM * FN == 8) ? 2 : 1) void gemm_kernel(GemmDesc p) {
     typedef typename std::conditional<AKC, KcSrc<T>, McSrc<T>>::type ASrc;
@@ -47,30 +103,7 @@ __global__ __launch_bounds__(64 * WM * WN, (WM * WN == 4 && FM * FN == 8) ? 2 : 
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
     Core::run(acc, a, b, p.K, lds);
 
-    const float* bias = p.bias ? p.bias + gi * p.sBiasI + gd * p.sBiasD : nullptr;
-    const int64_t coff = gi * p.sCi + gd * p.sCd;
-    const bool celem = p.c_elem != 0;
-#pragma unroll
-    for (int fn = 0; fn < FN; ++fn) {
-        const int col = n0 + Core::acc_col(fn);
-        if (col >= p.N) continue;
-        const float bv = bias ? bias[col] : 0.f;
-#pragma unroll
-        for (int fm = 0; fm < FM; ++fm) {
-#pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                const int row = m0 + Core::acc_row(fm, i);
-                if (row >= p.M) continue;
-                const float v = acc[fm][fn][i] + bv;
-#ifdef ADPSGD_DBG_NOEPI
-                if (v != 123456.75f) continue;
-#endif
-                const int64_t o = coff + (int64_t)row * p.ldc + col;
-                if (celem) ((T*)p.C)[o] = Elem<T>::from(v);
-                else ((float*)p.C)[o] = v;
-            }
-        }
-    }
+    store_tile<T, Core, FM, FN>(acc, p, m0, n0, gi, gd);
 }
 
 // Same tile bookkeeping with the direct-to-LDS main loop (both operands K-contiguous,
@@ -87,6 +120,14 @@ __global__ __launch_bounds__(64 * WM * WN, MINB) void gemm_dma_kernel(GemmDesc p
     const int m0 = tm * Core::BM, n0 = tn * Core::BN;
 #ifdef ADPSGD_DBG_TIMING
     const long long ts = wall_clock64();
+#endif
+#ifdef ADPSGD_STAGGER
+    // first wave of workgroups: delay each XCD by a different fraction of a tile's duration so that the
+    // epilogue write bursts of the XCDs do not coincide (the offset persists: every CU runs tiles back to back)
+    if (blockIdx.y == 0 && blockIdx.x < 256) {
+        const long long until = wall_clock64() + (long long)(blockIdx.x & 7) * ADPSGD_STAGGER;
+        while (wall_clock64() < until) __builtin_amdgcn_s_sleep(32);
+    }
 #endif
     KcSrc<T> a, b;
     a.base = (const T*)p.A + gi * p.sAi + gd * p.sAd + (int64_t)m0 * p.lda; a.ld = p.lda; a.R = p.M - m0;
@@ -109,30 +150,7 @@ __global__ __launch_bounds__(64 * WM * WN, MINB) void gemm_dma_kernel(GemmDesc p
 #endif
 
 
-    const float* bias = p.bias ? p.bias + gi * p.sBiasI + gd * p.sBiasD : nullptr;
-    const int64_t coff = gi * p.sCi + gd * p.sCd;
-    const bool celem = p.c_elem != 0;
-#pragma unroll
-    for (int fn = 0; fn < FN; ++fn) {
-        const int col = n0 + Core::acc_col(fn);
-        if (col >= p.N) continue;
-        const float bv = bias ? bias[col] : 0.f;
-#pragma unroll
-        for (int fm = 0; fm < FM; ++fm) {
-#pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                const int row = m0 + Core::acc_row(fm, i);
-                if (row >= p.M) continue;
-                const float v = acc[fm][fn][i] + bv;
-#ifdef ADPSGD_DBG_NOEPI
-                if (v != 123456.75f) continue;
-#endif
-                const int64_t o = coff + (int64_t)row * p.ldc + col;
-                if (celem) ((T*)p.C)[o] = Elem<T>::from(v);
-                else ((float*)p.C)[o] = v;
-            }
-        }
-    }
+    store_tile<T, Core, FM, FN>(acc, p, m0, n0, gi, gd);
 #ifdef ADPSGD_DBG_TIMING
     if (threadIdx.x == 0 && p.dbg) {
         long long* d = p.dbg + ((int64_t)blockIdx.y * gridDim.x + blockIdx.x) * 4;
@@ -218,6 +236,8 @@ hipError_t launch_gemm(const GemmDesc& d, hipStream_t s) {
             case 7: return launch_dma<bf16_t, 2, 4, 2, 2, 64, 3, 2>(d, s);
             case 8: return launch_dma<bf16_t, 4, 2, 2, 2, 64, 3, 2>(d, s);
             case 9: return launch_dma<bf16_t, 2, 2, 2, 2, 64, 4, 2>(d, s);
+            case 11: return launch_dma<bf16_t, 2, 2, 4, 4, 64, 2, 2>(d, s);
+            case 12: return launch_dma<bf16_t, 2, 2, 4, 4, 128, 2, 1>(d, s);
             default: return launch_dma<bf16_t, 2, 4, 4, 2, 128, 2, 1>(d, s);
         }
     }

@@ -50,7 +50,7 @@ __device__ inline void forward_prefetch(const RecDesc& p, FwdInputs& in, int li,
 // acc[0][gate][i]: gate pre-activation contributions h W_h' for unit u (per lane) and
 // batch rows Core::acc_row(0, i).
 template <typename T, class Core>
-__device__ inline void forward_epilogue(const RecDesc& p, f32x16_t (&acc)[1][4], const FwdInputs& in, int li, int d,
+__device__ inline void forward_epilogue(const RecDesc& p, f32x16_t (&acc)[1][4], FwdInputs& in, int li, int d,
                                         int t, int u0, int b0) {
     const int D = p.D, H = p.H, B = p.B;
     const int64_t DH = (int64_t)D * H, G4 = (int64_t)D * 4 * H;
@@ -61,20 +61,31 @@ __device__ inline void forward_epilogue(const RecDesc& p, f32x16_t (&acc)[1][4],
     float* gates = p.gates + li * p.sGi;
     float* cbuf = p.c + li * p.sCi + (int64_t)d * p.T * B * H;
     T* y = (T*)p.y + li * p.sYi;
+    // All results are computed first, each into a register of its own, and stored afterwards: a store
+    // whose data register is reused by later arithmetic would have to complete before that arithmetic.
+    float hv[16];
+    uint32_t hb[16];
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
-        const int row = b0 + Core::acc_row(0, i);
-        if (row >= B) continue;
-        float* gp = gates + ((int64_t)t * B + row) * G4 + (int64_t)d * 4 * H + u;
         const float ig = sigmoidf_(in.a[0][i] + acc[0][0][i]);
         const float fg = sigmoidf_(in.a[1][i] + acc[0][1][i]);
         const float gg = tanhf(in.a[2][i] + acc[0][2][i]);
         const float og = sigmoidf_(in.a[3][i] + acc[0][3][i]);
         const float cc = fg * in.c_prev[i] + ig * gg;
-        const float hh = og * tanhf(cc);
-        gp[0] = ig; gp[H] = fg; gp[2 * (int64_t)H] = gg; gp[3 * (int64_t)H] = og;
-        cbuf[((int64_t)t * B + row) * H + u] = cc;
-        y[((int64_t)t * B + row) * DH + (int64_t)d * H + u] = Elem<T>::from(hh);
+        acc[0][0][i] = ig; acc[0][1][i] = fg; acc[0][2][i] = gg; acc[0][3][i] = og;
+        hv[i] = og * tanhf(cc);
+        if constexpr (sizeof(T) == 2) hb[i] = f32_to_bf16(hv[i]);
+        in.c_prev[i] = cc;
+    }
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+        const int row = b0 + Core::acc_row(0, i);
+        if (row >= B) continue;
+        float* gp = gates + ((int64_t)t * B + row) * G4 + (int64_t)d * 4 * H + u;
+        gp[0] = acc[0][0][i]; gp[H] = acc[0][1][i]; gp[2 * (int64_t)H] = acc[0][2][i]; gp[3 * (int64_t)H] = acc[0][3][i];
+        cbuf[((int64_t)t * B + row) * H + u] = in.c_prev[i];
+        if constexpr (sizeof(T) == 2) y[((int64_t)t * B + row) * DH + (int64_t)d * H + u] = (bf16_t)hb[i];
+        else y[((int64_t)t * B + row) * DH + (int64_t)d * H + u] = hv[i];
     }
 }
 
@@ -98,27 +109,52 @@ __device__ inline void backward_epilogue(const RecDesc& p, f32x16_t (&acc)[1][FN
     for (int fn = 0; fn < FN; ++fn) {
         const int u = u0 + Core::acc_col(fn);
         if (u >= H) continue;
+        // load everything, compute everything, store everything (see the forward epilogue)
+        float dyv[16], gi[16], gf[16], gg[16], go[16], cv[16], cp[16], dcr[16];
+        uint32_t pk0[16], pk1[16];            // bf16 results packed two per register (i,f) and (g,o)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            const int row = b0 + Core::acc_row(0, i);
+            const bool ok = row < B;
+            const int64_t m = (int64_t)t * B + (ok ? row : 0);
+            const float* gp = gates + m * G4 + (int64_t)d * 4 * H + u;
+            dyv[i] = ok ? dy[m * DH + (int64_t)d * H + u] : 0.f;
+            gi[i] = ok ? gp[0] : 0.f; gf[i] = ok ? gp[H] : 0.f;
+            gg[i] = ok ? gp[2 * (int64_t)H] : 0.f; go[i] = ok ? gp[3 * (int64_t)H] : 0.f;
+            cv[i] = ok ? cbuf[m * H + u] : 0.f;
+            cp[i] = (ok && has_prev) ? cbuf[((int64_t)tp * B + row) * H + u] : 0.f;
+            dcr[i] = (ok && p.step > 0) ? dcb[(int64_t)row * H + u] : 0.f;
+        }
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            const float dh = dyv[i] + acc[0][fn][i];
+            const float ig = gi[i], fg = gf[i], g2 = gg[i], og = go[i];
+            const float tc = tanhf(cv[i]);
+            const float dov = dh * tc;
+            const float dcv = dcr[i] + dh * og * (1.f - tc * tc);
+            const float di = dcv * g2, dg = dcv * ig, df = dcv * cp[i];
+            dcr[i] = dcv * fg;
+            float a0 = di * ig * (1.f - ig), a1 = df * fg * (1.f - fg), a2 = dg * (1.f - g2 * g2), a3 = dov * og * (1.f - og);
+            if constexpr (sizeof(T) == 2) {
+                pk0[i] = (uint32_t)f32_to_bf16(a0) | ((uint32_t)f32_to_bf16(a1) << 16);
+                pk1[i] = (uint32_t)f32_to_bf16(a2) | ((uint32_t)f32_to_bf16(a3) << 16);
+            } else {
+                gi[i] = a0; gf[i] = a1; gg[i] = a2; go[i] = a3;
+            }
+        }
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
             const int row = b0 + Core::acc_row(0, i);
             if (row >= B) continue;
             const int64_t m = (int64_t)t * B + row;
-            const float dh = dy[m * DH + (int64_t)d * H + u] + acc[0][fn][i];
-            const float* gp = gates + m * G4 + (int64_t)d * 4 * H + u;
-            const float ig = gp[0], fg = gp[H], gg = gp[2 * (int64_t)H], og = gp[3 * (int64_t)H];
-            const float cc = cbuf[m * H + u];
-            const float c_prev = has_prev ? cbuf[((int64_t)tp * B + row) * H + u] : 0.f;
-            const float tc = tanhf(cc);
-            const float dc_rec = p.step > 0 ? dcb[(int64_t)row * H + u] : 0.f;
-            const float dov = dh * tc;
-            const float dcv = dc_rec + dh * og * (1.f - tc * tc);
-            const float di = dcv * gg, dg = dcv * ig, df = dcv * c_prev;
-            dcb[(int64_t)row * H + u] = dcv * fg;
+            dcb[(int64_t)row * H + u] = dcr[i];
             T* dp = da + m * G4 + (int64_t)d * 4 * H + u;
-            dp[0] = Elem<T>::from(di * ig * (1.f - ig));
-            dp[H] = Elem<T>::from(df * fg * (1.f - fg));
-            dp[2 * (int64_t)H] = Elem<T>::from(dg * (1.f - gg * gg));
-            dp[3 * (int64_t)H] = Elem<T>::from(dov * og * (1.f - og));
+            if constexpr (sizeof(T) == 2) {
+                dp[0] = (bf16_t)(pk0[i] & 0xffffu); dp[H] = (bf16_t)(pk0[i] >> 16);
+                dp[2 * (int64_t)H] = (bf16_t)(pk1[i] & 0xffffu); dp[3 * (int64_t)H] = (bf16_t)(pk1[i] >> 16);
+            } else {
+                dp[0] = gi[i]; dp[H] = gf[i]; dp[2 * (int64_t)H] = gg[i]; dp[3 * (int64_t)H] = go[i];
+            }
         }
     }
 }
