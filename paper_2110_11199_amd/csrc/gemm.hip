@@ -108,8 +108,8 @@ __global__ __launch_bounds__(64 * WM * WN, (WM * WN == 4 && FM * FN == 8) ? 2 : 
 
 // Same tile bookkeeping with the direct-to-LDS main loop (both operands K-contiguous,
 // 16-byte aligned rows, K a multiple of the stage length).
-template <typename T, int WM, int WN, int FM, int FN, int SB, int NS, int MINB>
-__global__ __launch_bounds__(64 * WM * WN, MINB) void gemm_dma_kernel(GemmDesc p) {
+template <typename T, int WM, int WN, int FM, int FN, int SB, int NS, int MINB, int PF = 0>
+__global__ __launch_bounds__(64 * WM * WN + (PF > 0 ? 64 : 0), MINB) void gemm_dma_kernel(GemmDesc p) {
     typedef GemmDma<T, KcSrc<T>, KcSrc<T>, WM, WN, FM, FN, SB, NS> Core;
     __shared__ __attribute__((aligned(1024))) char lds[Core::LDS_BYTES];
 
@@ -132,6 +132,9 @@ __global__ __launch_bounds__(64 * WM * WN, MINB) void gemm_dma_kernel(GemmDesc p
     KcSrc<T> a, b;
     a.base = (const T*)p.A + gi * p.sAi + gd * p.sAd + (int64_t)m0 * p.lda; a.ld = p.lda; a.R = p.M - m0;
     b.base = (const T*)p.B + gi * p.sBi + gd * p.sBd + (int64_t)n0 * p.ldb; b.ld = p.ldb; b.R = p.N - n0;
+    if constexpr (PF > 0) {
+        if (threadIdx.x >= Core::NT) { Core::template prefetch_wave<PF>(a, b, p.K, lds + Core::LDS_BYTES); return; }
+    }
 
     f32x16_t acc[FM][FN];
 #pragma unroll
@@ -159,12 +162,12 @@ __global__ __launch_bounds__(64 * WM * WN, MINB) void gemm_dma_kernel(GemmDesc p
 #endif
 }
 
-template <typename T, int WM, int WN, int FM, int FN, int SB, int NS, int MINB>
+template <typename T, int WM, int WN, int FM, int FN, int SB, int NS, int MINB, int PF = 0>
 static hipError_t launch_dma(const GemmDesc& d, hipStream_t s) {
     constexpr int BM = 32 * FM * WM, BN = 32 * FN * WN;
     const int tiles_m = (d.M + BM - 1) / BM, tiles_n = (d.N + BN - 1) / BN;
     dim3 grid((unsigned)(tiles_m * tiles_n), (unsigned)(d.groupsI * d.groupsD));
-    hipLaunchKernelGGL((gemm_dma_kernel<T, WM, WN, FM, FN, SB, NS, MINB>), grid, dim3(64 * WM * WN), 0, s, d);
+    hipLaunchKernelGGL((gemm_dma_kernel<T, WM, WN, FM, FN, SB, NS, MINB, PF>), grid, dim3(64 * WM * WN + (PF > 0 ? 64 : 0)), 0, s, d);
     return hipGetLastError();
 }
 
@@ -236,8 +239,9 @@ hipError_t launch_gemm(const GemmDesc& d, hipStream_t s) {
             case 7: return launch_dma<bf16_t, 2, 4, 2, 2, 64, 3, 2>(d, s);
             case 8: return launch_dma<bf16_t, 4, 2, 2, 2, 64, 3, 2>(d, s);
             case 9: return launch_dma<bf16_t, 2, 2, 2, 2, 64, 4, 2>(d, s);
-            case 11: return launch_dma<bf16_t, 2, 2, 4, 4, 64, 2, 2>(d, s);
-            case 12: return launch_dma<bf16_t, 2, 2, 4, 4, 128, 2, 1>(d, s);
+            case 11: return launch_dma<bf16_t, 2, 4, 4, 2, 128, 2, 1, 3>(d, s);
+            case 12: return launch_dma<bf16_t, 2, 4, 4, 2, 128, 2, 1, 4>(d, s);
+            case 13: return launch_dma<bf16_t, 2, 4, 4, 2, 128, 2, 1, 64>(d, s);
             default: return launch_dma<bf16_t, 2, 4, 4, 2, 128, 2, 1>(d, s);
         }
     }
