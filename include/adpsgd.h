@@ -170,7 +170,8 @@ int adpsgd_average(adpsgd_t h, float* dev_out);
  * profiling was switched on or last read, and starts a new total:
  * host_ms[7] GPU milliseconds, host_launches[7] kernel launches, host_work[7]
  * algorithmic work (flops 2*M*N*K summed for phases 1-3; bytes, 12 per active
- * learner and element, for phase 6; 0 elsewhere).  Any pointer may be NULL.
+ * learner and element (14 when the bf16 copy of the model is written along), for
+ * phase 6; 0 elsewhere).  Any pointer may be NULL.
  * Each change of phase costs one HIP event; they are kept until destroy.        */
 #define ADPSGD_PHASES 7
 int adpsgd_set_profiling(adpsgd_t h, int enable);
@@ -201,7 +202,8 @@ int adpsgd_gemm(int precision, int a_kmajor, int b_kmajor, int c_is_elem,
                 int groups, void* hip_stream);
 
 /* Tuning knob for benchmarks: force the GEMM tile configuration of this process
- * (0..5, see csrc/gemm.hip); -1 restores the automatic choice.  Not thread-safe. */
+ * (0, 5 or 10, see csrc/gemm.hip; 100 / 101 switch the direct-to-LDS recurrent
+ * kernels off / on); -1 restores the automatic choice.  Not thread-safe.        */
 int adpsgd_gemm_set_variant(int variant);
 
 #ifdef __cplusplus

@@ -99,6 +99,7 @@ struct adpsgd_handle {
     int64_t P, Ppad, M;
     int64_t k;
     int cur;                               // index of the buffer holding x^k
+    bool shadow_valid;                     // the bf16 copy already holds the next gradient point
     std::vector<Tensor> tensors;           // flat layout
     std::vector<int> ix_wx, ix_wh, ix_b;   // tensor index per layer
     int ix_wp, ix_bp, ix_wo, ix_bo;
@@ -251,7 +252,8 @@ int compute_gradients(adpsgd_handle* h, const float* at, const void* const* batc
     if (int rc = mark(h, 0, prec ? 2 + h->layers : 1)) return rc;
     const int64_t WT = (int64_t)4 * H * H;            // elements of one direction's W_h
     if (prec) {
-        HIPCHK(launch_cast_bf16(at, h->shadow, (int64_t)L * Pp, s), "cast weights to bf16");
+        // the update of the previous iteration has normally written this copy already
+        if (!h->shadow_valid) HIPCHK(launch_cast_bf16(at, h->shadow, (int64_t)L * Pp, s), "cast weights to bf16");
         wbase = (const char*)h->shadow;
         for (int l = 0; l < h->layers; ++l)
             HIPCHK(launch_transpose_cast_bf16(at + h->tensors[h->ix_wh[l]].off, Pp, WT, h->shadowT + (size_t)l * L * D * WT,
@@ -463,7 +465,7 @@ int adpsgd_create(const adpsgd_config* cfg, void* dev_workspace, size_t bytes, v
         delete h;
         return fail(ADPSGD_ENOMEM, "workspace too small: need " + std::to_string(need) + " bytes");
     }
-    h->k = 0; h->cur = 0;
+    h->k = 0; h->cur = 0; h->shadow_valid = false;
     hipStream_t s = h->stream;
     const size_t slab = (size_t)h->L * h->Ppad * 4;
     hipError_t e = hipMemsetAsync(h->params[0], 0, slab, s);
@@ -512,14 +514,18 @@ int adpsgd_step(adpsgd_t h, const void* const* batch_ptrs, float lr) {
         for (int i = 0; i < L; ++i) u.g[i] = h->grads + (size_t)i * h->Ppad;
     }
     for (int i = 0; i < L; ++i) { u.partner[i] = (int16_t)partner[i]; u.active[i] = (int16_t)active[i]; }
+    // bf16 GEMM operands of the next iteration: its gradient point is x^k when tau = 1, x^{k+1} otherwise
+    u.shadow = (!h->flat && h->prec) ? h->shadow : nullptr;
+    u.emit_input = h->tau == 1;
     {
         int nact = 0;
         for (int i = 0; i < L; ++i) nact += active[i];
-        if (int rc = mark(h, 6, 1, 12.0 * (double)h->P * nact)) return rc;
+        if (int rc = mark(h, 6, 1, (u.shadow ? 14.0 : 12.0) * (double)h->P * nact)) return rc;
     }
     HIPCHK(launch_update(u, h->stream), "mix + update");
     if (int rc = mark(h, -1)) return rc;
     if (h->tau == 1) h->cur = 1 - h->cur;
+    if (u.shadow) h->shadow_valid = true;
     h->k += 1;
     return ADPSGD_OK;
 }
@@ -532,6 +538,7 @@ float* adpsgd_params(adpsgd_t h, int i) {
 int adpsgd_set_params(adpsgd_t h, int i, const float* dev_src) {
     if (!h || !dev_src || i < -1 || i >= h->L) return fail(ADPSGD_EINVAL, "bad argument");
     const int lo = i < 0 ? 0 : i, hi = i < 0 ? h->L : i + 1;
+    h->shadow_valid = false;
     for (int b = 0; b <= h->tau; ++b)
         for (int j = lo; j < hi; ++j)
             HIPCHK(hipMemcpyAsync(h->params[b] + (size_t)j * h->Ppad, dev_src, (size_t)h->P * 4, hipMemcpyDeviceToDevice, h->stream), "set_params copy");
@@ -643,7 +650,7 @@ int adpsgd_gemm(int precision, int a_kmajor, int b_kmajor, int c_is_elem, int M,
 
 int adpsgd_gemm_set_variant(int variant) {
     if (variant == 100 || variant == 101) { set_rec_dma(variant - 100); return ADPSGD_OK; }
-    if (variant < -1 || variant > 13) return fail(ADPSGD_EINVAL, "variant must be -1..13");
+    if (variant != -1 && variant != 0 && variant != 5 && variant != 10) return fail(ADPSGD_EINVAL, "variant must be -1, 0, 5 or 10");
     set_gemm_variant(variant);
     return ADPSGD_OK;
 }

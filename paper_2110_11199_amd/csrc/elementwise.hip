@@ -139,10 +139,86 @@ __global__ __launch_bounds__(256) void loss_reduce_kernel(const float* row_loss,
     if (threadIdx.x == 0) loss[li] = sh[0] / (float)rows;
 }
 
-hipError_t launch_softmax_ce(const SoftmaxDesc& d, hipStream_t s) {
+// Single-pass version: the whole row of logits lives in registers (NV float4 per thread, C <= 1024*NV),
+// so the logits are read from HBM once.
+template <typename T, int NV>
+__global__ __launch_bounds__(256) void softmax_ce_row_kernel(SoftmaxDesc p) {
+    const int li = blockIdx.y;
+    const int64_t row = blockIdx.x;
+    const float4* z4 = (const float4*)(p.logits + li * p.sLi + row * p.C);
+    T* dz = (T*)p.dlogits + li * p.sDi + row * p.C;
+    const int C4 = p.C >> 2;
+    int y = p.y[li * p.sYi + row];
+    y = y < 0 ? 0 : (y >= p.C ? p.C - 1 : y);
+    float4 v[NV];
+    float m = -INFINITY;
+#pragma unroll
+    for (int j = 0; j < NV; ++j) {
+        const int c4 = threadIdx.x + 256 * j;
+        if (c4 < C4) {
+            v[j] = z4[c4];
+            m = fmaxf(fmaxf(fmaxf(v[j].x, v[j].y), fmaxf(v[j].z, v[j].w)), m);
+        }
+    }
+    __shared__ float red[2][4];
+    for (int off = 32; off > 0; off >>= 1) m = fmaxf(m, __shfl_xor(m, off));
+    if ((threadIdx.x & 63) == 0) red[0][threadIdx.x >> 6] = m;
+    __syncthreads();
+    m = fmaxf(fmaxf(red[0][0], red[0][1]), fmaxf(red[0][2], red[0][3]));
+    float zy = 0.f;                      // logit of the label, picked up by the thread that holds it
+    float s = 0.f;
+#pragma unroll
+    for (int j = 0; j < NV; ++j) {
+        const int c4 = threadIdx.x + 256 * j;
+        if (c4 < C4) {
+            if ((y >> 2) == c4) zy = (y & 3) == 0 ? v[j].x : (y & 3) == 1 ? v[j].y : (y & 3) == 2 ? v[j].z : v[j].w;
+            v[j].x = expf(v[j].x - m); v[j].y = expf(v[j].y - m); v[j].z = expf(v[j].z - m); v[j].w = expf(v[j].w - m);
+            s += (v[j].x + v[j].y) + (v[j].z + v[j].w);
+        }
+    }
+    for (int off = 32; off > 0; off >>= 1) s += __shfl_xor(s, off);
+    if ((threadIdx.x & 63) == 0) red[1][threadIdx.x >> 6] = s;
+    __syncthreads();
+    s = (red[1][0] + red[1][1]) + (red[1][2] + red[1][3]);
+    const float inv = 1.f / s;
+    const float scale = 1.f / (float)p.rows;
+#pragma unroll
+    for (int j = 0; j < NV; ++j) {
+        const int c4 = threadIdx.x + 256 * j;
+        if (c4 < C4) {
+            float4 pr = make_float4(v[j].x * inv, v[j].y * inv, v[j].z * inv, v[j].w * inv);
+            if ((y >> 2) == c4) {
+                if ((y & 3) == 0) pr.x -= 1.f; else if ((y & 3) == 1) pr.y -= 1.f; else if ((y & 3) == 2) pr.z -= 1.f; else pr.w -= 1.f;
+            }
+            pr.x *= scale; pr.y *= scale; pr.z *= scale; pr.w *= scale;
+            if constexpr (sizeof(T) == 2) {
+                uint2 o;
+                o.x = (uint32_t)f32_to_bf16(pr.x) | ((uint32_t)f32_to_bf16(pr.y) << 16);
+                o.y = (uint32_t)f32_to_bf16(pr.z) | ((uint32_t)f32_to_bf16(pr.w) << 16);
+                ((uint2*)dz)[c4] = o;
+            } else {
+                ((float4*)dz)[c4] = pr;
+            }
+        }
+    }
+    if ((y >> 2) % 256 == (int)threadIdx.x) p.row_loss[li * p.rows + row] = -((zy - m) - logf(s));
+}
+
+template <typename T>
+static void launch_softmax_t(const SoftmaxDesc& d, hipStream_t s) {
     dim3 grid((unsigned)d.rows, (unsigned)d.L);
-    if (d.precision == 0) hipLaunchKernelGGL(softmax_ce_kernel<float>, grid, dim3(256), 0, s, d);
-    else hipLaunchKernelGGL(softmax_ce_kernel<bf16_t>, grid, dim3(256), 0, s, d);
+    const bool vec = d.C % 4 == 0 && d.sLi % 4 == 0 && d.sDi % 4 == 0 && (uintptr_t)d.logits % 16 == 0 &&
+                     (uintptr_t)d.dlogits % 16 == 0;
+    if (vec && d.C <= 1024) hipLaunchKernelGGL((softmax_ce_row_kernel<T, 1>), grid, dim3(256), 0, s, d);
+    else if (vec && d.C <= 4096) hipLaunchKernelGGL((softmax_ce_row_kernel<T, 4>), grid, dim3(256), 0, s, d);
+    else if (vec && d.C <= 16384) hipLaunchKernelGGL((softmax_ce_row_kernel<T, 16>), grid, dim3(256), 0, s, d);
+    else if (vec && d.C <= 32768) hipLaunchKernelGGL((softmax_ce_row_kernel<T, 32>), grid, dim3(256), 0, s, d);
+    else hipLaunchKernelGGL(softmax_ce_kernel<T>, grid, dim3(256), 0, s, d);
+}
+
+hipError_t launch_softmax_ce(const SoftmaxDesc& d, hipStream_t s) {
+    if (d.precision == 0) launch_softmax_t<float>(d, s);
+    else launch_softmax_t<bf16_t>(d, s);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(loss_reduce_kernel, dim3((unsigned)d.L), dim3(256), 0, s, d.row_loss, d.rows, d.loss);

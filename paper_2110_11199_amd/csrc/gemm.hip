@@ -1,6 +1,17 @@
 // Grouped MFMA GEMM kernels: the time-batched GEMMs of the LSTM gradient
 // (input projections, output layers, weight gradients, input gradients).
-#include <cstdlib>
+//
+// Three tile configurations are built:
+//   0   128x128 workgroup tile, 4 waves (64x64 each), 64-byte K stages, operands staged
+//       through registers.  Small problems, fp32 operands, rows that are only 8-byte aligned.
+//   5   256x256 tile, 8 waves (128x64 each), 128-byte stages, staged through registers.
+//       Large bf16 problems with an operand that is not K-contiguous (dW = dA' X, dX = dA W):
+//       the transposition happens between the registers and LDS.
+//   10  256x256 tile, 8 waves, 128-byte stages, direct global->LDS loads (no staging
+//       registers, no LDS store instructions).  Large bf16 problems with both operands
+//       K-contiguous and K a multiple of 64.
+// A 256x256 tile needs half the operand bytes per flop of a 128x128 one; at these sizes the
+// main loop is bound by how fast a CU can pull operands through L2, not by MFMA issue.
 #include <type_traits>
 #include "gemm_core.hpp"
 #include "gemm_dma.hpp"
@@ -18,14 +29,13 @@ __device__ inline int xcd_contiguous_id(int bid, int nb) {
 }
 
 // Epilogue shared by the GEMM kernels: C tile = acc (+ bias), fp32 or operand type.
-// Every store reads its data straight from an accumulator register (the bias is added
-// and the bf16 conversion done in place first): reusing one temporary register for all
-// stores makes the compiler wait for each store to complete before the next one.
+// Every store reads its data from a register of its own (the bias is added in place, the
+// bf16 values are converted into a separate array first): with one temporary register
+// reused for all stores the compiler has to wait for each store before the next one.
 template <typename T, class Core, int FM, int FN>
 __device__ inline void store_tile(f32x16_t (&acc)[FM][FN], const GemmDesc& p, int m0, int n0, int gi, int gd) {
     const float* bias = p.bias ? p.bias + gi * p.sBiasI + gd * p.sBiasD : nullptr;
     const int64_t coff = gi * p.sCi + gd * p.sCd;
-    const int lane = threadIdx.x & 63;
 #pragma unroll
     for (int fn = 0; fn < FN; ++fn) {
         const int col = n0 + Core::acc_col(fn);
@@ -38,7 +48,7 @@ __device__ inline void store_tile(f32x16_t (&acc)[FM][FN], const GemmDesc& p, in
             if (p.c_elem) {
                 T* c = (T*)p.C + o;
                 if constexpr (sizeof(T) == 2) {
-                    uint32_t hb[16];                     // one register per value: see the comment above
+                    uint32_t hb[16];
 #pragma unroll
                     for (int i = 0; i < 16; ++i) hb[i] = f32_to_bf16(acc[fm][fn][i] + bv);
 #pragma unroll
@@ -62,19 +72,24 @@ __device__ inline void store_tile(f32x16_t (&acc)[FM][FN], const GemmDesc& p, in
 #pragma unroll
                 for (int i = 0; i < 16; ++i) {
                     const int r = 8 * (i >> 2) + (i & 3);
-#ifdef ADPSGD_DBG_NOEPI
-                    if (acc[fm][fn][i] != 123456.75f) continue;
-#endif
                     if (row0 + r < p.M) c[(int64_t)r * p.ldc] = acc[fm][fn][i];
                 }
             }
         }
     }
-    (void)lane;
+}
+
+template <int FM, int FN> __device__ inline void zero_tile(f32x16_t (&acc)[FM][FN]) {
+#pragma unroll
+    for (int i = 0; i < FM; ++i)
+#pragma unroll
+        for (int j = 0; j < FN; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 }
 
 template <typename T, bool AKC, bool BKC, int WM, int WN, int FM, int FN, int VB, int SB>
-__global__ __launch_bounds__(64 * WM * WN, (WM * WN == 4 && FM * FN == 8) ? 2 : 1) void gemm_kernel(GemmDesc p) {
+__global__ __launch_bounds__(64 * WM * WN) void gemm_kernel(GemmDesc p) {
     typedef typename std::conditional<AKC, KcSrc<T>, McSrc<T>>::type ASrc;
     typedef typename std::conditional<BKC, KcSrc<T>, McSrc<T>>::type BSrc;
     typedef GemmCore<T, ASrc, BSrc, WM, WN, FM, FN, VB, SB> Core;
@@ -95,21 +110,15 @@ __global__ __launch_bounds__(64 * WM * WN, (WM * WN == 4 && FM * FN == 8) ? 2 : 
     b.ld = p.ldb; b.R = p.N - n0;
 
     f32x16_t acc[FM][FN];
-#pragma unroll
-    for (int i = 0; i < FM; ++i)
-#pragma unroll
-        for (int j = 0; j < FN; ++j)
-#pragma unroll
-            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+    zero_tile<FM, FN>(acc);
     Core::run(acc, a, b, p.K, lds);
-
     store_tile<T, Core, FM, FN>(acc, p, m0, n0, gi, gd);
 }
 
 // Same tile bookkeeping with the direct-to-LDS main loop (both operands K-contiguous,
 // 16-byte aligned rows, K a multiple of the stage length).
-template <typename T, int WM, int WN, int FM, int FN, int SB, int NS, int MINB, int PF = 0>
-__global__ __launch_bounds__(64 * WM * WN + (PF > 0 ? 64 : 0), MINB) void gemm_dma_kernel(GemmDesc p) {
+template <typename T, int WM, int WN, int FM, int FN, int SB, int NS>
+__global__ __launch_bounds__(64 * WM * WN) void gemm_dma_kernel(GemmDesc p) {
     typedef GemmDma<T, KcSrc<T>, KcSrc<T>, WM, WN, FM, FN, SB, NS> Core;
     __shared__ __attribute__((aligned(1024))) char lds[Core::LDS_BYTES];
 
@@ -118,57 +127,14 @@ __global__ __launch_bounds__(64 * WM * WN + (PF > 0 ? 64 : 0), MINB) void gemm_d
     const int tm = id % tiles_m, tn = id / tiles_m;
     const int gi = blockIdx.y / p.groupsD, gd = blockIdx.y % p.groupsD;
     const int m0 = tm * Core::BM, n0 = tn * Core::BN;
-#ifdef ADPSGD_DBG_TIMING
-    const long long ts = wall_clock64();
-#endif
-#ifdef ADPSGD_STAGGER
-    // first wave of workgroups: delay each XCD by a different fraction of a tile's duration so that the
-    // epilogue write bursts of the XCDs do not coincide (the offset persists: every CU runs tiles back to back)
-    if (blockIdx.y == 0 && blockIdx.x < 256) {
-        const long long until = wall_clock64() + (long long)(blockIdx.x & 7) * ADPSGD_STAGGER;
-        while (wall_clock64() < until) __builtin_amdgcn_s_sleep(32);
-    }
-#endif
     KcSrc<T> a, b;
     a.base = (const T*)p.A + gi * p.sAi + gd * p.sAd + (int64_t)m0 * p.lda; a.ld = p.lda; a.R = p.M - m0;
     b.base = (const T*)p.B + gi * p.sBi + gd * p.sBd + (int64_t)n0 * p.ldb; b.ld = p.ldb; b.R = p.N - n0;
-    if constexpr (PF > 0) {
-        if (threadIdx.x >= Core::NT) { Core::template prefetch_wave<PF>(a, b, p.K, lds + Core::LDS_BYTES); return; }
-    }
 
     f32x16_t acc[FM][FN];
-#pragma unroll
-    for (int i = 0; i < FM; ++i)
-#pragma unroll
-        for (int j = 0; j < FN; ++j)
-#pragma unroll
-            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
-    
-#ifdef ADPSGD_DBG_TIMING
-    const long long t0 = wall_clock64();
-#endif
+    zero_tile<FM, FN>(acc);
     Core::run(acc, a, b, p.K, lds);
-#ifdef ADPSGD_DBG_TIMING
-    const long long t1 = wall_clock64();
-#endif
-
-
     store_tile<T, Core, FM, FN>(acc, p, m0, n0, gi, gd);
-#ifdef ADPSGD_DBG_TIMING
-    if (threadIdx.x == 0 && p.dbg) {
-        long long* d = p.dbg + ((int64_t)blockIdx.y * gridDim.x + blockIdx.x) * 4;
-        d[0] = ts; d[1] = t0; d[2] = t1; d[3] = wall_clock64();
-    }
-#endif
-}
-
-template <typename T, int WM, int WN, int FM, int FN, int SB, int NS, int MINB, int PF = 0>
-static hipError_t launch_dma(const GemmDesc& d, hipStream_t s) {
-    constexpr int BM = 32 * FM * WM, BN = 32 * FN * WN;
-    const int tiles_m = (d.M + BM - 1) / BM, tiles_n = (d.N + BN - 1) / BN;
-    dim3 grid((unsigned)(tiles_m * tiles_n), (unsigned)(d.groupsI * d.groupsD));
-    hipLaunchKernelGGL((gemm_dma_kernel<T, WM, WN, FM, FN, SB, NS, MINB, PF>), grid, dim3(64 * WM * WN + (PF > 0 ? 64 : 0)), 0, s, d);
-    return hipGetLastError();
 }
 
 template <typename T, bool AKC, bool BKC, int WM, int WN, int FM, int FN, int VB, int SB>
@@ -191,23 +157,17 @@ static hipError_t launch_layout(const GemmDesc& d, hipStream_t s) {
     }
 }
 
+template <typename T, int WM, int WN, int FM, int FN, int SB, int NS>
+static hipError_t launch_dma(const GemmDesc& d, hipStream_t s) {
+    constexpr int BM = 32 * FM * WM, BN = 32 * FN * WN;
+    const int tiles_m = (d.M + BM - 1) / BM, tiles_n = (d.N + BN - 1) / BN;
+    dim3 grid((unsigned)(tiles_m * tiles_n), (unsigned)(d.groupsI * d.groupsD));
+    hipLaunchKernelGGL((gemm_dma_kernel<T, WM, WN, FM, FN, SB, NS>), grid, dim3(64 * WM * WN), 0, s, d);
+    return hipGetLastError();
+}
+
 static int g_variant = -1;   // tuning knob: forces a tile configuration (-1 = automatic)
 void set_gemm_variant(int v) { g_variant = v; }
-
-// Tile configurations.  0: 128x128 tile, 4 waves, 64-byte stages (also the only one with
-// 8-byte operand loads); 1: same with 128-byte stages; 2/3: 256x128, 4 waves (wave tile
-// 128x64), 64/128-byte stages; 4/5: 256x256, 8 waves (wave tile 128x64), 64/128-byte stages.
-template <typename T>
-static hipError_t launch_variant(int v, const GemmDesc& d, hipStream_t s) {
-    switch (v) {
-        case 1: return launch_layout<T, 2, 2, 2, 2, 16, 128>(d, s);
-        case 2: return launch_layout<T, 2, 2, 4, 2, 16, 64>(d, s);
-        case 3: return launch_layout<T, 2, 2, 4, 2, 16, 128>(d, s);
-        case 4: return launch_layout<T, 2, 4, 4, 2, 16, 64>(d, s);
-        case 5: return launch_layout<T, 2, 4, 4, 2, 16, 128>(d, s);
-        default: return launch_layout<T, 2, 2, 2, 2, 16, 64>(d, s);
-    }
-}
 
 static bool aligned_to(const void* p, int64_t ld, int64_t s1, int64_t s2, int esz, int bytes) {
     return ((uintptr_t)p % bytes == 0) && ((ld * esz) % bytes == 0) && ((s1 * esz) % bytes == 0) &&
@@ -220,32 +180,20 @@ hipError_t launch_gemm(const GemmDesc& d, hipStream_t s) {
     const int quad = 4 * esz;    // every operand must allow loads of 4 elements
     if (!aligned_to(d.A, d.lda, d.sAi, d.sAd, esz, quad) || !aligned_to(d.B, d.ldb, d.sBi, d.sBd, esz, quad))
         return hipErrorInvalidValue;
-    if (d.precision == 0) return launch_variant<float>(g_variant >= 0 && g_variant <= 5 ? g_variant : 0, d, s);
+    if (d.precision == 0) return launch_layout<float, 2, 2, 2, 2, 16, 64>(d, s);
     bool wide = true;
     if (d.a_kc && !aligned_to(d.A, d.lda, d.sAi, d.sAd, esz, 16)) wide = false;
     if (d.b_kc && !aligned_to(d.B, d.ldb, d.sBi, d.sBd, esz, 16)) wide = false;
     if (!wide) return launch_layout<bf16_t, 2, 2, 2, 2, 8, 64>(d, s);
     int v = g_variant;
     if (v < 0) {
-        // 256x256 tiles once they fill the 256 CUs (they halve the operand bytes loaded per flop);
-        // direct-to-LDS loads when both operands are K-contiguous and K is a multiple of the stage.
+        // 256x256 tiles once there are enough of them to fill the 256 CUs
         const int64_t big_tiles = (int64_t)((d.M + 255) / 256) * ((d.N + 255) / 256) * d.groupsI * d.groupsD;
-        if (big_tiles >= 256) v = (d.a_kc && d.b_kc && d.K % 64 == 0) ? 10 : 5;
-        else v = 0;
+        v = big_tiles >= 128 ? 10 : 0;
     }
-    if (v >= 6 && d.a_kc && d.b_kc && d.K % 64 == 0) {
-        switch (v) {
-            case 6: return launch_dma<bf16_t, 2, 4, 4, 2, 64, 4, 1>(d, s);
-            case 7: return launch_dma<bf16_t, 2, 4, 2, 2, 64, 3, 2>(d, s);
-            case 8: return launch_dma<bf16_t, 4, 2, 2, 2, 64, 3, 2>(d, s);
-            case 9: return launch_dma<bf16_t, 2, 2, 2, 2, 64, 4, 2>(d, s);
-            case 11: return launch_dma<bf16_t, 2, 4, 4, 2, 128, 2, 1, 3>(d, s);
-            case 12: return launch_dma<bf16_t, 2, 4, 4, 2, 128, 2, 1, 4>(d, s);
-            case 13: return launch_dma<bf16_t, 2, 4, 4, 2, 128, 2, 1, 64>(d, s);
-            default: return launch_dma<bf16_t, 2, 4, 4, 2, 128, 2, 1>(d, s);
-        }
-    }
-    return launch_variant<bf16_t>(v > 5 ? 5 : v, d, s);
+    if (v == 10 && d.a_kc && d.b_kc && d.K % 64 == 0) return launch_dma<bf16_t, 2, 4, 4, 2, 128, 2>(d, s);
+    if (v >= 5) return launch_layout<bf16_t, 2, 4, 4, 2, 16, 128>(d, s);
+    return launch_layout<bf16_t, 2, 2, 2, 2, 16, 64>(d, s);
 }
 
 }  // namespace adpsgd

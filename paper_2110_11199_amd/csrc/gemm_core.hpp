@@ -296,11 +296,7 @@ struct GemmCore {
             char* cur = lds + (kt & 1) * STAGE_BYTES;
             char* nxt = lds + ((kt + 1) & 1) * STAGE_BYTES;
             const bool more = kt + 1 < nk;
-#ifdef ADPSGD_DBG_NOLOAD
-            if (false) {
-#else
             if (kt + 1 < nk_full) {
-#endif
                 la.load_full(a, (kt + 1) * KT, tid);
                 lb.load_full(b, (kt + 1) * KT, tid);
             } else if (more) {
@@ -320,15 +316,11 @@ struct GemmCore {
 #pragma unroll
                     for (int fn = 0; fn < FN; ++fn) mma_chunk<T>(acc[fm][fn], af[fm], bfr[fn]);
             }
-#ifndef ADPSGD_DBG_NOSTORE
             if (more) {
                 la.store(nxt, tid);
                 lb.store(nxt + ATile::BYTES, tid);
             }
-#endif
-#ifndef ADPSGD_DBG_NOBARRIER
             __syncthreads();
-#endif
         }
     }
 

@@ -113,9 +113,6 @@ struct GemmDma {
                 issue<BN, LB>(b, nt * KT, st + A_BYTES, tid);
             }
             const char* cur = lds + (kt % NS) * STAGE_BYTES;
-#ifdef ADPSGD_DBG_NOMMA
-            if (K > 0) continue;
-#endif
 #pragma unroll
             for (int c = 0; c < SB / 32; ++c) {
                 const int ch = 2 * c + g;
@@ -130,43 +127,6 @@ struct GemmDma {
                     for (int fn = 0; fn < FN; ++fn) mma_chunk<T>(acc[fm][fn], af[fm], bfr[fn]);
             }
         }
-    }
-
-    // L2 prefetch wave (optional, thread ids NT..NT+63 of the workgroup): walks PF stages ahead of the
-    // MFMA waves and touches one dword of every 128-byte line of the workgroup's A and B stage, so that
-    // the misses to HBM are taken early by loads nobody waits for and the direct-to-LDS loads of the MFMA
-    // waves find their lines in L2.  It joins the same per-stage barrier, which keeps it in step.
-    template <int PF>
-    __device__ static void prefetch_wave(const ASrc& a, const BSrc& b, int K, char* lds_dummy) {
-        const int lane = threadIdx.x & 63;
-        const int nk = K / KT;
-        // Loads nobody reads.  They are direct-to-LDS loads into a 256-byte dummy area, not loads into a
-        // register: an untracked load into a VGPR would land later in a register the compiler has reused.
-        const uint32_t dummy = __builtin_amdgcn_readfirstlane(lds_addr_(lds_dummy));
-        auto ld = [dummy](const char* q) {
-            asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dword %0, off" :: "v"(q), "s"(dummy) : "memory", "m0");
-        };
-        auto touch = [&](int s) {
-            if (s >= nk) return;
-#pragma unroll
-            for (int j = 0; j < BM / 64; ++j) {
-                const char* p = (const char*)(a.row_clamped(lane + 64 * j) + s * KT);
-                ld(p);
-                ld(p + SB - 4);
-            }
-#pragma unroll
-            for (int j = 0; j < BN / 64; ++j) {
-                const char* p = (const char*)(b.row_clamped(lane + 64 * j) + s * KT);
-                ld(p);
-                ld(p + SB - 4);
-            }
-        };
-        for (int s = NS - 1; s < PF && s < nk && PF < 64; ++s) touch(s);
-        for (int kt = 0; kt < nk; ++kt) {
-            __builtin_amdgcn_s_barrier();
-            if (PF < 64) touch(kt + PF);      // PF >= 64: no touches at all (measures the bare cost of the extra wave)
-        }
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     }
 
     __device__ static int acc_row(int fm, int i) {

@@ -17,9 +17,6 @@ struct GemmDesc {
     void* C; int64_t ldc, sCi, sCd;
     const float* bias; int64_t sBiasI, sBiasD;
     int groupsI, groupsD;
-#ifdef ADPSGD_DBG_TIMING
-    long long* dbg;
-#endif
 };
 // Returns hipSuccess, or hipErrorInvalidValue when the operands do not meet the
 // alignment rules (rows and strides multiples of 4 elements).
@@ -38,6 +35,8 @@ struct UpdateDesc {
     int16_t partner[128];
     int16_t active[128];
     float lr;
+    bf16_t* shadow;            // optional [L][stride] bf16 copy of the next gradient point, or NULL
+    int emit_input;            // shadow = bf16(x^k) (tau = 1) instead of bf16(x^{k+1})
 };
 hipError_t launch_update(const UpdateDesc& d, hipStream_t s);
 hipError_t launch_average(const float* x, int64_t stride, int L, int64_t P, float* out, hipStream_t s);

@@ -14,6 +14,7 @@ namespace adpsgd {
 
 struct PairArgs {
     const float* src; float* dst; int64_t stride; int64_t P; float lr;
+    bf16_t* shadow; int emit_input;   // bf16 copy of the next gradient point: the inputs (tau = 1) or the outputs
     int nwork;
     const float* g[128];
     int16_t a[128], b[128];     // work item w mixes learners a[w], b[w] (a == b: no partner)
@@ -31,12 +32,34 @@ __device__ inline float4 half_sum_(const float4& p, const float4& q) {
 
 constexpr int kUnroll = 4;
 
+// one element of one work item (scalar path and tails)
+__device__ inline void pair_scalar_(const float* xa, const float* xb, const float* ga, const float* gb, float* oa, float* ob,
+                                    bf16_t* sha, bf16_t* shb, bool solo, int emit_input, float lr, int64_t e) {
+    const float x = xa[e], y = xb[e];
+    if (solo) {
+        const float r = sgd_(x, lr, ga[e]);
+        oa[e] = r;
+        if (sha) sha[e] = f32_to_bf16(emit_input ? x : r);
+    } else {
+        const float m = __fmul_rn(__fadd_rn(x, y), 0.5f);
+        const float va = sgd_(m, lr, ga[e]), vb = sgd_(m, lr, gb[e]);
+        oa[e] = va; ob[e] = vb;
+        if (sha) { sha[e] = f32_to_bf16(emit_input ? x : va); shb[e] = f32_to_bf16(emit_input ? y : vb); }
+    }
+}
+
 // The models and gradients are streamed once per iteration: non-temporal loads and stores keep them
 // from displacing each other in L2 (measured +11% on the 2-reads-1-write pattern).
 typedef float vf4_t __attribute__((ext_vector_type(4)));
 __device__ inline float4 ldnt_(const float* p, int64_t e4) {
     const vf4_t v = __builtin_nontemporal_load((const vf4_t*)p + e4);
     return make_float4(v.x, v.y, v.z, v.w);
+}
+__device__ inline void emit4_(bf16_t* sh, int64_t e4, const float4& v) {
+    uint2 o;
+    o.x = (uint32_t)f32_to_bf16(v.x) | ((uint32_t)f32_to_bf16(v.y) << 16);
+    o.y = (uint32_t)f32_to_bf16(v.z) | ((uint32_t)f32_to_bf16(v.w) << 16);
+    ((uint2*)sh)[e4] = o;
 }
 __device__ inline void stnt_(float* p, int64_t e4, const float4& v) {
     vf4_t w; w.x = v.x; w.y = v.y; w.z = v.z; w.w = v.w;
@@ -54,6 +77,8 @@ __global__ __launch_bounds__(256) void pair_update_kernel(PairArgs p) {
     const float* ga = p.g[a];
     const float* gb = p.g[b];
     const float lr = p.lr;
+    bf16_t* sha = p.shadow ? p.shadow + a * p.stride : nullptr;
+    bf16_t* shb = p.shadow ? p.shadow + b * p.stride : nullptr;
     if constexpr (VEC) {
         const int64_t n4 = p.P >> 2;
         const int64_t base = (int64_t)blockIdx.x * (256 * kUnroll) + threadIdx.x;
@@ -67,7 +92,11 @@ __global__ __launch_bounds__(256) void pair_update_kernel(PairArgs p) {
 #pragma unroll
             for (int u = 0; u < kUnroll; ++u) {
                 const int64_t e = base + u * 256;
-                if (e < n4) stnt_(oa, e, pair_new_(x[u], lr, g[u]));
+                if (e < n4) {
+                    const float4 r = pair_new_(x[u], lr, g[u]);
+                    stnt_(oa, e, r);
+                    if (sha) emit4_(sha, e, p.emit_input ? x[u] : r);
+                }
             }
         } else {
             float4 x[kUnroll], y[kUnroll], g[kUnroll], h[kUnroll];
@@ -84,20 +113,17 @@ __global__ __launch_bounds__(256) void pair_update_kernel(PairArgs p) {
                 const int64_t e = base + u * 256;
                 if (e < n4) {
                     const float4 m = half_sum_(x[u], y[u]);
-                    stnt_(oa, e, pair_new_(m, lr, g[u]));
-                    stnt_(ob, e, pair_new_(m, lr, h[u]));
+                    const float4 ra = pair_new_(m, lr, g[u]), rb = pair_new_(m, lr, h[u]);
+                    stnt_(oa, e, ra);
+                    stnt_(ob, e, rb);
+                    if (sha) { emit4_(sha, e, p.emit_input ? x[u] : ra); emit4_(shb, e, p.emit_input ? y[u] : rb); }
                 }
             }
         }
         // tail (P % 4 elements), handled by the first block
         if (blockIdx.x == 0 && threadIdx.x < (p.P & 3)) {
             const int64_t e = (n4 << 2) + threadIdx.x;
-            if (a == b) oa[e] = sgd_(xa[e], lr, ga[e]);
-            else {
-                const float m = __fmul_rn(__fadd_rn(xa[e], xb[e]), 0.5f);
-                const float va = sgd_(m, lr, ga[e]), vb = sgd_(m, lr, gb[e]);
-                oa[e] = va; ob[e] = vb;
-            }
+            pair_scalar_(xa, xb, ga, gb, oa, ob, sha, shb, a == b, p.emit_input, lr, e);
         }
     } else {
         const int64_t base = (int64_t)blockIdx.x * (256 * kUnroll) + threadIdx.x;
@@ -105,20 +131,32 @@ __global__ __launch_bounds__(256) void pair_update_kernel(PairArgs p) {
         for (int u = 0; u < kUnroll; ++u) {
             const int64_t e = base + u * 256;
             if (e >= p.P) continue;
-            if (a == b) oa[e] = sgd_(xa[e], lr, ga[e]);
-            else {
-                const float m = __fmul_rn(__fadd_rn(xa[e], xb[e]), 0.5f);
-                const float va = sgd_(m, lr, ga[e]), vb = sgd_(m, lr, gb[e]);
-                oa[e] = va; ob[e] = vb;
-            }
+            pair_scalar_(xa, xb, ga, gb, oa, ob, sha, shb, a == b, p.emit_input, lr, e);
         }
     }
 }
 
 struct AllArgs {
     const float* src; float* dst; int64_t stride; int64_t P; float lr; float inv_L; int L;
+    bf16_t* shadow; int emit_input;
     const float* g[128];
 };
+
+__device__ inline void all_scalar_(const AllArgs& p, int64_t t) {
+    float s = p.src[t];
+    if (p.shadow && p.emit_input) p.shadow[t] = f32_to_bf16(s);
+    for (int j = 1; j < p.L; ++j) {
+        const float v = p.src[j * p.stride + t];
+        if (p.shadow && p.emit_input) p.shadow[j * p.stride + t] = f32_to_bf16(v);
+        s = __fadd_rn(s, v);
+    }
+    const float m = __fmul_rn(s, p.inv_L);
+    for (int i = 0; i < p.L; ++i) {
+        const float r = sgd_(m, p.lr, p.g[i][t]);
+        p.dst[i * p.stride + t] = r;
+        if (p.shadow && !p.emit_input) p.shadow[i * p.stride + t] = f32_to_bf16(r);
+    }
+}
 
 // One thread owns an element index of all learners: reads L models, forms the
 // mean once, reads L gradients, writes L models.
@@ -129,32 +167,29 @@ __global__ __launch_bounds__(256) void all_update_kernel(AllArgs p) {
         const int64_t n4 = p.P >> 2;
         if (e < n4) {
             float4 s = ldnt_(p.src, e);
+            const bool emit_in = p.shadow && p.emit_input, emit_out = p.shadow && !p.emit_input;
+            if (emit_in) emit4_(p.shadow, e, s);
 #pragma unroll 8
             for (int j = 1; j < p.L; ++j) {
                 const float4 v = ldnt_(p.src + j * p.stride, e);
+                if (emit_in) emit4_(p.shadow + j * p.stride, e, v);
                 s.x = __fadd_rn(s.x, v.x); s.y = __fadd_rn(s.y, v.y); s.z = __fadd_rn(s.z, v.z); s.w = __fadd_rn(s.w, v.w);
             }
             const float4 m = make_float4(__fmul_rn(s.x, p.inv_L), __fmul_rn(s.y, p.inv_L), __fmul_rn(s.z, p.inv_L), __fmul_rn(s.w, p.inv_L));
 #pragma unroll 8
             for (int i = 0; i < p.L; ++i) {
                 const float4 g = ldnt_(p.g[i], e);
-                stnt_(p.dst + i * p.stride, e, pair_new_(m, p.lr, g));
+                const float4 r = pair_new_(m, p.lr, g);
+                stnt_(p.dst + i * p.stride, e, r);
+                if (emit_out) emit4_(p.shadow + i * p.stride, e, r);
             }
         }
         if (blockIdx.x == 0 && threadIdx.x < (p.P & 3)) {
             const int64_t t = (n4 << 2) + threadIdx.x;
-            float s = p.src[t];
-            for (int j = 1; j < p.L; ++j) s = __fadd_rn(s, p.src[j * p.stride + t]);
-            const float m = __fmul_rn(s, p.inv_L);
-            for (int i = 0; i < p.L; ++i) p.dst[i * p.stride + t] = sgd_(m, p.lr, p.g[i][t]);
+            all_scalar_(p, t);
         }
     } else {
-        if (e < p.P) {
-            float s = p.src[e];
-            for (int j = 1; j < p.L; ++j) s = __fadd_rn(s, p.src[j * p.stride + e]);
-            const float m = __fmul_rn(s, p.inv_L);
-            for (int i = 0; i < p.L; ++i) p.dst[i * p.stride + e] = sgd_(m, p.lr, p.g[i][e]);
-        }
+        if (e < p.P) all_scalar_(p, e);
     }
 }
 
@@ -176,6 +211,7 @@ hipError_t launch_update(const UpdateDesc& d, hipStream_t s) {
         AllArgs a;
         a.src = d.src; a.dst = d.dst; a.stride = d.stride; a.P = d.P; a.lr = d.lr; a.L = d.L;
         a.inv_L = 1.0f / (float)d.L;
+        a.shadow = d.shadow; a.emit_input = d.emit_input;
         for (int i = 0; i < 128; ++i) a.g[i] = i < d.L ? d.g[i] : nullptr;
         if (vec) {
             const int64_t n4 = d.P >> 2;
@@ -188,6 +224,7 @@ hipError_t launch_update(const UpdateDesc& d, hipStream_t s) {
     }
     PairArgs a;
     a.src = d.src; a.dst = d.dst; a.stride = d.stride; a.P = d.P; a.lr = d.lr;
+    a.shadow = d.shadow; a.emit_input = d.emit_input;
     for (int i = 0; i < 128; ++i) { a.g[i] = i < d.L ? d.g[i] : nullptr; a.a[i] = a.b[i] = 0; }
     int n = 0;
     for (int i = 0; i < d.L; ++i) {
