@@ -173,10 +173,10 @@ __global__ __launch_bounds__(256) void rec_forward_kernel(RecDesc p) {
     typedef GemmCore<T, KcSrc<T>, GateSrc<T>, WM, WN, 1, 4, VB> Core;
     __shared__ __attribute__((aligned(16))) char lds[Core::LDS_BYTES];
     const int D = p.D, H = p.H, B = p.B;
-    const int li = blockIdx.y / D, d = blockIdx.y % D;
+    const int li = blockIdx.x / D, d = blockIdx.x % D;      // groups on x: the tiles of one (learner, direction) share an XCD and its L2
     const int t = d == 0 ? p.step : p.T - 1 - p.step;
     const int tp = d == 0 ? t - 1 : t + 1;
-    const int u0 = blockIdx.x * (32 * WN), b0 = blockIdx.z * (32 * WM);
+    const int u0 = blockIdx.y * (32 * WN), b0 = blockIdx.z * (32 * WM);
     f32x16_t acc[1][4];
     zero_acc<4>(acc);
     FwdInputs in;
@@ -198,11 +198,11 @@ __global__ __launch_bounds__(256) void rec_backward_kernel(RecDesc p) {
     typedef GemmCore<T, KcSrc<T>, McSrc<T>, WM, WN, 1, FN, VB> Core;
     __shared__ __attribute__((aligned(16))) char lds[Core::LDS_BYTES];
     const int D = p.D, H = p.H, B = p.B;
-    const int li = blockIdx.y / D, d = blockIdx.y % D;
+    const int li = blockIdx.x / D, d = blockIdx.x % D;      // groups on x: the tiles of one (learner, direction) share an XCD and its L2
     const int t = d == 0 ? p.T - 1 - p.step : p.step;     // reverse of the forward processing order
     const int tn = d == 0 ? t + 1 : t - 1;                 // frame handled by the previous launch
     const int tp = d == 0 ? t - 1 : t + 1;                 // frame the forward pass processed before t
-    const int u0 = blockIdx.x * Core::BN, b0 = blockIdx.z * Core::BM;
+    const int u0 = blockIdx.y * Core::BN, b0 = blockIdx.z * Core::BM;
     const int64_t G4 = (int64_t)D * 4 * H;
     f32x16_t acc[1][FN];
     zero_acc<FN>(acc);
@@ -225,10 +225,10 @@ __global__ __launch_bounds__(256) void rec_forward_dma_kernel(RecDesc p) {
     typedef GemmDma<T, KcSrc<T>, GateSrc<T>, WM, WN, 1, 4, SB, NS> Core;
     __shared__ __attribute__((aligned(1024))) char lds[Core::LDS_BYTES];
     const int D = p.D, H = p.H, B = p.B;
-    const int li = blockIdx.y / D, d = blockIdx.y % D;
+    const int li = blockIdx.x / D, d = blockIdx.x % D;      // groups on x: the tiles of one (learner, direction) share an XCD and its L2
     const int t = d == 0 ? p.step : p.T - 1 - p.step;
     const int tp = d == 0 ? t - 1 : t + 1;
-    const int u0 = blockIdx.x * (32 * WN), b0 = blockIdx.z * (32 * WM);
+    const int u0 = blockIdx.y * (32 * WN), b0 = blockIdx.z * (32 * WM);
     f32x16_t acc[1][4];
     zero_acc<4>(acc);
     FwdInputs in;
@@ -242,20 +242,21 @@ __global__ __launch_bounds__(256) void rec_forward_dma_kernel(RecDesc p) {
         b.ld = H; b.H = H; b.u0 = u0;
         Core::run(acc, a, b, H, lds);
     }
-    forward_epilogue<T, Core>(p, acc, in, li, d, t, u0, b0);
+        forward_epilogue<T, Core>(p, acc, in, li, d, t, u0, b0);
+
 }
 
 // B operand = transposed copy of W_h: whT [D][H][4H], row u contiguous over the 4H gate rows.
 template <typename T, int WM, int WN, int FN, int SB, int NS>
-__global__ __launch_bounds__(256) void rec_backward_dma_kernel(RecDesc p) {
+__global__ __launch_bounds__(64 * WM * WN) void rec_backward_dma_kernel(RecDesc p) {
     typedef GemmDma<T, KcSrc<T>, KcSrc<T>, WM, WN, 1, FN, SB, NS> Core;
     __shared__ __attribute__((aligned(1024))) char lds[Core::LDS_BYTES];
     const int D = p.D, H = p.H, B = p.B;
-    const int li = blockIdx.y / D, d = blockIdx.y % D;
+    const int li = blockIdx.x / D, d = blockIdx.x % D;      // groups on x: the tiles of one (learner, direction) share an XCD and its L2
     const int t = d == 0 ? p.T - 1 - p.step : p.step;
     const int tn = d == 0 ? t + 1 : t - 1;
     const int tp = d == 0 ? t - 1 : t + 1;
-    const int u0 = blockIdx.x * Core::BN, b0 = blockIdx.z * Core::BM;
+    const int u0 = blockIdx.y * Core::BN, b0 = blockIdx.z * Core::BM;
     const int64_t G4 = (int64_t)D * 4 * H;
     f32x16_t acc[1][FN];
     zero_acc<FN>(acc);
@@ -267,7 +268,8 @@ __global__ __launch_bounds__(256) void rec_backward_dma_kernel(RecDesc p) {
         b.ld = (int64_t)4 * H; b.R = H - u0;
         Core::run(acc, a, b, 4 * H, lds);
     }
-    backward_epilogue<T, Core, FN>(p, acc, li, d, t, tp, u0, b0);
+        backward_epilogue<T, Core, FN>(p, acc, li, d, t, tp, u0, b0);
+
 }
 
 // ---- launchers ----------------------------------------------------------------------
@@ -276,13 +278,13 @@ template <typename T, int VB>
 static hipError_t fwd_t(const RecDesc& d, hipStream_t s) {
     const unsigned groups = (unsigned)(d.L * d.D);
     if (d.B > 64) {
-        dim3 grid((d.H + 31) / 32, groups, (d.B + 127) / 128);
+        dim3 grid(groups, (d.H + 31) / 32, (d.B + 127) / 128);
         hipLaunchKernelGGL((rec_forward_kernel<T, 4, 1, VB>), grid, dim3(256), 0, s, d);
     } else if (d.B > 32) {
-        dim3 grid((d.H + 63) / 64, groups, (d.B + 63) / 64);
+        dim3 grid(groups, (d.H + 63) / 64, (d.B + 63) / 64);
         hipLaunchKernelGGL((rec_forward_kernel<T, 2, 2, VB>), grid, dim3(256), 0, s, d);
     } else {
-        dim3 grid((d.H + 127) / 128, groups, (d.B + 31) / 32);
+        dim3 grid(groups, (d.H + 127) / 128, (d.B + 31) / 32);
         hipLaunchKernelGGL((rec_forward_kernel<T, 1, 4, VB>), grid, dim3(256), 0, s, d);
     }
     return hipGetLastError();
@@ -292,13 +294,13 @@ template <typename T, int VB>
 static hipError_t bwd_t(const RecDesc& d, hipStream_t s) {
     const unsigned groups = (unsigned)(d.L * d.D);
     if (d.B > 64) {
-        dim3 grid((d.H + 63) / 64, groups, (d.B + 127) / 128);
+        dim3 grid(groups, (d.H + 63) / 64, (d.B + 127) / 128);
         hipLaunchKernelGGL((rec_backward_kernel<T, 4, 1, 2, VB>), grid, dim3(256), 0, s, d);
     } else if (d.B > 32) {
-        dim3 grid((d.H + 63) / 64, groups, (d.B + 63) / 64);
+        dim3 grid(groups, (d.H + 63) / 64, (d.B + 63) / 64);
         hipLaunchKernelGGL((rec_backward_kernel<T, 2, 2, 1, VB>), grid, dim3(256), 0, s, d);
     } else {
-        dim3 grid((d.H + 127) / 128, groups, (d.B + 31) / 32);
+        dim3 grid(groups, (d.H + 127) / 128, (d.B + 31) / 32);
         hipLaunchKernelGGL((rec_backward_kernel<T, 1, 4, 1, VB>), grid, dim3(256), 0, s, d);
     }
     return hipGetLastError();
@@ -322,10 +324,10 @@ hipError_t launch_rec_forward(const RecDesc& d, hipStream_t s) {
     if (dma_ok(d)) {
         const unsigned groups = (unsigned)(d.L * d.D);
         if (d.B > 64) {
-            dim3 grid((d.H + 31) / 32, groups, (d.B + 127) / 128);
+            dim3 grid(groups, (d.H + 31) / 32, (d.B + 127) / 128);
             hipLaunchKernelGGL((rec_forward_dma_kernel<bf16_t, 4, 1, 128, 4>), grid, dim3(256), 0, s, d);
         } else {
-            dim3 grid((d.H + 63) / 64, groups, (d.B + 63) / 64);
+            dim3 grid(groups, (d.H + 63) / 64, (d.B + 63) / 64);
             hipLaunchKernelGGL((rec_forward_dma_kernel<bf16_t, 2, 2, 128, 3>), grid, dim3(256), 0, s, d);
         }
         return hipGetLastError();
@@ -339,10 +341,10 @@ hipError_t launch_rec_backward(const RecDesc& d, hipStream_t s) {
     if (dma_ok(d) && d.whT != nullptr) {
         const unsigned groups = (unsigned)(d.L * d.D);
         if (d.B > 64) {
-            dim3 grid((d.H + 127) / 128, groups, (d.B + 127) / 128);
-            hipLaunchKernelGGL((rec_backward_dma_kernel<bf16_t, 4, 1, 4, 128, 4>), grid, dim3(256), 0, s, d);
+            dim3 grid(groups, (d.H + 127) / 128, (d.B + 127) / 128);
+            hipLaunchKernelGGL((rec_backward_dma_kernel<bf16_t, 4, 2, 2, 128, 4>), grid, dim3(512), 0, s, d);
         } else {
-            dim3 grid((d.H + 127) / 128, groups, (d.B + 63) / 64);
+            dim3 grid(groups, (d.H + 127) / 128, (d.B + 63) / 64);
             hipLaunchKernelGGL((rec_backward_dma_kernel<bf16_t, 2, 2, 2, 128, 4>), grid, dim3(256), 0, s, d);
         }
         return hipGetLastError();
