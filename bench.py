@@ -95,8 +95,9 @@ def run_flat(wl, steps, warmup, seed=0):
     return dt, prof, active
 
 
-def cpu_baseline(wl, seed=0):
-    """The numpy oracle, as it stands, on one learner's minibatch of the workload."""
+def cpu_baseline(wl, seed=0, budget_s=12.0):
+    """The numpy oracle, as it stands, on learner minibatches of the workload until about budget_s
+    seconds of CPU work are spent."""
     import numpy as np
     from paper_2110_11199_amd import synth
     from oracle import lstm
@@ -109,13 +110,26 @@ def cpu_baseline(wl, seed=0):
                        wl.batch, wl.frames)
     w0 = synth.initial_model(seed, lstm.param_count(shape), wl.init_scale)
     cdf = synth.zipf_cdf(wl.classes) if wl.label_dist == "zipf" else None
-    f, y = synth.batch(wl, seed, 0, 0, cdf)
-    t0 = time.perf_counter()
-    lstm.loss_and_grad(shape, w0, f, y, np.float32)
-    dt = time.perf_counter() - t0
-    return {"value": wl.batch * wl.frames / dt, "unit": "frames/s", "cores": int(cores), "kind": "oracle",
-            "sample": "gradient of 1 of the %d learner minibatches of one %s iteration (%.1f s); the mixing/update "
-                      "part of the oracle is elementwise and under 1%% of that" % (wl.L, wl.name, dt)}
+    done, dt = 0, 0.0
+    while done < wl.L and dt < budget_s:
+        f, y = synth.batch(wl, seed, 0, done, cdf)
+        t0 = time.perf_counter()
+        lstm.loss_and_grad(shape, w0, f, y, np.float32)
+        dt += time.perf_counter() - t0
+        done += 1
+    return {"value": done * wl.batch * wl.frames / dt, "unit": "frames/s", "cores": int(cores), "kind": "oracle",
+            "sample": "gradients of %d of the %d learner minibatches of one %s iteration (%.1f s of oracle time); the "
+                      "mixing/update part of the oracle is elementwise and under 1%% of that" % (done, wl.L, wl.name, dt)}
+
+
+# HBM traffic per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (KiB per dispatch), scaled by what
+# the same counters read for cast_bf16_kernel, whose size is known (FETCH_SIZE reads 0.5x its bytes, WRITE_SIZE
+# 1.0x): profiles/hbm_traffic_cfg4_cfg5.txt.  Keyed by workload; bytes per launch of the named kernel class.
+TRAFFIC = {
+    ("cfg4", "batched_gemm"): 5.06e9,     # mean over the 29 time-batched GEMM launches of one iteration
+    ("cfg4", "mix_update"): 32.5e9,       # all_update_kernel with the bf16 copy written along
+    ("cfg5", "mix_update"): 93.2e9,       # pair_update_kernel, mean over the profiled iterations
+}
 
 
 def main():
@@ -140,12 +154,14 @@ def main():
     out = {"metric": METRIC, "unit": "frames/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
            "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "data": "synthetic"}
 
-    def update_roofline(prof, steps):
-        u = prof["mix_update"]
-        gbs = u["work"] / (u["ms"] * 1e-3) / 1e9 if u["ms"] > 0 else 0.0
+    def hbm_roofline(prof, phases, kernel, workload, traffic_key=None):
+        ms = sum(prof[p]["ms"] for p in phases)
+        nbytes = sum(prof[p]["bytes"] for p in phases)
+        launches = max(sum(prof[p]["launches"] for p in phases), 1)
+        gbs = nbytes / (ms * 1e-3) / 1e9 if ms > 0 else 0.0
         return {"bound": "hbm", "achieved": gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": gbs / PEAK_HBM_GBS,
-                "traffic": None, "kernel": "pair_update_kernel/all_update_kernel",
-                "avg_launch_ms": u["ms"] / max(u["launches"], 1), "bytes_per_launch": u["work"] / max(u["launches"], 1)}
+                "traffic": TRAFFIC.get((workload, traffic_key)) if traffic_key else None, "kernel": kernel,
+                "avg_launch_ms": ms / launches, "algorithmic_bytes_per_launch": nbytes / launches}
 
     if wl.flat_params:
         dt, prof, active = run_flat(wl, args.steps, args.warmup)
@@ -154,7 +170,7 @@ def main():
                     "learner_steps_per_s": active / dt,
                     "config": {"workload": wl.name, "L": wl.L, "flat_params": wl.flat_params, "pattern": "random ring",
                                "straggler_p": wl.straggler_p, "note": "model-free: no frames"},
-                    "roofline": update_roofline(prof, args.steps)})
+                    "roofline": hbm_roofline(prof, ["mix_update"], "pair_update_kernel", wl.name, "mix_update")})
         out["mix_update_GBps"] = out["roofline"]["achieved"]
     else:
         dt, prof, loss = run_model(wl, args.steps, args.warmup)
@@ -165,8 +181,9 @@ def main():
         tf = g["work"] / (g["ms"] * 1e-3) / 1e12 if g["ms"] > 0 else 0.0
         rec_ms = prof["recurrent_fwd"]["ms"] + prof["recurrent_bwd"]["ms"]
         rec_work = prof["recurrent_fwd"]["work"] + prof["recurrent_bwd"]["work"]
-        rec_tf = rec_work / (rec_ms * 1e-3) / 1e12 if rec_ms > 0 else 0.0
         peak = PEAK_TFLOPS[dtype]
+        rec = hbm_roofline(prof, ["recurrent_fwd", "recurrent_bwd"], "rec_forward_*_kernel + rec_backward_*_kernel", wl.name)
+        rec["mfma_TFLOPs"] = rec_work / (rec_ms * 1e-3) / 1e12 if rec_ms > 0 else 0.0
         out.update({
             "value": frames / (ms * 1e-3), "ms_per_step": ms, "dtype": dtype,
             "learner_steps_per_s": wl.L / (ms * 1e-3),
@@ -177,19 +194,19 @@ def main():
             "mean_loss_last_step": loss,
             "phases_ms_per_step": {k: v["ms"] / args.steps for k, v in prof.items()},
             "roofline": {"bound": "mfma", "achieved": tf, "peak": peak, "unit": "TFLOP/s", "frac": tf / peak,
-                         "traffic": None, "kernel": "gemm_kernel (time-batched GEMMs)",
+                         "traffic": TRAFFIC.get((wl.name, "batched_gemm")),
+                         "kernel": "gemm_kernel / gemm_dma_kernel (time-batched GEMMs)",
                          "launches_per_step": g["launches"] / args.steps,
                          "avg_launch_ms": g["ms"] / max(g["launches"], 1),
-                         "flops_per_launch": g["work"] / max(g["launches"], 1)},
-            "roofline_recurrent": {"bound": "hbm-or-mfma", "achieved": rec_tf, "peak": peak, "unit": "TFLOP/s",
-                                   "frac": rec_tf / peak, "kernel": "rec_forward_kernel + rec_backward_kernel",
-                                   "avg_launch_ms": rec_ms / max(prof["recurrent_fwd"]["launches"] + prof["recurrent_bwd"]["launches"], 1)},
-            "roofline_update": update_roofline(prof, args.steps),
+                         "flops_per_launch": g["work"] / max(g["launches"], 1),
+                         "algorithmic_bytes_per_launch": g["bytes"] / max(g["launches"], 1)},
+            "roofline_recurrent": rec,
+            "roofline_update": hbm_roofline(prof, ["mix_update"], "all_update_kernel / pair_update_kernel", wl.name, "mix_update"),
         })
         if args.mix_steps > 0:
             w5 = synth.WORKLOADS["cfg5"]
             dt5, prof5, active5 = run_flat(w5, args.mix_steps, 2)
-            r5 = update_roofline(prof5, args.mix_steps)
+            r5 = hbm_roofline(prof5, ["mix_update"], "pair_update_kernel", "cfg5", "mix_update")
             r5.update({"workload": "cfg5", "steps": args.mix_steps, "ms_per_step": dt5 / args.mix_steps * 1e3,
                        "learner_steps_per_s": active5 / dt5})
             out["mix_update"] = r5

@@ -171,11 +171,12 @@ int adpsgd_average(adpsgd_t h, float* dev_out);
  * host_ms[7] GPU milliseconds, host_launches[7] kernel launches, host_work[7]
  * algorithmic work (flops 2*M*N*K summed for phases 1-3; bytes, 12 per active
  * learner and element (14 when the bf16 copy of the model is written along), for
- * phase 6; 0 elsewhere).  Any pointer may be NULL.
+ * phase 6; 0 elsewhere), host_bytes[7] algorithmic HBM bytes of phases 1-3 and 6
+ * (every operand and result counted once per launch).  Any pointer may be NULL.
  * Each change of phase costs one HIP event; they are kept until destroy.        */
 #define ADPSGD_PHASES 7
 int adpsgd_set_profiling(adpsgd_t h, int enable);
-int adpsgd_profile(adpsgd_t h, float* host_ms, int32_t* host_launches, double* host_work);
+int adpsgd_profile(adpsgd_t h, float* host_ms, int32_t* host_launches, double* host_work, double* host_bytes);
 
 /* Release the handle (host memory only; the workspace stays the caller's).     */
 void adpsgd_destroy(adpsgd_t h);

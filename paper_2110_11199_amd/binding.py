@@ -59,7 +59,7 @@ _lib.adpsgd_iteration.argtypes = [_vp]
 _lib.adpsgd_iteration.restype = _i64
 _lib.adpsgd_average.argtypes = [_vp, _vp]
 _lib.adpsgd_set_profiling.argtypes = [_vp, C.c_int]
-_lib.adpsgd_profile.argtypes = [_vp, C.POINTER(C.c_float), _i32p, C.POINTER(C.c_double)]
+_lib.adpsgd_profile.argtypes = [_vp, C.POINTER(C.c_float), _i32p, C.POINTER(C.c_double), C.POINTER(C.c_double)]
 _lib.adpsgd_destroy.argtypes = [_vp]
 _lib.adpsgd_destroy.restype = None
 _lib.adpsgd_last_error.restype = C.c_char_p
@@ -170,9 +170,9 @@ def adpsgd_set_profiling(h, enable):
 
 def adpsgd_profile(h):
     n = len(PHASES)
-    ms, cnt, work = (C.c_float * n)(), (C.c_int32 * n)(), (C.c_double * n)()
-    _check(_lib.adpsgd_profile(h, ms, cnt, work))
-    return {PHASES[i]: {"ms": ms[i], "launches": cnt[i], "work": work[i]} for i in range(n)}
+    ms, cnt, work, nbytes = (C.c_float * n)(), (C.c_int32 * n)(), (C.c_double * n)(), (C.c_double * n)()
+    _check(_lib.adpsgd_profile(h, ms, cnt, work, nbytes))
+    return {PHASES[i]: {"ms": ms[i], "launches": cnt[i], "work": work[i], "bytes": nbytes[i]} for i in range(n)}
 
 
 def adpsgd_gemm_set_variant(v):

@@ -87,6 +87,7 @@ struct Profiler {
     int cur = -1;
     int launches[ADPSGD_PHASES];
     double work[ADPSGD_PHASES];
+    double bytes[ADPSGD_PHASES];      // algorithmic HBM bytes (each operand and result once)
 };
 
 struct adpsgd_handle {
@@ -212,10 +213,10 @@ size_t plan(adpsgd_handle* h, void* base) {
 }
 
 // Marks the start of work belonging to `phase` (-1: end of the step).
-int mark(adpsgd_handle* h, int phase, int launches = 0, double work = 0.0) {
+int mark(adpsgd_handle* h, int phase, int launches = 0, double work = 0.0, double bytes = 0.0) {
     Profiler& p = h->prof;
     if (!p.on) return ADPSGD_OK;
-    if (phase >= 0) { p.launches[phase] += launches; p.work[phase] += work; }
+    if (phase >= 0) { p.launches[phase] += launches; p.work[phase] += work; p.bytes[phase] += bytes; }
     if (phase == p.cur) return ADPSGD_OK;
     const size_t need = p.seg_phase.size() + 1;     // events recorded so far + this one
     while (p.ev.size() < need) {
@@ -232,11 +233,13 @@ int mark(adpsgd_handle* h, int phase, int launches = 0, double work = 0.0) {
 void prof_reset(adpsgd_handle* h) {
     Profiler& p = h->prof;
     p.seg_phase.clear(); p.cur = -1;
-    for (int i = 0; i < ADPSGD_PHASES; ++i) { p.launches[i] = 0; p.work[i] = 0.0; }
+    for (int i = 0; i < ADPSGD_PHASES; ++i) { p.launches[i] = 0; p.work[i] = 0.0; p.bytes[i] = 0.0; }
 }
 
 int gemm(adpsgd_handle* h, const GemmDesc& d, const char* what) {
-    if (int rc = mark(h, 1, 1, 2.0 * d.M * d.N * d.K * d.groupsI * d.groupsD)) return rc;
+    const double esz = d.precision ? 2.0 : 4.0, g = (double)d.groupsI * d.groupsD;
+    if (int rc = mark(h, 1, 1, 2.0 * d.M * d.N * d.K * g,
+                      g * (((double)d.M + d.N) * d.K * esz + (double)d.M * d.N * (d.c_elem ? esz : 4.0)))) return rc;
     HIPCHK(launch_gemm(d, h->stream), what);
     return ADPSGD_OK;
 }
@@ -295,7 +298,9 @@ int compute_gradients(adpsgd_handle* h, const float* at, const void* const* batc
         r.c = Cb(l); r.sCi = M * DH;
         r.y = Y(l); r.sYi = M * DH;
         r.wh = W(h->ix_wh[l]); r.sWi = Pp; r.sWd = (int64_t)4 * H * H;
-        if (int rc = mark(h, 2, T, 2.0 * B * H * 4 * H * (T - 1) * L * D)) return rc;
+        // per frame and (learner, direction): W_h once, h in and out, 4 gates in and out (fp32), c in and out
+        if (int rc = mark(h, 2, T, 2.0 * B * H * 4 * H * (T - 1) * L * D,
+                          (double)T * L * D * (4.0 * H * H * esz + (double)B * H * (2 * esz + 8 * 4 + 2 * 4)))) return rc;
         for (int t = 0; t < T; ++t) {
             r.step = t;
             HIPCHK(launch_rec_forward(r, s), "recurrent forward step");
@@ -389,7 +394,9 @@ int compute_gradients(adpsgd_handle* h, const float* at, const void* const* batc
         r.dy = h->dy; r.sDYi = M * DH;
         r.da = h->da; r.sDAi = M * G4;
         r.dc = h->dc; r.sDCi = (int64_t)B * DH;
-        if (int rc = mark(h, 3, T, 2.0 * B * H * 4 * H * (T - 1) * L * D)) return rc;
+        // per frame and (learner, direction): W_h once, da in (4 gates) and out, dY, 4 gates, c, c', dc in and out
+        if (int rc = mark(h, 3, T, 2.0 * B * H * 4 * H * (T - 1) * L * D,
+                          (double)T * L * D * (4.0 * H * H * esz + (double)B * H * (8 * esz + 4 + 16 + 8 + 8)))) return rc;
         for (int t = 0; t < T; ++t) {
             r.step = t;
             HIPCHK(launch_rec_backward(r, s), "recurrent backward step");
@@ -520,7 +527,8 @@ int adpsgd_step(adpsgd_t h, const void* const* batch_ptrs, float lr) {
     {
         int nact = 0;
         for (int i = 0; i < L; ++i) nact += active[i];
-        if (int rc = mark(h, 6, 1, (u.shadow ? 14.0 : 12.0) * (double)h->P * nact)) return rc;
+        const double ub = (u.shadow ? 14.0 : 12.0) * (double)h->P * nact;
+        if (int rc = mark(h, 6, 1, ub, ub)) return rc;
     }
     HIPCHK(launch_update(u, h->stream), "mix + update");
     if (int rc = mark(h, -1)) return rc;
@@ -600,7 +608,7 @@ int adpsgd_set_profiling(adpsgd_t h, int enable) {
     return ADPSGD_OK;
 }
 
-int adpsgd_profile(adpsgd_t h, float* host_ms, int32_t* host_launches, double* host_work) {
+int adpsgd_profile(adpsgd_t h, float* host_ms, int32_t* host_launches, double* host_work, double* host_bytes) {
     if (!h) return fail(ADPSGD_EINVAL, "NULL handle");
     Profiler& p = h->prof;
     HIPCHK(hipStreamSynchronize(h->stream), "stream sync");
@@ -616,6 +624,7 @@ int adpsgd_profile(adpsgd_t h, float* host_ms, int32_t* host_launches, double* h
         if (host_ms) host_ms[i] = ms[i];
         if (host_launches) host_launches[i] = p.launches[i];
         if (host_work) host_work[i] = p.work[i];
+        if (host_bytes) host_bytes[i] = p.bytes[i];
     }
     prof_reset(h);
     return ADPSGD_OK;
