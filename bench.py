@@ -127,6 +127,7 @@ def cpu_baseline(wl, seed=0, budget_s=12.0):
 # 1.0x): profiles/hbm_traffic_cfg4_cfg5.txt.  Keyed by workload; bytes per launch of the named kernel class.
 TRAFFIC = {
     ("cfg4", "batched_gemm"): 5.06e9,     # mean over the 29 time-batched GEMM launches of one iteration
+    ("cfg4", "recurrent"): 0.468e9,       # mean of rec_forward_dma_kernel (0.464) and rec_backward_dma_kernel (0.472)
     ("cfg4", "mix_update"): 32.5e9,       # all_update_kernel with the bf16 copy written along
     ("cfg5", "mix_update"): 93.2e9,       # pair_update_kernel, mean over the profiled iterations
 }
@@ -182,7 +183,7 @@ def main():
         rec_ms = prof["recurrent_fwd"]["ms"] + prof["recurrent_bwd"]["ms"]
         rec_work = prof["recurrent_fwd"]["work"] + prof["recurrent_bwd"]["work"]
         peak = PEAK_TFLOPS[dtype]
-        rec = hbm_roofline(prof, ["recurrent_fwd", "recurrent_bwd"], "rec_forward_*_kernel + rec_backward_*_kernel", wl.name)
+        rec = hbm_roofline(prof, ["recurrent_fwd", "recurrent_bwd"], "rec_forward_*_kernel + rec_backward_*_kernel", wl.name, "recurrent")
         rec["mfma_TFLOPs"] = rec_work / (rec_ms * 1e-3) / 1e12 if rec_ms > 0 else 0.0
         out.update({
             "value": frames / (ms * 1e-3), "ms_per_step": ms, "dtype": dtype,
