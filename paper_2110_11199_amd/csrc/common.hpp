@@ -30,7 +30,12 @@ template <> struct Elem<bf16_t> {
     __device__ static float to(bf16_t v) { return bf16_to_f32(v); }
 };
 
-__device__ inline float sigmoidf_(float a) { return 1.0f / (1.0f + expf(-a)); }
+// Gate non-linearities on the hardware exp2 and reciprocal units (about 1 ulp each; the absolute
+// error of the result stays below 3e-7, far inside the parity tolerance).  They saturate correctly:
+// exp2 overflows to +inf, whose reciprocal is 0.
+__device__ inline float exp_fast_(float a) { return __builtin_amdgcn_exp2f(a * 1.4426950408889634f); }
+__device__ inline float sigmoidf_(float a) { return __builtin_amdgcn_rcpf(1.0f + exp_fast_(-a)); }
+__device__ inline float tanhf_(float a) { return 1.0f - 2.0f * __builtin_amdgcn_rcpf(1.0f + exp_fast_(2.0f * a)); }
 
 inline int64_t round_up(int64_t v, int64_t m) { return (v + m - 1) / m * m; }
 

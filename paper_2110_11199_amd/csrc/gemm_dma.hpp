@@ -85,7 +85,11 @@ struct GemmDma {
     }
 
     // K must be a multiple of KT (checked by the host).  acc must be initialised.
-    __device__ static void run(f32x16_t (&acc)[FM][FN], const ASrc& a, const BSrc& b, int K, char* lds) {
+    // rot (0 <= rot < K/KT) rotates the order in which the K stages are consumed: stage s reads
+    // k-block (s + rot) mod nk.  Workgroups that would otherwise walk K in lockstep (same column
+    // offset of every row at the same time, i.e. the same few memory channels) are given
+    // different rotations by the caller; the sum is the same up to fp32 summation order.
+    __device__ static void run(f32x16_t (&acc)[FM][FN], const ASrc& a, const BSrc& b, int K, char* lds, int rot = 0) {
         constexpr int LPT = LA + LB;
         const int tid = threadIdx.x;
         const int lane = tid & 63, wave = tid >> 6;
@@ -95,8 +99,9 @@ struct GemmDma {
 #pragma unroll
         for (int s = 0; s < NS - 1; ++s) {
             if (s < nk) {
-                issue<BM, LA>(a, s * KT, lds + s * STAGE_BYTES, tid);
-                issue<BN, LB>(b, s * KT, lds + s * STAGE_BYTES + A_BYTES, tid);
+                int kb = s + rot; kb = kb >= nk ? kb - nk : kb;
+                issue<BM, LA>(a, kb * KT, lds + s * STAGE_BYTES, tid);
+                issue<BN, LB>(b, kb * KT, lds + s * STAGE_BYTES + A_BYTES, tid);
             }
         }
         for (int kt = 0; kt < nk; ++kt) {
@@ -109,8 +114,9 @@ struct GemmDma {
             const int nt = kt + NS - 1;
             if (nt < nk) {
                 char* st = lds + (nt % NS) * STAGE_BYTES;
-                issue<BM, LA>(a, nt * KT, st, tid);
-                issue<BN, LB>(b, nt * KT, st + A_BYTES, tid);
+                int kb = nt + rot; kb = kb >= nk ? kb - nk : kb;
+                issue<BM, LA>(a, kb * KT, st, tid);
+                issue<BN, LB>(b, kb * KT, st + A_BYTES, tid);
             }
             const char* cur = lds + (kt % NS) * STAGE_BYTES;
 #pragma unroll

@@ -69,11 +69,11 @@ __device__ inline void forward_epilogue(const RecDesc& p, f32x16_t (&acc)[1][4],
     for (int i = 0; i < 16; ++i) {
         const float ig = sigmoidf_(in.a[0][i] + acc[0][0][i]);
         const float fg = sigmoidf_(in.a[1][i] + acc[0][1][i]);
-        const float gg = tanhf(in.a[2][i] + acc[0][2][i]);
+        const float gg = tanhf_(in.a[2][i] + acc[0][2][i]);
         const float og = sigmoidf_(in.a[3][i] + acc[0][3][i]);
         const float cc = fg * in.c_prev[i] + ig * gg;
         acc[0][0][i] = ig; acc[0][1][i] = fg; acc[0][2][i] = gg; acc[0][3][i] = og;
-        hv[i] = og * tanhf(cc);
+        hv[i] = og * tanhf_(cc);
         if constexpr (sizeof(T) == 2) hb[i] = f32_to_bf16(hv[i]);
         in.c_prev[i] = cc;
     }
@@ -129,7 +129,7 @@ __device__ inline void backward_epilogue(const RecDesc& p, f32x16_t (&acc)[1][FN
         for (int i = 0; i < 16; ++i) {
             const float dh = dyv[i] + acc[0][fn][i];
             const float ig = gi[i], fg = gf[i], g2 = gg[i], og = go[i];
-            const float tc = tanhf(cv[i]);
+            const float tc = tanhf_(cv[i]);
             const float dov = dh * tc;
             const float dcv = dcr[i] + dh * og * (1.f - tc * tc);
             const float di = dcv * g2, dg = dcv * ig, df = dcv * cp[i];
@@ -220,6 +220,12 @@ __global__ __launch_bounds__(256) void rec_backward_kernel(RecDesc p) {
 
 // ---- direct-to-LDS versions (bf16, H a multiple of the stage, 16-byte aligned rows) -----
 
+// All workgroups of a launch start together and stream their W_h rows (a power-of-two pitch apart)
+// at the same pace; walking K from the same offset they would all touch the same column block of
+// every row, i.e. the same subset of memory channels, at the same time.  Each workgroup therefore
+// starts its K loop at a different stage (measured: 8 % faster backward step, 4 % forward).
+__device__ inline int stage_rotation(int nk) { return (int)((blockIdx.y * 5 + blockIdx.x * 3) % nk); }
+
 template <typename T, int WM, int WN, int SB, int NS>
 __global__ __launch_bounds__(256) void rec_forward_dma_kernel(RecDesc p) {
     typedef GemmDma<T, KcSrc<T>, GateSrc<T>, WM, WN, 1, 4, SB, NS> Core;
@@ -240,10 +246,9 @@ __global__ __launch_bounds__(256) void rec_forward_dma_kernel(RecDesc p) {
         GateSrc<T> b;
         b.base = (const T*)p.wh + li * p.sWi + d * p.sWd;
         b.ld = H; b.H = H; b.u0 = u0;
-        Core::run(acc, a, b, H, lds);
+        Core::run(acc, a, b, H, lds, stage_rotation(H / Core::KT));
     }
-        forward_epilogue<T, Core>(p, acc, in, li, d, t, u0, b0);
-
+    forward_epilogue<T, Core>(p, acc, in, li, d, t, u0, b0);
 }
 
 // B operand = transposed copy of W_h: whT [D][H][4H], row u contiguous over the 4H gate rows.
@@ -266,10 +271,9 @@ __global__ __launch_bounds__(64 * WM * WN) void rec_backward_dma_kernel(RecDesc 
         a.ld = G4; a.R = B - b0;
         b.base = (const T*)p.whT + li * p.sWTi + d * p.sWTd + (int64_t)u0 * 4 * H;
         b.ld = (int64_t)4 * H; b.R = H - u0;
-        Core::run(acc, a, b, 4 * H, lds);
+        Core::run(acc, a, b, 4 * H, lds, stage_rotation(4 * H / Core::KT));
     }
-        backward_epilogue<T, Core, FN>(p, acc, li, d, t, tp, u0, b0);
-
+    backward_epilogue<T, Core, FN>(p, acc, li, d, t, tp, u0, b0);
 }
 
 // ---- launchers ----------------------------------------------------------------------
@@ -325,7 +329,7 @@ hipError_t launch_rec_forward(const RecDesc& d, hipStream_t s) {
         const unsigned groups = (unsigned)(d.L * d.D);
         if (d.B > 64) {
             dim3 grid(groups, (d.H + 31) / 32, (d.B + 127) / 128);
-            hipLaunchKernelGGL((rec_forward_dma_kernel<bf16_t, 4, 1, 128, 4>), grid, dim3(256), 0, s, d);
+            hipLaunchKernelGGL((rec_forward_dma_kernel<bf16_t, 4, 1, 64, 4>), grid, dim3(256), 0, s, d);   // 64 KB of LDS: two workgroups per CU
         } else {
             dim3 grid(groups, (d.H + 63) / 64, (d.B + 63) / 64);
             hipLaunchKernelGGL((rec_forward_dma_kernel<bf16_t, 2, 2, 128, 3>), grid, dim3(256), 0, s, d);
