@@ -115,11 +115,13 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_kernel(GemmDesc p) {
     store_tile<T, Core, FM, FN>(acc, p, m0, n0, gi, gd);
 }
 
-// Same tile bookkeeping with the direct-to-LDS main loop (both operands K-contiguous,
-// 16-byte aligned rows, K a multiple of the stage length).
-template <typename T, int WM, int WN, int FM, int FN, int SB, int NS>
+// Same tile bookkeeping with the direct-to-LDS main loop (16-byte aligned operands, K a multiple of
+// the stage length; an operand that is not K-contiguous must have a row count that is a multiple of 8).
+template <typename T, bool AKC, bool BKC, int WM, int WN, int FM, int FN, int SB, int NS>
 __global__ __launch_bounds__(64 * WM * WN) void gemm_dma_kernel(GemmDesc p) {
-    typedef GemmDma<T, KcSrc<T>, KcSrc<T>, WM, WN, FM, FN, SB, NS> Core;
+    typedef typename std::conditional<AKC, KcSrc<T>, McSrc<T>>::type ASrc;
+    typedef typename std::conditional<BKC, KcSrc<T>, McSrc<T>>::type BSrc;
+    typedef GemmDma<T, ASrc, BSrc, WM, WN, FM, FN, SB, NS> Core;
     __shared__ __attribute__((aligned(1024))) char lds[Core::LDS_BYTES];
 
     const int tiles_m = (p.M + Core::BM - 1) / Core::BM;
@@ -127,9 +129,13 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_dma_kernel(GemmDesc p) {
     const int tm = id % tiles_m, tn = id / tiles_m;
     const int gi = blockIdx.y / p.groupsD, gd = blockIdx.y % p.groupsD;
     const int m0 = tm * Core::BM, n0 = tn * Core::BN;
-    KcSrc<T> a, b;
-    a.base = (const T*)p.A + gi * p.sAi + gd * p.sAd + (int64_t)m0 * p.lda; a.ld = p.lda; a.R = p.M - m0;
-    b.base = (const T*)p.B + gi * p.sBi + gd * p.sBd + (int64_t)n0 * p.ldb; b.ld = p.ldb; b.R = p.N - n0;
+    const T* A = (const T*)p.A + gi * p.sAi + gd * p.sAd;
+    const T* B = (const T*)p.B + gi * p.sBi + gd * p.sBd;
+    ASrc a; BSrc b;
+    if constexpr (AKC) { a.base = A + (int64_t)m0 * p.lda; } else { a.base = A + m0; }
+    a.ld = p.lda; a.R = p.M - m0;
+    if constexpr (BKC) { b.base = B + (int64_t)n0 * p.ldb; } else { b.base = B + n0; }
+    b.ld = p.ldb; b.R = p.N - n0;
 
     f32x16_t acc[FM][FN];
     zero_tile<FM, FN>(acc);
@@ -157,13 +163,24 @@ static hipError_t launch_layout(const GemmDesc& d, hipStream_t s) {
     }
 }
 
-template <typename T, int WM, int WN, int FM, int FN, int SB, int NS>
-static hipError_t launch_dma(const GemmDesc& d, hipStream_t s) {
+template <typename T, bool AKC, bool BKC, int WM, int WN, int FM, int FN, int SB, int NS>
+static hipError_t launch_dma_t(const GemmDesc& d, hipStream_t s) {
     constexpr int BM = 32 * FM * WM, BN = 32 * FN * WN;
     const int tiles_m = (d.M + BM - 1) / BM, tiles_n = (d.N + BN - 1) / BN;
     dim3 grid((unsigned)(tiles_m * tiles_n), (unsigned)(d.groupsI * d.groupsD));
-    hipLaunchKernelGGL((gemm_dma_kernel<T, WM, WN, FM, FN, SB, NS>), grid, dim3(64 * WM * WN), 0, s, d);
+    hipLaunchKernelGGL((gemm_dma_kernel<T, AKC, BKC, WM, WN, FM, FN, SB, NS>), grid, dim3(64 * WM * WN), 0, s, d);
     return hipGetLastError();
+}
+
+template <typename T, int WM, int WN, int FM, int FN, int SB, int NS>
+static hipError_t launch_dma(const GemmDesc& d, hipStream_t s) {
+    const int key = (d.a_kc ? 2 : 0) | (d.b_kc ? 1 : 0);
+    switch (key) {
+        case 0: return launch_dma_t<T, false, false, WM, WN, FM, FN, SB, NS>(d, s);
+        case 1: return launch_dma_t<T, false, true, WM, WN, FM, FN, SB, NS>(d, s);
+        case 2: return launch_dma_t<T, true, false, WM, WN, FM, FN, SB, NS>(d, s);
+        default: return launch_dma_t<T, true, true, WM, WN, FM, FN, SB, NS>(d, s);
+    }
 }
 
 static int g_variant = -1;   // tuning knob: forces a tile configuration (-1 = automatic)
@@ -191,7 +208,10 @@ hipError_t launch_gemm(const GemmDesc& d, hipStream_t s) {
         const int64_t big_tiles = (int64_t)((d.M + 255) / 256) * ((d.N + 255) / 256) * d.groupsI * d.groupsD;
         v = big_tiles >= 128 ? 10 : 0;
     }
-    if (v == 10 && d.a_kc && d.b_kc && d.K % 64 == 0) return launch_dma<bf16_t, 2, 4, 4, 2, 128, 2>(d, s);
+    // direct-to-LDS loads need whole stages and, for a rows-contiguous operand, whole 16-byte chunks of rows
+    const bool dma = d.K % 64 == 0 && (d.a_kc || d.M % 8 == 0) && (d.b_kc || d.N % 8 == 0) &&
+                     aligned_to(d.A, d.lda, d.sAi, d.sAd, esz, 16) && aligned_to(d.B, d.ldb, d.sBi, d.sBd, esz, 16);
+    if (v == 10 && dma) return launch_dma<bf16_t, 2, 4, 4, 2, 128, 2>(d, s);
     if (v >= 5) return launch_layout<bf16_t, 2, 4, 4, 2, 16, 128>(d, s);
     return launch_layout<bf16_t, 2, 2, 2, 2, 16, 64>(d, s);
 }

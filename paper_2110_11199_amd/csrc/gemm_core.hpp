@@ -63,6 +63,11 @@ template <typename T> struct McSrc {  // element (r,k) at base[k*ld + r], r < R
     static constexpr bool kc = false;
     const T* base; int64_t ld; int R;
     __device__ bool full(int rows) const { return R >= rows; }
+    // 8 consecutive rows r = 8*chunk.. of k-row k (R a multiple of 8); chunks past the end repeat the last one
+    __device__ const T* chunk_clamped(int k, int chunk) const {
+        const int last = (R >> 3) - 1;
+        return base + (int64_t)k * ld + 8 * (chunk < last ? chunk : last);
+    }
 };
 
 template <typename T, int ROWS, int SB, bool KC> struct LdsTile;

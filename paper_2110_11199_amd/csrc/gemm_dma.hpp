@@ -13,12 +13,23 @@
 // side: the 16-byte slot s of row r holds chunk s ^ swz(r) of that row, with
 // swz(r) = (r / (256/SB)) mod (SB/16), so that any 16 rows read at one chunk index hit 16
 // different 16-byte bank groups.
+//
+// An operand stored rows-contiguous ("mc": element (r,k) at base[k*ld + r], bf16 only) is copied as
+// it lies in memory, k-row by k-row (tile = [KT][ROWS], ROWS*2 bytes per k-row), and transposed
+// on the LDS read: ds_read_b64_tr_b16 hands lane i of a 16-lane group the four 16-bit values that
+// lanes 4c + i/4 (c = 0..3) of the group address at position i%4.  With lane 4c+q addressing
+// (k0+c, r0+4q..r0+4q+3), lane i receives (k0..k0+3, r0+i): four consecutive k of its own row, so
+// two such reads give the same 8-k fragment as one 16-byte read of a K-contiguous tile.  The 16-byte
+// slot s of k-row k holds chunk s ^ 4*(k mod 4) of that row: the 32 lanes served in one LDS
+// cycle (4 k-rows x 64 bytes, twice) then cover all 64 banks once.
 #pragma once
 #include "gemm_core.hpp"
 
 namespace adpsgd {
 
 typedef __attribute__((address_space(3))) void lds_void_t;
+typedef __attribute__((ext_vector_type(4))) short s16x4_t;
+typedef __attribute__((address_space(3))) s16x4_t lds_s16x4_t;
 typedef __attribute__((address_space(1))) const void glb_void_t;
 
 // One wave-wide direct load: lane l's 16 bytes at gptr land in LDS at lds_addr + 16*l.
@@ -44,7 +55,7 @@ struct GemmDma {
     static constexpr int LDS_BYTES = NS * STAGE_BYTES;
     static constexpr int LA = BM * CPR / NT, LB = BN * CPR / NT;   // loads per thread per stage
     static_assert((BM * CPR) % NT == 0 && (BN * CPR) % NT == 0, "tile must divide over the workgroup");
-    static_assert(ASrc::kc && BSrc::kc, "direct loads need K-contiguous operands");
+    static_assert((ASrc::kc && BSrc::kc) || sizeof(T) == 2, "transposing LDS reads exist for 16-bit operands only");
 
     template <int ROWS, int L, class Src>
     __device__ static void issue(const Src& src, int k0, char* lds_tile, int tid) {
@@ -52,18 +63,41 @@ struct GemmDma {
 #pragma unroll
         for (int j = 0; j < L; ++j) {
             const int c = tid + j * NT;
-            const int row = c / CPR;
-            const int slot = c % CPR;
-            const int chunk = slot ^ swz_<SB>(row);
-            const T* p = src.row_clamped(row) + k0 + chunk * (16 / (int)sizeof(T));
+            const T* p;
+            if constexpr (Src::kc) {
+                const int row = c / CPR;
+                const int slot = c % CPR;
+                const int chunk = slot ^ swz_<SB>(row);
+                p = src.row_clamped(row) + k0 + chunk * (16 / (int)sizeof(T));
+            } else {
+                constexpr int CPK = ROWS / 8;                 // 16-byte chunks per k-row
+                static_assert(ROWS % 128 == 0, "the chunk swizzle needs k-rows of a multiple of 16 chunks");
+                const int krow = c / CPK;
+                const int slot = c % CPK;
+                const int chunk = slot ^ (4 * (krow & 3));
+                p = src.chunk_clamped(k0 + krow, chunk);
+            }
             // wave-uniform destination; lane l lands at dst + 16*l
             const uint32_t dst = __builtin_amdgcn_readfirstlane(lds_addr_(lds_tile) + (uint32_t)(wave_base + j * NT) * 16u);
             dma16_(p, dst);
         }
     }
 
-    __device__ static uint4 frag(const char* tile, int row, int ch) {
-        return *(const uint4*)(tile + row * SB + ((ch ^ swz_<SB>(row)) * 16));
+    // 16-byte MFMA fragment of tile row `row0 + lane%32`, k-chunk `ch` (8 consecutive k) of the stage.
+    template <int ROWS, bool KC>
+    __device__ static uint4 frag(const char* tile, int row0, int ch, int lane) {
+        if constexpr (KC) {
+            const int row = row0 + (lane & 31);
+            return *(const uint4*)(tile + row * SB + ((ch ^ swz_<SB>(row)) * 16));
+        } else {
+            const int j = lane & 15, c = j >> 2, q = j & 3;
+            const int r = row0 + (lane & 16) + 4 * q;         // first of the 4 rows this lane addresses
+            const char* p = tile + (ch * 8 + c) * (ROWS * 2) + (((r >> 3) ^ (4 * c)) * 16) + (r & 7) * 2;
+            const s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_t*)p);
+            const s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_t*)(p + 4 * (ROWS * 2)));
+            const uint2 l2 = __builtin_bit_cast(uint2, lo), h2 = __builtin_bit_cast(uint2, hi);
+            return make_uint4(l2.x, l2.y, h2.x, h2.y);
+        }
     }
 
     template <int N> __device__ static void wait_vm() {
@@ -94,7 +128,7 @@ struct GemmDma {
         const int tid = threadIdx.x;
         const int lane = tid & 63, wave = tid >> 6;
         const int wave_m = wave / WN, wave_n = wave % WN;
-        const int r = lane & 31, g = lane >> 5;
+        const int g = lane >> 5;
         const int nk = K / KT;
 #pragma unroll
         for (int s = 0; s < NS - 1; ++s) {
@@ -124,9 +158,9 @@ struct GemmDma {
                 const int ch = 2 * c + g;
                 uint4 af[FM], bfr[FN];
 #pragma unroll
-                for (int fm = 0; fm < FM; ++fm) af[fm] = frag(cur, (wave_m * FM + fm) * 32 + r, ch);
+                for (int fm = 0; fm < FM; ++fm) af[fm] = frag<BM, ASrc::kc>(cur, (wave_m * FM + fm) * 32, ch, lane);
 #pragma unroll
-                for (int fn = 0; fn < FN; ++fn) bfr[fn] = frag(cur + A_BYTES, (wave_n * FN + fn) * 32 + r, ch);
+                for (int fn = 0; fn < FN; ++fn) bfr[fn] = frag<BN, BSrc::kc>(cur + A_BYTES, (wave_n * FN + fn) * 32, ch, lane);
 #pragma unroll
                 for (int fm = 0; fm < FM; ++fm)
 #pragma unroll
