@@ -108,7 +108,6 @@ struct adpsgd_handle {
     float* params[2];
     float* grads;
     bf16_t* shadow;
-    bf16_t* shadowT;   // [layers][L][D][H][4H]: transposed bf16 W_h for the recurrent backward kernels
     void* x0; int32_t* labels;
     void* ybuf;        // [layers][L][M][D*H]
     float* gates;      // [layers][L][M][D*4H]
@@ -193,7 +192,6 @@ size_t plan(adpsgd_handle* h, void* base) {
         const size_t M = (size_t)h->M, DH = (size_t)h->D * h->H, G4 = DH * 4, e = (size_t)h->esz;
         h->grads = (float*)w.take(L * h->Ppad * 4);
         h->shadow = h->prec ? (bf16_t*)w.take(L * h->Ppad * 2) : nullptr;
-        h->shadowT = h->prec ? (bf16_t*)w.take((size_t)h->layers * L * h->D * 4 * h->H * h->H * 2) : nullptr;
         h->x0 = w.take(L * M * h->ldx * e);
         h->labels = (int32_t*)w.take(L * M * 4);
         h->ybuf = w.take((size_t)h->layers * L * M * DH * e);
@@ -252,15 +250,11 @@ int compute_gradients(adpsgd_handle* h, const float* at, const void* const* batc
     hipStream_t s = h->stream;
     // weights as GEMM operands: the fp32 models themselves, or their bf16 copy
     const char* wbase = (const char*)at;
-    if (int rc = mark(h, 0, prec ? 2 + h->layers : 1)) return rc;
-    const int64_t WT = (int64_t)4 * H * H;            // elements of one direction's W_h
+    if (int rc = mark(h, 0, prec ? 2 : 1)) return rc;
     if (prec) {
         // the update of the previous iteration has normally written this copy already
         if (!h->shadow_valid) HIPCHK(launch_cast_bf16(at, h->shadow, (int64_t)L * Pp, s), "cast weights to bf16");
         wbase = (const char*)h->shadow;
-        for (int l = 0; l < h->layers; ++l)
-            HIPCHK(launch_transpose_cast_bf16(at + h->tensors[h->ix_wh[l]].off, Pp, WT, h->shadowT + (size_t)l * L * D * WT,
-                                              D * WT, WT, 4 * H, H, L, D, s), "transpose W_h to bf16");
     }
     auto W = [&](int ix) { return (const void*)(wbase + h->tensors[ix].off * esz); };
     auto Bias = [&](int ix) { return at + h->tensors[ix].off; };
@@ -390,7 +384,6 @@ int compute_gradients(adpsgd_handle* h, const float* at, const void* const* batc
         r.c = Cb(l); r.sCi = M * DH;
         r.y = Y(l); r.sYi = M * DH;
         r.wh = W(h->ix_wh[l]); r.sWi = Pp; r.sWd = (int64_t)4 * H * H;
-        r.whT = prec ? (const void*)(h->shadowT + (size_t)l * L * D * WT) : nullptr; r.sWTi = D * WT; r.sWTd = WT;
         r.dy = h->dy; r.sDYi = M * DH;
         r.da = h->da; r.sDAi = M * G4;
         r.dc = h->dc; r.sDCi = (int64_t)B * DH;

@@ -58,30 +58,6 @@ hipError_t launch_cast_bf16(const float* src, bf16_t* dst, int64_t n, hipStream_
     return hipGetLastError();
 }
 
-// 64x64 tiles through LDS: coalesced fp32 reads along the source rows, coalesced bf16 writes
-// along the destination rows.
-__global__ __launch_bounds__(256) void transpose_cast_kernel(const float* src, int64_t sSi, int64_t sSd, bf16_t* dst,
-                                                             int64_t sDi, int64_t sDd, int rows, int cols, int D) {
-    __shared__ float tile[64][65];
-    const int li = blockIdx.z / D, d = blockIdx.z % D;
-    const float* s = src + li * sSi + d * sSd;
-    bf16_t* o = dst + li * sDi + d * sDd;
-    const int r0 = blockIdx.y * 64, c0 = blockIdx.x * 64;
-    const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
-    for (int r = ty; r < 64; r += 4)
-        tile[r][tx] = (r0 + r < rows && c0 + tx < cols) ? s[(int64_t)(r0 + r) * cols + c0 + tx] : 0.f;
-    __syncthreads();
-    for (int c = ty; c < 64; c += 4)
-        if (c0 + c < cols && r0 + tx < rows) o[(int64_t)(c0 + c) * rows + r0 + tx] = f32_to_bf16(tile[tx][c]);
-}
-
-hipError_t launch_transpose_cast_bf16(const float* src, int64_t sSi, int64_t sSd, bf16_t* dst, int64_t sDi, int64_t sDd,
-                                      int rows, int cols, int L, int D, hipStream_t s) {
-    dim3 grid((unsigned)((cols + 63) / 64), (unsigned)((rows + 63) / 64), (unsigned)(L * D));
-    hipLaunchKernelGGL(transpose_cast_kernel, grid, dim3(256), 0, s, src, sSi, sSd, dst, sDi, sDd, rows, cols, D);
-    return hipGetLastError();
-}
-
 // ---- softmax cross-entropy ---------------------------------------------------
 // One workgroup per frame (row of logits).  loss_row = -(z_y - max - log sum exp(z - max));
 // dlogits = (softmax - onehot) / rows   (mean over the B*T frames of the minibatch).

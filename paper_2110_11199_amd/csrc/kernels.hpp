@@ -53,10 +53,6 @@ struct StageDesc {             // copy / cast the minibatches into the workspace
 };
 hipError_t launch_stage(const StageDesc& d, hipStream_t s);
 hipError_t launch_cast_bf16(const float* src, bf16_t* dst, int64_t n, hipStream_t s);
-// dst[z][c][r] = bf16(src[z][r][c]) for z = i*D + d: src at src + i*sSi + d*sSd ([rows][cols] fp32),
-// dst at dst + i*sDi + d*sDd ([cols][rows] bf16).
-hipError_t launch_transpose_cast_bf16(const float* src, int64_t sSi, int64_t sSd, bf16_t* dst, int64_t sDi, int64_t sDd,
-                                      int rows, int cols, int L, int D, hipStream_t s);
 
 struct RecDesc {               // one time step of one layer, all learners and directions
     int precision;
@@ -67,7 +63,6 @@ struct RecDesc {               // one time step of one layer, all learners and d
     float* c; int64_t sCi;               // [L][D][T*B][H] fp32
     void* y; int64_t sYi;                // [L][T*B][D*H] operand type (layer output)
     const void* wh; int64_t sWi, sWd;    // W_h [D][4H][H] operand type, learner stride
-    const void* whT; int64_t sWTi, sWTd; // optional transposed copy [D][H][4H] (bf16 backward), or NULL
     // backward only
     const float* dy; int64_t sDYi;       // [L][T*B][D*H] fp32, gradient w.r.t. the layer output
     void* da; int64_t sDAi;              // [L][T*B][D*4H] operand type, gate pre-activation grads

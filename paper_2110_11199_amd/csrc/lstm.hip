@@ -13,8 +13,8 @@
 // Each launch re-streams every learner's W_h from HBM (weights are not shared
 // between learners), so these kernels are bound by HBM bandwidth and latency, not
 // by MFMA: the bf16 versions feed LDS with direct global->LDS loads several stages
-// ahead; the backward one reads a transposed bf16 copy of W_h so that both of its
-// operands are K-contiguous.
+// ahead; the backward one reads W_h rows-contiguous (dh = da W_h contracts over the
+// rows of W_h) and transposes on the LDS read.
 #include "gemm_core.hpp"
 #include "gemm_dma.hpp"
 #include "kernels.hpp"
@@ -251,10 +251,11 @@ __global__ __launch_bounds__(256) void rec_forward_dma_kernel(RecDesc p) {
     forward_epilogue<T, Core>(p, acc, in, li, d, t, u0, b0);
 }
 
-// B operand = transposed copy of W_h: whT [D][H][4H], row u contiguous over the 4H gate rows.
+// B operand = W_h itself read rows-contiguous: element (unit u, k = gate row j) at W_h[j*H + u];
+// the transposition happens on the LDS read.
 template <typename T, int WM, int WN, int FN, int SB, int NS>
 __global__ __launch_bounds__(64 * WM * WN) void rec_backward_dma_kernel(RecDesc p) {
-    typedef GemmDma<T, KcSrc<T>, KcSrc<T>, WM, WN, 1, FN, SB, NS> Core;
+    typedef GemmDma<T, KcSrc<T>, McSrc<T>, WM, WN, 1, FN, SB, NS> Core;
     __shared__ __attribute__((aligned(1024))) char lds[Core::LDS_BYTES];
     const int D = p.D, H = p.H, B = p.B;
     const int li = blockIdx.x / D, d = blockIdx.x % D;      // groups on x: the tiles of one (learner, direction) share an XCD and its L2
@@ -266,11 +267,12 @@ __global__ __launch_bounds__(64 * WM * WN) void rec_backward_dma_kernel(RecDesc 
     f32x16_t acc[1][FN];
     zero_acc<FN>(acc);
     if (p.step > 0) {
-        KcSrc<T> a, b;
+        KcSrc<T> a;
         a.base = (const T*)p.da + li * p.sDAi + ((int64_t)tn * B + b0) * G4 + (int64_t)d * 4 * H;
         a.ld = G4; a.R = B - b0;
-        b.base = (const T*)p.whT + li * p.sWTi + d * p.sWTd + (int64_t)u0 * 4 * H;
-        b.ld = (int64_t)4 * H; b.R = H - u0;
+        McSrc<T> b;
+        b.base = (const T*)p.wh + li * p.sWi + d * p.sWd + u0;
+        b.ld = H; b.R = H - u0;
         Core::run(acc, a, b, 4 * H, lds, stage_rotation(4 * H / Core::KT));
     }
     backward_epilogue<T, Core, FN>(p, acc, li, d, t, tp, u0, b0);
@@ -319,7 +321,9 @@ static int g_rec_dma = 1;    // tuning knob: 0 disables the direct-to-LDS kernel
 void set_rec_dma(int on) { g_rec_dma = on; }
 
 static bool dma_ok(const RecDesc& d) {
-    return g_rec_dma && d.precision == 1 && d.H % 64 == 0 && d.B > 32;
+    // whole stages, and 16-byte aligned rows of every operand the direct loads touch
+    return g_rec_dma && d.precision == 1 && d.H % 64 == 0 && d.B > 32 && (uintptr_t)d.wh % 16 == 0 && d.sWi % 8 == 0 &&
+           d.sWd % 8 == 0 && (uintptr_t)d.y % 16 == 0 && d.sYi % 8 == 0 && (uintptr_t)d.da % 16 == 0 && d.sDAi % 8 == 0;
 }
 
 hipError_t launch_rec_forward(const RecDesc& d, hipStream_t s) {
@@ -342,7 +346,7 @@ hipError_t launch_rec_forward(const RecDesc& d, hipStream_t s) {
 hipError_t launch_rec_backward(const RecDesc& d, hipStream_t s) {
     if (!rec_ok(d)) return hipErrorInvalidValue;
     if (d.precision == 0) return bwd_t<float, 16>(d, s);
-    if (dma_ok(d) && d.whT != nullptr) {
+    if (dma_ok(d)) {
         const unsigned groups = (unsigned)(d.L * d.D);
         if (d.B > 64) {
             dim3 grid(groups, (d.H + 127) / 128, (d.B + 127) / 128);
