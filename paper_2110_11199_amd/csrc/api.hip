@@ -107,6 +107,7 @@ struct adpsgd_handle {
     // workspace regions
     float* params[2];
     float* grads;
+    bf16_t* wx0p;      // [L][D*4H][ldx] bf16: W_x of layer 0 with zero-padded rows, or NULL
     bf16_t* shadow;
     void* x0; int32_t* labels;
     void* ybuf;        // [layers][L][M][D*H]
@@ -163,7 +164,8 @@ size_t plan(adpsgd_handle* h, void* base) {
     } else {
         h->D = s.bidirectional ? 2 : 1; h->H = s.hidden; h->T = s.frames; h->B = s.batch; h->I = s.input_dim;
         h->C = s.classes; h->Bn = s.bottleneck; h->layers = s.layers; h->M = (int64_t)h->T * h->B;
-        h->ldx = (int)round_up(h->I, 8);
+        // staged input rows: whole 16-byte chunks; whole 64-element K stages for the direct-to-LDS GEMM (bf16)
+        h->ldx = (int)round_up(h->I, c.precision ? 64 : 8);
         int64_t off = 0;
         const int64_t G4 = (int64_t)h->D * 4 * h->H;
         for (int l = 0; l < h->layers; ++l) {
@@ -193,6 +195,8 @@ size_t plan(adpsgd_handle* h, void* base) {
         h->grads = (float*)w.take(L * h->Ppad * 4);
         h->shadow = h->prec ? (bf16_t*)w.take(L * h->Ppad * 2) : nullptr;
         h->x0 = w.take(L * M * h->ldx * e);
+        // bf16 W_x of layer 0 with its rows zero-padded to ldx (when the input width is not a multiple of 64)
+        h->wx0p = (h->prec && h->ldx != h->I) ? (bf16_t*)w.take(L * G4 * h->ldx * 2) : nullptr;
         h->labels = (int32_t*)w.take(L * M * 4);
         h->ybuf = w.take((size_t)h->layers * L * M * DH * e);
         h->gates = (float*)w.take((size_t)h->layers * L * M * G4 * 4);
@@ -234,10 +238,13 @@ void prof_reset(adpsgd_handle* h) {
     for (int i = 0; i < ADPSGD_PHASES; ++i) { p.launches[i] = 0; p.work[i] = 0.0; p.bytes[i] = 0.0; }
 }
 
-int gemm(adpsgd_handle* h, const GemmDesc& d, const char* what) {
+// k_alg: the contraction length the flop and byte counts are taken for (0: d.K; smaller than d.K when
+// the operands carry zero padding along K)
+int gemm(adpsgd_handle* h, const GemmDesc& d, const char* what, int k_alg = 0) {
     const double esz = d.precision ? 2.0 : 4.0, g = (double)d.groupsI * d.groupsD;
-    if (int rc = mark(h, 1, 1, 2.0 * d.M * d.N * d.K * g,
-                      g * (((double)d.M + d.N) * d.K * esz + (double)d.M * d.N * (d.c_elem ? esz : 4.0)))) return rc;
+    const double K = k_alg > 0 ? k_alg : d.K;
+    if (int rc = mark(h, 1, 1, 2.0 * d.M * d.N * K * g,
+                      g * (((double)d.M + d.N) * K * esz + (double)d.M * d.N * (d.c_elem ? esz : 4.0)))) return rc;
     HIPCHK(launch_gemm(d, h->stream), what);
     return ADPSGD_OK;
 }
@@ -250,11 +257,14 @@ int compute_gradients(adpsgd_handle* h, const float* at, const void* const* batc
     hipStream_t s = h->stream;
     // weights as GEMM operands: the fp32 models themselves, or their bf16 copy
     const char* wbase = (const char*)at;
-    if (int rc = mark(h, 0, prec ? 2 : 1)) return rc;
+    if (int rc = mark(h, 0, prec ? (h->wx0p ? 3 : 2) : 1)) return rc;
     if (prec) {
         // the update of the previous iteration has normally written this copy already
         if (!h->shadow_valid) HIPCHK(launch_cast_bf16(at, h->shadow, (int64_t)L * Pp, s), "cast weights to bf16");
         wbase = (const char*)h->shadow;
+        if (h->wx0p)
+            HIPCHK(launch_pad_rows_bf16(at + h->tensors[h->ix_wx[0]].off, Pp, h->wx0p, (int64_t)G4 * h->ldx, G4, h->I, h->ldx,
+                                        L, s), "pad W_x of layer 0");
     }
     auto W = [&](int ix) { return (const void*)(wbase + h->tensors[ix].off * esz); };
     auto Bias = [&](int ix) { return at + h->tensors[ix].off; };
@@ -282,10 +292,13 @@ int compute_gradients(adpsgd_handle* h, const float* at, const void* const* batc
         g.M = (int)M; g.N = (int)G4; g.K = (int)Il;
         g.A = l == 0 ? h->x0 : Y(l - 1); g.lda = l == 0 ? h->ldx : DH; g.sAi = M * g.lda;
         g.B = W(h->ix_wx[l]); g.ldb = Il; g.sBi = Pp;
+        if (l == 0 && h->wx0p) {     // zero-padded K: the staged input and this copy of W_x share the row length ldx
+            g.K = h->ldx; g.B = h->wx0p; g.ldb = h->ldx; g.sBi = G4 * h->ldx;
+        }
         g.C = Gates(l); g.ldc = G4; g.sCi = M * G4;
         g.bias = Bias(h->ix_b[l]); g.sBiasI = Pp;
         g.groupsI = L; g.groupsD = 1;
-        if (int rc = gemm(h, g, "input projection GEMM")) return rc;
+        if (int rc = gemm(h, g, "input projection GEMM", (int)Il)) return rc;
         RecDesc r{};
         r.precision = prec; r.L = L; r.D = D; r.B = B; r.H = H; r.T = T;
         r.gates = Gates(l); r.sGi = M * G4;

@@ -58,6 +58,24 @@ hipError_t launch_cast_bf16(const float* src, bf16_t* dst, int64_t n, hipStream_
     return hipGetLastError();
 }
 
+// dst[z][r][0..ld) = bf16(src[z][r][0..cols)) followed by zeros: rows of a weight matrix padded to
+// a row length the direct-to-LDS GEMM can load (16-byte aligned rows, whole K stages).
+__global__ __launch_bounds__(256) void pad_rows_bf16_kernel(const float* src, int64_t sS, bf16_t* dst, int64_t sD,
+                                                            int64_t rows, int cols, int ld) {
+    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= rows * ld) return;
+    const int64_t r = idx / ld;
+    const int c = (int)(idx % ld);
+    dst[blockIdx.y * sD + idx] = c < cols ? f32_to_bf16(src[blockIdx.y * sS + r * cols + c]) : (bf16_t)0;
+}
+
+hipError_t launch_pad_rows_bf16(const float* src, int64_t sS, bf16_t* dst, int64_t sD, int64_t rows, int cols, int ld,
+                                int L, hipStream_t s) {
+    dim3 grid((unsigned)((rows * ld + 255) / 256), (unsigned)L);
+    hipLaunchKernelGGL(pad_rows_bf16_kernel, grid, dim3(256), 0, s, src, sS, dst, sD, rows, cols, ld);
+    return hipGetLastError();
+}
+
 // ---- softmax cross-entropy ---------------------------------------------------
 // One workgroup per frame (row of logits).  loss_row = -(z_y - max - log sum exp(z - max));
 // dlogits = (softmax - onehot) / rows   (mean over the B*T frames of the minibatch).

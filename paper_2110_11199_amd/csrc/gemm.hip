@@ -116,7 +116,7 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_kernel(GemmDesc p) {
 }
 
 // Same tile bookkeeping with the direct-to-LDS main loop (16-byte aligned operands, K a multiple of
-// the stage length; an operand that is not K-contiguous must have a row count that is a multiple of 8).
+// the stage length).
 template <typename T, bool AKC, bool BKC, int WM, int WN, int FM, int FN, int SB, int NS>
 __global__ __launch_bounds__(64 * WM * WN) void gemm_dma_kernel(GemmDesc p) {
     typedef typename std::conditional<AKC, KcSrc<T>, McSrc<T>>::type ASrc;
@@ -132,10 +132,12 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_dma_kernel(GemmDesc p) {
     const T* A = (const T*)p.A + gi * p.sAi + gd * p.sAd;
     const T* B = (const T*)p.B + gi * p.sBi + gd * p.sBd;
     ASrc a; BSrc b;
-    if constexpr (AKC) { a.base = A + (int64_t)m0 * p.lda; } else { a.base = A + m0; }
-    a.ld = p.lda; a.R = p.M - m0;
-    if constexpr (BKC) { b.base = B + (int64_t)n0 * p.ldb; } else { b.base = B + n0; }
-    b.ld = p.ldb; b.R = p.N - n0;
+    // A rows-contiguous operand is loaded in chunks of 8 rows: its row count is rounded up (its k-rows
+    // are ld >= that many elements long, so the extra rows are readable; their products are never stored).
+    if constexpr (AKC) { a.base = A + (int64_t)m0 * p.lda; a.R = p.M - m0; } else { a.base = A + m0; a.R = (p.M - m0 + 7) & ~7; }
+    a.ld = p.lda;
+    if constexpr (BKC) { b.base = B + (int64_t)n0 * p.ldb; b.R = p.N - n0; } else { b.base = B + n0; b.R = (p.N - n0 + 7) & ~7; }
+    b.ld = p.ldb;
 
     f32x16_t acc[FM][FN];
     zero_tile<FM, FN>(acc);
@@ -209,8 +211,10 @@ hipError_t launch_gemm(const GemmDesc& d, hipStream_t s) {
         v = big_tiles >= 128 ? 10 : 0;
     }
     // direct-to-LDS loads need whole stages and, for a rows-contiguous operand, whole 16-byte chunks of rows
-    const bool dma = d.K % 64 == 0 && (d.a_kc || d.M % 8 == 0) && (d.b_kc || d.N % 8 == 0) &&
-                     aligned_to(d.A, d.lda, d.sAi, d.sAd, esz, 16) && aligned_to(d.B, d.ldb, d.sBi, d.sBd, esz, 16);
+    // (16-byte aligned k-rows of a rows-contiguous operand must be at least round_up(rows, 8) long)
+    const bool dma = d.K % 64 == 0 && aligned_to(d.A, d.lda, d.sAi, d.sAd, esz, 16) &&
+                     aligned_to(d.B, d.ldb, d.sBi, d.sBd, esz, 16) &&
+                     (d.a_kc || d.lda >= ((d.M + 7) & ~7)) && (d.b_kc || d.ldb >= ((d.N + 7) & ~7));
     if (v == 10 && dma) return launch_dma<bf16_t, 2, 4, 4, 2, 128, 2>(d, s);
     if (v >= 5) return launch_layout<bf16_t, 2, 4, 4, 2, 16, 128>(d, s);
     return launch_layout<bf16_t, 2, 2, 2, 2, 16, 64>(d, s);

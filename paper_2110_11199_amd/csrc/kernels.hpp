@@ -53,6 +53,9 @@ struct StageDesc {             // copy / cast the minibatches into the workspace
 };
 hipError_t launch_stage(const StageDesc& d, hipStream_t s);
 hipError_t launch_cast_bf16(const float* src, bf16_t* dst, int64_t n, hipStream_t s);
+// dst[z][r][0..ld) = bf16(src[z][r][0..cols)), zero padded; z < L, strides sS / sD in elements
+hipError_t launch_pad_rows_bf16(const float* src, int64_t sS, bf16_t* dst, int64_t sD, int64_t rows, int cols, int ld,
+                                int L, hipStream_t s);
 
 struct RecDesc {               // one time step of one layer, all learners and directions
     int precision;

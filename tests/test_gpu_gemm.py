@@ -67,10 +67,12 @@ def test_gemm_bf16(a_k, b_k, M, N, K):
 
 
 @pytest.mark.parametrize("a_k,b_k", LAYOUTS)
-@pytest.mark.parametrize("M,N,K,pad", [(520, 520, 192, 0), (520, 520, 192, 8), (516, 524, 128, 0), (264, 776, 100, 0)])
+@pytest.mark.parametrize("M,N,K,pad", [(520, 520, 192, 0), (520, 520, 192, 8), (516, 524, 128, 0), (516, 524, 128, 4),
+                                         (264, 776, 100, 0)])
 def test_gemm_bf16_large_tiles(a_k, b_k, M, N, K, pad):
     # enough 256x256 tiles (>= 128 over the groups) for the large-tile kernels: direct-to-LDS loads
-    # when K is a multiple of 64 and rows-contiguous operands have a multiple of 8 rows, else register staging
+    # when K is a multiple of 64 and all rows are 16-byte aligned (row counts need not be multiples of 8: pad=4
+    # makes the k-rows of a 516-row operand 520 long), else register staging
     print("gemm bf16 large", a_k, b_k, M, N, K, pad, flush=True)
     groups = 16 if N < 600 else 22
     assert _run(1, a_k, b_k, 0, M, N, K, groups, True, pad=pad) < 2e-6
