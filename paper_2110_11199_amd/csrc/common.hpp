@@ -9,12 +9,14 @@ typedef uint16_t bf16_t;   // raw bfloat16 bits
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
 typedef __attribute__((ext_vector_type(16))) float f32x16_t;
 
-// fp32 -> bf16, round to nearest even (the bfloat16 format rule); NaN stays NaN.
-__host__ __device__ inline bf16_t f32_to_bf16(float f) {
-    uint32_t u = __builtin_bit_cast(uint32_t, f);
-    if ((u & 0x7fffffffu) > 0x7f800000u) return (bf16_t)((u >> 16) | 0x40);
-    u += 0x7fffu + ((u >> 16) & 1u);
-    return (bf16_t)(u >> 16);
+// fp32 -> bf16, round to nearest even, on the gfx950 conversion unit (v_cvt_pk_bf16_f32).
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_t;
+typedef __attribute__((ext_vector_type(2))) float f32x2_t;
+__device__ inline bf16_t f32_to_bf16(float f) { return __builtin_bit_cast(bf16_t, (__bf16)f); }
+// two values into one register: lo in bits 0..15, hi in bits 16..31
+__device__ inline uint32_t pack_bf16(float lo, float hi) {
+    const f32x2_t v = {lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_t));
 }
 __host__ __device__ inline float bf16_to_f32(bf16_t h) {
     return __builtin_bit_cast(float, (uint32_t)h << 16);

@@ -43,8 +43,8 @@ __global__ __launch_bounds__(256) void cast_bf16_kernel(const float4* src, uint2
     for (; i < n4; i += stride) {
         const float4 v = src[i];
         uint2 o;
-        o.x = (uint32_t)f32_to_bf16(v.x) | ((uint32_t)f32_to_bf16(v.y) << 16);
-        o.y = (uint32_t)f32_to_bf16(v.z) | ((uint32_t)f32_to_bf16(v.w) << 16);
+        o.x = pack_bf16(v.x, v.y);
+        o.y = pack_bf16(v.z, v.w);
         dst[i] = o;
     }
 }
@@ -166,7 +166,7 @@ __global__ __launch_bounds__(256) void softmax_ce_row_kernel(SoftmaxDesc p) {
         const int c4 = threadIdx.x + 256 * j;
         if (c4 < C4) {
             if ((y >> 2) == c4) zy = (y & 3) == 0 ? v[j].x : (y & 3) == 1 ? v[j].y : (y & 3) == 2 ? v[j].z : v[j].w;
-            v[j].x = expf(v[j].x - m); v[j].y = expf(v[j].y - m); v[j].z = expf(v[j].z - m); v[j].w = expf(v[j].w - m);
+            v[j].x = exp_fast_(v[j].x - m); v[j].y = exp_fast_(v[j].y - m); v[j].z = exp_fast_(v[j].z - m); v[j].w = exp_fast_(v[j].w - m);
             s += (v[j].x + v[j].y) + (v[j].z + v[j].w);
         }
     }
@@ -187,8 +187,8 @@ __global__ __launch_bounds__(256) void softmax_ce_row_kernel(SoftmaxDesc p) {
             pr.x *= scale; pr.y *= scale; pr.z *= scale; pr.w *= scale;
             if constexpr (sizeof(T) == 2) {
                 uint2 o;
-                o.x = (uint32_t)f32_to_bf16(pr.x) | ((uint32_t)f32_to_bf16(pr.y) << 16);
-                o.y = (uint32_t)f32_to_bf16(pr.z) | ((uint32_t)f32_to_bf16(pr.w) << 16);
+                o.x = pack_bf16(pr.x, pr.y);
+                o.y = pack_bf16(pr.z, pr.w);
                 ((uint2*)dz)[c4] = o;
             } else {
                 ((float4*)dz)[c4] = pr;

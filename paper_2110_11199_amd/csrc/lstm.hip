@@ -136,8 +136,8 @@ __device__ inline void backward_epilogue(const RecDesc& p, f32x16_t (&acc)[1][FN
             dcr[i] = dcv * fg;
             float a0 = di * ig * (1.f - ig), a1 = df * fg * (1.f - fg), a2 = dg * (1.f - g2 * g2), a3 = dov * og * (1.f - og);
             if constexpr (sizeof(T) == 2) {
-                pk0[i] = (uint32_t)f32_to_bf16(a0) | ((uint32_t)f32_to_bf16(a1) << 16);
-                pk1[i] = (uint32_t)f32_to_bf16(a2) | ((uint32_t)f32_to_bf16(a3) << 16);
+                pk0[i] = pack_bf16(a0, a1);
+                pk1[i] = pack_bf16(a2, a3);
             } else {
                 gi[i] = a0; gf[i] = a1; gg[i] = a2; go[i] = a3;
             }

@@ -57,8 +57,8 @@ __device__ inline float4 ldnt_(const float* p, int64_t e4) {
 }
 __device__ inline void emit4_(bf16_t* sh, int64_t e4, const float4& v) {
     uint2 o;
-    o.x = (uint32_t)f32_to_bf16(v.x) | ((uint32_t)f32_to_bf16(v.y) << 16);
-    o.y = (uint32_t)f32_to_bf16(v.z) | ((uint32_t)f32_to_bf16(v.w) << 16);
+    o.x = pack_bf16(v.x, v.y);
+    o.y = pack_bf16(v.z, v.w);
     ((uint2*)sh)[e4] = o;
 }
 __device__ inline void stnt_(float* p, int64_t e4, const float4& v) {
