@@ -28,6 +28,27 @@ __device__ inline int xcd_contiguous_id(int bid, int nb) {
     return start + local;
 }
 
+// Workgroup -> (group, tile row, tile column).  The grid is one-dimensional over all tiles of all
+// groups.  Each XCD (own L2, 32 CUs) owns a contiguous range of the ordered tile list, so it works on
+// whole groups when there are enough of them instead of on a slice of every group; inside a group
+// the tiles are ordered in bands of gm <= 8 tile rows walked column by column, so that the 32 tiles an
+// XCD runs at one time form a gm x 32/gm patch that shares gm + 32/gm operand panels (an m-fastest
+// walk of the whole group needs tiles_m + 32/tiles_m and re-reads every A panel in every round).
+__device__ inline void map_tile(int bid, int total, int tiles_m, int tiles_n, int& grp, int& tm, int& tn) {
+    const int id = xcd_contiguous_id(bid, total);
+    const int per = tiles_m * tiles_n;
+    grp = id / per;
+    const int t = id - grp * per;
+    const int nband = (tiles_m + 7) >> 3;
+    const int gm = (tiles_m + nband - 1) / nband;
+    const int band = t / (gm * tiles_n);
+    const int first = band * gm;
+    const int rows = tiles_m - first < gm ? tiles_m - first : gm;
+    const int r = t - band * gm * tiles_n;
+    tn = r / rows;
+    tm = first + r - tn * rows;
+}
+
 // Epilogue shared by the GEMM kernels: C tile = acc (+ bias), fp32 or operand type.
 // Every store reads its data from a register of its own (the bias is added in place, the
 // bf16 values are converted into a separate array first): with one temporary register
@@ -95,10 +116,10 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_kernel(GemmDesc p) {
     typedef GemmCore<T, ASrc, BSrc, WM, WN, FM, FN, VB, SB> Core;
     __shared__ __attribute__((aligned(16))) char lds[Core::LDS_BYTES];
 
-    const int tiles_m = (p.M + Core::BM - 1) / Core::BM;
-    const int id = xcd_contiguous_id(blockIdx.x, gridDim.x);
-    const int tm = id % tiles_m, tn = id / tiles_m;
-    const int gi = blockIdx.y / p.groupsD, gd = blockIdx.y % p.groupsD;
+    const int tiles_m = (p.M + Core::BM - 1) / Core::BM, tiles_n = (p.N + Core::BN - 1) / Core::BN;
+    int grp, tm, tn;
+    map_tile(blockIdx.x, gridDim.x, tiles_m, tiles_n, grp, tm, tn);
+    const int gi = grp / p.groupsD, gd = grp % p.groupsD;
     const int m0 = tm * Core::BM, n0 = tn * Core::BN;
     const T* A = (const T*)p.A + gi * p.sAi + gd * p.sAd;
     const T* B = (const T*)p.B + gi * p.sBi + gd * p.sBd;
@@ -124,10 +145,10 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_dma_kernel(GemmDesc p) {
     typedef GemmDma<T, ASrc, BSrc, WM, WN, FM, FN, SB, NS> Core;
     __shared__ __attribute__((aligned(1024))) char lds[Core::LDS_BYTES];
 
-    const int tiles_m = (p.M + Core::BM - 1) / Core::BM;
-    const int id = xcd_contiguous_id(blockIdx.x, gridDim.x);
-    const int tm = id % tiles_m, tn = id / tiles_m;
-    const int gi = blockIdx.y / p.groupsD, gd = blockIdx.y % p.groupsD;
+    const int tiles_m = (p.M + Core::BM - 1) / Core::BM, tiles_n = (p.N + Core::BN - 1) / Core::BN;
+    int grp, tm, tn;
+    map_tile(blockIdx.x, gridDim.x, tiles_m, tiles_n, grp, tm, tn);
+    const int gi = grp / p.groupsD, gd = grp % p.groupsD;
     const int m0 = tm * Core::BM, n0 = tn * Core::BN;
     const T* A = (const T*)p.A + gi * p.sAi + gd * p.sAd;
     const T* B = (const T*)p.B + gi * p.sBi + gd * p.sBd;
@@ -149,7 +170,7 @@ template <typename T, bool AKC, bool BKC, int WM, int WN, int FM, int FN, int VB
 static hipError_t launch_t(const GemmDesc& d, hipStream_t s) {
     constexpr int BM = 32 * FM * WM, BN = 32 * FN * WN;
     const int tiles_m = (d.M + BM - 1) / BM, tiles_n = (d.N + BN - 1) / BN;
-    dim3 grid((unsigned)(tiles_m * tiles_n), (unsigned)(d.groupsI * d.groupsD));
+    dim3 grid((unsigned)(tiles_m * tiles_n * d.groupsI * d.groupsD));
     hipLaunchKernelGGL((gemm_kernel<T, AKC, BKC, WM, WN, FM, FN, VB, SB>), grid, dim3(64 * WM * WN), 0, s, d);
     return hipGetLastError();
 }
@@ -169,7 +190,7 @@ template <typename T, bool AKC, bool BKC, int WM, int WN, int FM, int FN, int SB
 static hipError_t launch_dma_t(const GemmDesc& d, hipStream_t s) {
     constexpr int BM = 32 * FM * WM, BN = 32 * FN * WN;
     const int tiles_m = (d.M + BM - 1) / BM, tiles_n = (d.N + BN - 1) / BN;
-    dim3 grid((unsigned)(tiles_m * tiles_n), (unsigned)(d.groupsI * d.groupsD));
+    dim3 grid((unsigned)(tiles_m * tiles_n * d.groupsI * d.groupsD));
     hipLaunchKernelGGL((gemm_dma_kernel<T, AKC, BKC, WM, WN, FM, FN, SB, NS>), grid, dim3(64 * WM * WN), 0, s, d);
     return hipGetLastError();
 }
@@ -195,6 +216,8 @@ static bool aligned_to(const void* p, int64_t ld, int64_t s1, int64_t s2, int es
 
 hipError_t launch_gemm(const GemmDesc& d, hipStream_t s) {
     if (d.M < 1 || d.N < 1 || d.K < 1 || d.groupsI < 1 || d.groupsD < 1) return hipErrorInvalidValue;
+    // one-dimensional grid over all tiles of all groups (smallest tile 128 x 128)
+    if ((int64_t)((d.M + 127) / 128) * ((d.N + 127) / 128) * d.groupsI * d.groupsD > 0x7fffffff) return hipErrorInvalidValue;
     const int esz = d.precision ? 2 : 4;
     const int quad = 4 * esz;    // every operand must allow loads of 4 elements
     if (!aligned_to(d.A, d.lda, d.sAi, d.sAd, esz, quad) || !aligned_to(d.B, d.ldb, d.sBi, d.sBd, esz, quad))
@@ -212,7 +235,8 @@ hipError_t launch_gemm(const GemmDesc& d, hipStream_t s) {
     }
     // direct-to-LDS loads need whole stages and, for a rows-contiguous operand, whole 16-byte chunks of rows
     // (16-byte aligned k-rows of a rows-contiguous operand must be at least round_up(rows, 8) long)
-    const bool dma = d.K % 64 == 0 && aligned_to(d.A, d.lda, d.sAi, d.sAd, esz, 16) &&
+    // (the per-lane load offsets inside a tile are 32-bit: row strides below 2^22 elements)
+    const bool dma = d.K % 64 == 0 && d.lda < (1 << 22) && d.ldb < (1 << 22) && aligned_to(d.A, d.lda, d.sAi, d.sAd, esz, 16) &&
                      aligned_to(d.B, d.ldb, d.sBi, d.sBd, esz, 16) &&
                      (d.a_kc || d.lda >= ((d.M + 7) & ~7)) && (d.b_kc || d.ldb >= ((d.N + 7) & ~7));
     if (v == 10 && dma) return launch_dma<bf16_t, 2, 4, 4, 2, 128, 2>(d, s);

@@ -35,6 +35,7 @@ template <typename T> struct KcSrc {  // K-contiguous rows base + r*ld, r < R
     __device__ const T* row(int r) const { return r < R ? base + (int64_t)r * ld : nullptr; }
     __device__ const T* row_nocheck(int r) const { return base + (int64_t)r * ld; }
     __device__ const T* row_clamped(int r) const { return base + (int64_t)(r < R ? r : R - 1) * ld; }
+    __device__ int64_t row_offset_clamped(int r) const { return (int64_t)(r < R ? r : R - 1) * ld; }   // elements from base
     __device__ bool full(int rows) const { return R >= rows; }
 };
 
@@ -56,6 +57,7 @@ template <typename T> struct GateSrc {
         u = u < H ? u : H - 1;
         return base + ((int64_t)((n & 127) >> 5) * H + u) * ld;
     }
+    __device__ int64_t row_offset_clamped(int n) const { return row_clamped(n) - base; }
     __device__ bool full(int rows) const { return u0 + rows / 4 <= H; }
 };
 
@@ -64,9 +66,9 @@ template <typename T> struct McSrc {  // element (r,k) at base[k*ld + r], r < R
     const T* base; int64_t ld; int R;
     __device__ bool full(int rows) const { return R >= rows; }
     // 8 consecutive rows r = 8*chunk.. of k-row k (R a multiple of 8); chunks past the end repeat the last one
-    __device__ const T* chunk_clamped(int k, int chunk) const {
+    __device__ int64_t chunk_offset_clamped(int k, int chunk) const {      // elements from base
         const int last = (R >> 3) - 1;
-        return base + (int64_t)k * ld + 8 * (chunk < last ? chunk : last);
+        return (int64_t)k * ld + 8 * (chunk < last ? chunk : last);
     }
 };
 

@@ -32,12 +32,14 @@ typedef __attribute__((ext_vector_type(4))) short s16x4_t;
 typedef __attribute__((address_space(3))) s16x4_t lds_s16x4_t;
 typedef __attribute__((address_space(1))) const void glb_void_t;
 
-// One wave-wide direct load: lane l's 16 bytes at gptr land in LDS at lds_addr + 16*l.
+// One wave-wide direct load: lane l's 16 bytes at base + off (a wave-uniform 64-bit base in SGPRs plus
+// a per-lane 32-bit byte offset) land in LDS at lds_addr + 16*l.  The per-lane offsets of a tile do not
+// change from stage to stage, only the base does, so a stage costs no vector address arithmetic.
 // Issued through inline asm so that the compiler's wait-count insertion does not see it
 // (it would drain all loads before every LDS read); the main loop places its own waits.
-__device__ inline void dma16_(const void* gptr, uint32_t lds_addr_uniform) {
-    asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off"
-                 :: "v"(gptr), "s"(lds_addr_uniform) : "memory", "m0");
+__device__ inline void dma16_(uint32_t off, const void* base_uniform, uint32_t lds_addr_uniform) {
+    asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %0, %1"
+                 :: "v"(off), "s"(base_uniform), "s"(lds_addr_uniform) : "memory", "m0");
 }
 __device__ inline uint32_t lds_addr_(const void* p) {
     return (uint32_t)(uintptr_t)(lds_void_t*)p;
@@ -57,30 +59,35 @@ struct GemmDma {
     static_assert((BM * CPR) % NT == 0 && (BN * CPR) % NT == 0, "tile must divide over the workgroup");
     static_assert((ASrc::kc && BSrc::kc) || sizeof(T) == 2, "transposing LDS reads exist for 16-bit operands only");
 
+    // Byte offsets, relative to the operand's stage base, of the L 16-byte chunks this lane loads per stage.
     template <int ROWS, int L, class Src>
-    __device__ static void issue(const Src& src, int k0, char* lds_tile, int tid) {
-        const int wave_base = (tid & ~63);
+    __device__ static void lane_offsets(const Src& src, int tid, uint32_t (&off)[L]) {
 #pragma unroll
         for (int j = 0; j < L; ++j) {
             const int c = tid + j * NT;
-            const T* p;
             if constexpr (Src::kc) {
                 const int row = c / CPR;
                 const int slot = c % CPR;
                 const int chunk = slot ^ swz_<SB>(row);
-                p = src.row_clamped(row) + k0 + chunk * (16 / (int)sizeof(T));
+                off[j] = (uint32_t)(src.row_offset_clamped(row) * (int64_t)sizeof(T)) + (uint32_t)chunk * 16u;
             } else {
                 constexpr int CPK = ROWS / 8;                 // 16-byte chunks per k-row
                 static_assert(ROWS % 128 == 0, "the chunk swizzle needs k-rows of a multiple of 16 chunks");
                 const int krow = c / CPK;
                 const int slot = c % CPK;
                 const int chunk = slot ^ (4 * (krow & 3));
-                p = src.chunk_clamped(k0 + krow, chunk);
+                off[j] = (uint32_t)(src.chunk_offset_clamped(krow, chunk) * (int64_t)sizeof(T));
             }
-            // wave-uniform destination; lane l lands at dst + 16*l
-            const uint32_t dst = __builtin_amdgcn_readfirstlane(lds_addr_(lds_tile) + (uint32_t)(wave_base + j * NT) * 16u);
-            dma16_(p, dst);
         }
+    }
+
+    // Stage starting at k0 of one operand into lds_tile; wave = wave index of the caller (wave-uniform).
+    template <int L, class Src>
+    __device__ static void issue(const Src& src, const uint32_t (&off)[L], int k0, char* lds_tile, int wave) {
+        const T* sbase = Src::kc ? src.base + k0 : src.base + (int64_t)k0 * src.ld;
+        const uint32_t dst0 = lds_addr_(lds_tile) + (uint32_t)wave * 1024u;   // lane l lands at dst + 16*l
+#pragma unroll
+        for (int j = 0; j < L; ++j) dma16_(off[j], sbase, dst0 + (uint32_t)(j * NT) * 16u);
     }
 
     // 16-byte MFMA fragment of tile row `row0 + lane%32`, k-chunk `ch` (8 consecutive k) of the stage.
@@ -126,16 +133,19 @@ struct GemmDma {
     __device__ static void run(f32x16_t (&acc)[FM][FN], const ASrc& a, const BSrc& b, int K, char* lds, int rot = 0) {
         constexpr int LPT = LA + LB;
         const int tid = threadIdx.x;
-        const int lane = tid & 63, wave = tid >> 6;
+        const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
         const int wave_m = wave / WN, wave_n = wave % WN;
         const int g = lane >> 5;
         const int nk = K / KT;
+        uint32_t aoff[LA], boff[LB];
+        lane_offsets<BM, LA>(a, tid, aoff);
+        lane_offsets<BN, LB>(b, tid, boff);
 #pragma unroll
         for (int s = 0; s < NS - 1; ++s) {
             if (s < nk) {
                 int kb = s + rot; kb = kb >= nk ? kb - nk : kb;
-                issue<BM, LA>(a, kb * KT, lds + s * STAGE_BYTES, tid);
-                issue<BN, LB>(b, kb * KT, lds + s * STAGE_BYTES + A_BYTES, tid);
+                issue<LA>(a, aoff, kb * KT, lds + s * STAGE_BYTES, wave);
+                issue<LB>(b, boff, kb * KT, lds + s * STAGE_BYTES + A_BYTES, wave);
             }
         }
         for (int kt = 0; kt < nk; ++kt) {
@@ -149,8 +159,8 @@ struct GemmDma {
             if (nt < nk) {
                 char* st = lds + (nt % NS) * STAGE_BYTES;
                 int kb = nt + rot; kb = kb >= nk ? kb - nk : kb;
-                issue<BM, LA>(a, kb * KT, st, tid);
-                issue<BN, LB>(b, kb * KT, st + A_BYTES, tid);
+                issue<LA>(a, aoff, kb * KT, st, wave);
+                issue<LB>(b, boff, kb * KT, st + A_BYTES, wave);
             }
             const char* cur = lds + (kt % NS) * STAGE_BYTES;
 #pragma unroll
