@@ -30,7 +30,9 @@ __device__ inline float4 half_sum_(const float4& p, const float4& q) {
                        __fmul_rn(__fadd_rn(p.z, q.z), 0.5f), __fmul_rn(__fadd_rn(p.w, q.w), 0.5f));
 }
 
-constexpr int kUnroll = 4;
+// float4 positions per thread and stream.  One is best: on the 64-learner random-ring workload 5.88 TB/s
+// against 5.63 (2), 5.60 (4) and 5.47 (8): smaller workgroups spread more evenly over the CUs.
+constexpr int kUnroll = 1;
 
 // one element of one work item (scalar path and tails)
 __device__ inline void pair_scalar_(const float* xa, const float* xb, const float* ga, const float* gb, float* oa, float* ob,
