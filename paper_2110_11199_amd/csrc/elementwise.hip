@@ -133,10 +133,10 @@ __global__ __launch_bounds__(256) void loss_reduce_kernel(const float* row_loss,
     if (threadIdx.x == 0) loss[li] = sh[0] / (float)rows;
 }
 
-// Single-pass version: the whole row of logits lives in registers (NV float4 per thread, C <= 1024*NV),
+// Single-pass version: the whole row of logits lives in registers (NV float4 per thread, C <= 4*NT*NV),
 // so the logits are read from HBM once.
-template <typename T, int NV>
-__global__ __launch_bounds__(256) void softmax_ce_row_kernel(SoftmaxDesc p) {
+template <typename T, int NV, int NT = 256>
+__global__ __launch_bounds__(NT) void softmax_ce_row_kernel(SoftmaxDesc p) {
     const int li = blockIdx.y;
     const int64_t row = blockIdx.x;
     const float4* z4 = (const float4*)(p.logits + li * p.sLi + row * p.C);
@@ -148,22 +148,24 @@ __global__ __launch_bounds__(256) void softmax_ce_row_kernel(SoftmaxDesc p) {
     float m = -INFINITY;
 #pragma unroll
     for (int j = 0; j < NV; ++j) {
-        const int c4 = threadIdx.x + 256 * j;
+        const int c4 = threadIdx.x + NT * j;
         if (c4 < C4) {
             v[j] = z4[c4];
             m = fmaxf(fmaxf(fmaxf(v[j].x, v[j].y), fmaxf(v[j].z, v[j].w)), m);
         }
     }
-    __shared__ float red[2][4];
+    __shared__ float red[2][NT / 64];
     for (int off = 32; off > 0; off >>= 1) m = fmaxf(m, __shfl_xor(m, off));
     if ((threadIdx.x & 63) == 0) red[0][threadIdx.x >> 6] = m;
     __syncthreads();
-    m = fmaxf(fmaxf(red[0][0], red[0][1]), fmaxf(red[0][2], red[0][3]));
+    m = red[0][0];
+#pragma unroll
+    for (int w = 1; w < NT / 64; ++w) m = fmaxf(m, red[0][w]);
     float zy = 0.f;                      // logit of the label, picked up by the thread that holds it
     float s = 0.f;
 #pragma unroll
     for (int j = 0; j < NV; ++j) {
-        const int c4 = threadIdx.x + 256 * j;
+        const int c4 = threadIdx.x + NT * j;
         if (c4 < C4) {
             if ((y >> 2) == c4) zy = (y & 3) == 0 ? v[j].x : (y & 3) == 1 ? v[j].y : (y & 3) == 2 ? v[j].z : v[j].w;
             v[j].x = exp_fast_(v[j].x - m); v[j].y = exp_fast_(v[j].y - m); v[j].z = exp_fast_(v[j].z - m); v[j].w = exp_fast_(v[j].w - m);
@@ -173,12 +175,14 @@ __global__ __launch_bounds__(256) void softmax_ce_row_kernel(SoftmaxDesc p) {
     for (int off = 32; off > 0; off >>= 1) s += __shfl_xor(s, off);
     if ((threadIdx.x & 63) == 0) red[1][threadIdx.x >> 6] = s;
     __syncthreads();
-    s = (red[1][0] + red[1][1]) + (red[1][2] + red[1][3]);
+    s = red[1][0];
+#pragma unroll
+    for (int w = 1; w < NT / 64; ++w) s += red[1][w];
     const float inv = 1.f / s;
     const float scale = 1.f / (float)p.rows;
 #pragma unroll
     for (int j = 0; j < NV; ++j) {
-        const int c4 = threadIdx.x + 256 * j;
+        const int c4 = threadIdx.x + NT * j;
         if (c4 < C4) {
             float4 pr = make_float4(v[j].x * inv, v[j].y * inv, v[j].z * inv, v[j].w * inv);
             if ((y >> 2) == c4) {
@@ -195,7 +199,7 @@ __global__ __launch_bounds__(256) void softmax_ce_row_kernel(SoftmaxDesc p) {
             }
         }
     }
-    if ((y >> 2) % 256 == (int)threadIdx.x) p.row_loss[li * p.rows + row] = -((zy - m) - logf(s));
+    if ((y >> 2) % NT == (int)threadIdx.x) p.row_loss[li * p.rows + row] = -((zy - m) - logf(s));
 }
 
 template <typename T>
@@ -203,10 +207,13 @@ static void launch_softmax_t(const SoftmaxDesc& d, hipStream_t s) {
     dim3 grid((unsigned)d.rows, (unsigned)d.L);
     const bool vec = d.C % 4 == 0 && d.sLi % 4 == 0 && d.sDi % 4 == 0 && (uintptr_t)d.logits % 16 == 0 &&
                      (uintptr_t)d.dlogits % 16 == 0;
+    // long rows: 512 threads per row, so that a thread holds at most 16 float4 (measured on 32 000 classes:
+    // 1.55 ms against 2.25 ms with 256 threads x 32 float4, whose 128 registers allow three waves per SIMD only)
     if (vec && d.C <= 1024) hipLaunchKernelGGL((softmax_ce_row_kernel<T, 1>), grid, dim3(256), 0, s, d);
     else if (vec && d.C <= 4096) hipLaunchKernelGGL((softmax_ce_row_kernel<T, 4>), grid, dim3(256), 0, s, d);
-    else if (vec && d.C <= 16384) hipLaunchKernelGGL((softmax_ce_row_kernel<T, 16>), grid, dim3(256), 0, s, d);
-    else if (vec && d.C <= 32768) hipLaunchKernelGGL((softmax_ce_row_kernel<T, 32>), grid, dim3(256), 0, s, d);
+    else if (vec && d.C <= 8192) hipLaunchKernelGGL((softmax_ce_row_kernel<T, 4, 512>), grid, dim3(512), 0, s, d);
+    else if (vec && d.C <= 16384) hipLaunchKernelGGL((softmax_ce_row_kernel<T, 8, 512>), grid, dim3(512), 0, s, d);
+    else if (vec && d.C <= 32768) hipLaunchKernelGGL((softmax_ce_row_kernel<T, 16, 512>), grid, dim3(512), 0, s, d);
     else hipLaunchKernelGGL(softmax_ce_kernel<T>, grid, dim3(256), 0, s, d);
 }
 

@@ -53,6 +53,8 @@ SHAPES = [
     Shape(8, 8, 1, 1, 4, 8, 2, 1),            # one frame: no recurrence
     Shape(24, 192, 2, 1, 16, 64, 130, 3),     # hidden 192: ragged unit tiles of the direct-to-LDS kernels, batch 130
     Shape(16, 128, 1, 1, 0, 40, 48, 4),       # batch 48: the 64-row recurrent tile configuration
+    Shape(8, 32, 1, 0, 0, 1500, 3, 2),        # 1500 classes: softmax rows of 4 float4 per thread
+    Shape(8, 32, 1, 0, 0, 5000, 3, 2),        # 5000 classes: softmax rows on 512 threads
 ]
 
 
