@@ -135,6 +135,9 @@ __global__ __launch_bounds__(256) void loss_reduce_kernel(const float* row_loss,
 
 // Single-pass version: the whole row of logits lives in registers (NV float4 per thread, C <= 4*NT*NV),
 // so the logits are read from HBM once.
+typedef float vf4_t __attribute__((ext_vector_type(4)));
+typedef uint32_t vu2_t __attribute__((ext_vector_type(2)));
+
 template <typename T, int NV, int NT = 256>
 __global__ __launch_bounds__(NT) void softmax_ce_row_kernel(SoftmaxDesc p) {
     const int li = blockIdx.y;
@@ -150,7 +153,7 @@ __global__ __launch_bounds__(NT) void softmax_ce_row_kernel(SoftmaxDesc p) {
     for (int j = 0; j < NV; ++j) {
         const int c4 = threadIdx.x + NT * j;
         if (c4 < C4) {
-            v[j] = z4[c4];
+            { const vf4_t t4 = __builtin_nontemporal_load((const vf4_t*)z4 + c4); v[j] = make_float4(t4.x, t4.y, t4.z, t4.w); }   // read once
             m = fmaxf(fmaxf(fmaxf(v[j].x, v[j].y), fmaxf(v[j].z, v[j].w)), m);
         }
     }
@@ -193,9 +196,9 @@ __global__ __launch_bounds__(NT) void softmax_ce_row_kernel(SoftmaxDesc p) {
                 uint2 o;
                 o.x = pack_bf16(pr.x, pr.y);
                 o.y = pack_bf16(pr.z, pr.w);
-                ((uint2*)dz)[c4] = o;
+                { vu2_t o2; o2.x = o.x; o2.y = o.y; __builtin_nontemporal_store(o2, (vu2_t*)dz + c4); }
             } else {
-                ((float4*)dz)[c4] = pr;
+                { vf4_t o4; o4.x = pr.x; o4.y = pr.y; o4.z = pr.z; o4.w = pr.w; __builtin_nontemporal_store(o4, (vf4_t*)dz + c4); }
             }
         }
     }
@@ -239,10 +242,10 @@ __global__ __launch_bounds__(256) void colsum_kernel(const T* in, int64_t ld, in
     if (col < N) {
         int64_t r = slice;
         for (; r + 12 < rows; r += 16) {
-            s0 += Elem<T>::to(src[r * ld + col]);
-            s1 += Elem<T>::to(src[(r + 4) * ld + col]);
-            s2 += Elem<T>::to(src[(r + 8) * ld + col]);
-            s3 += Elem<T>::to(src[(r + 12) * ld + col]);
+            s0 += Elem<T>::to(__builtin_nontemporal_load(src + r * ld + col));
+            s1 += Elem<T>::to(__builtin_nontemporal_load(src + (r + 4) * ld + col));
+            s2 += Elem<T>::to(__builtin_nontemporal_load(src + (r + 8) * ld + col));
+            s3 += Elem<T>::to(__builtin_nontemporal_load(src + (r + 12) * ld + col));
         }
         for (; r < rows; r += 4) s0 += Elem<T>::to(src[r * ld + col]);
     }

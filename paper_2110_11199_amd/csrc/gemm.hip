@@ -93,7 +93,8 @@ __device__ inline void store_tile(f32x16_t (&acc)[FM][FN], const GemmDesc& p, in
 #pragma unroll
                 for (int i = 0; i < 16; ++i) {
                     const int r = 8 * (i >> 2) + (i & 3);
-                    if (row0 + r < p.M) c[(int64_t)r * p.ldc] = acc[fm][fn][i];
+                    // written once, read by a later kernel: keep it from displacing the operand panels in L2
+                    if (row0 + r < p.M) __builtin_nontemporal_store(acc[fm][fn][i], c + (int64_t)r * p.ldc);
                 }
             }
         }
