@@ -342,7 +342,8 @@ hipError_t launch_rec_forward(const RecDesc& d, hipStream_t s) {
         const unsigned groups = (unsigned)(d.L * d.D);
         if (d.B > 64) {
             dim3 grid(groups, (d.H + 31) / 32, (d.B + 127) / 128);
-            hipLaunchKernelGGL((rec_forward_dma_kernel<bf16_t, 4, 1, 64, 4>), grid, dim3(256), 0, s, d);   // 64 KB of LDS: two workgroups per CU
+            // two 32 KB stages (whole 128-byte lines per row and stage): 64 KB of LDS, two workgroups per CU
+            hipLaunchKernelGGL((rec_forward_dma_kernel<bf16_t, 4, 1, 128, 2>), grid, dim3(256), 0, s, d);
         } else {
             dim3 grid(groups, (d.H + 63) / 64, (d.B + 63) / 64);
             hipLaunchKernelGGL((rec_forward_dma_kernel<bf16_t, 2, 2, 128, 3>), grid, dim3(256), 0, s, d);
