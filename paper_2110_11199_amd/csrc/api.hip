@@ -107,6 +107,7 @@ struct adpsgd_handle {
     // workspace regions
     float* params[2];
     float* grads;
+    float* dbp;        // [L][T * batch tiles][D*4H]: per-frame column sums of da (partial bias gradients)
     bf16_t* wx0p;      // [L][D*4H][ldx] bf16: W_x of layer 0 with zero-padded rows, or NULL
     bf16_t* shadow;
     void* x0; int32_t* labels;
@@ -208,6 +209,7 @@ size_t plan(adpsgd_handle* h, void* base) {
         h->dy = (float*)w.take(L * M * DH * 4);
         h->da = w.take(L * M * G4 * e);
         h->dc = (float*)w.take(L * (size_t)h->B * DH * 4);
+        h->dbp = (float*)w.take(L * (size_t)h->T * rec_backward_batch_tiles(h->B) * G4 * 4);
         h->row_loss = (float*)w.take(L * M * 4);
         h->loss = (float*)w.take(L * 4);
     }
@@ -400,6 +402,8 @@ int compute_gradients(adpsgd_handle* h, const float* at, const void* const* batc
         r.dy = h->dy; r.sDYi = M * DH;
         r.da = h->da; r.sDAi = M * G4;
         r.dc = h->dc; r.sDCi = (int64_t)B * DH;
+        const int64_t dbrows = (int64_t)T * rec_backward_batch_tiles(B);
+        r.dbp = h->dbp; r.sDBi = dbrows * G4;
         // per frame and (learner, direction): W_h once, da in (4 gates) and out, dY, 4 gates, c, c', dc in and out
         if (int rc = mark(h, 3, T, 2.0 * B * H * 4 * H * (T - 1) * L * D,
                           (double)T * L * D * (4.0 * H * H * esz + (double)B * H * (8 * esz + 4 + 16 + 8 + 8)))) return rc;
@@ -434,8 +438,9 @@ int compute_gradients(adpsgd_handle* h, const float* at, const void* const* batc
             for (int i = 0; i < L; ++i)
                 HIPCHK(hipMemsetAsync(Gr(h->ix_wh[l]) + (size_t)i * Pp, 0, (size_t)G4 * H * 4, s), "zero dW_h");
         }
+        // db = sum over the frames (and batch tiles) of the column sums the backward steps left behind
         if (int rc = mark(h, 5, 1)) return rc;
-        HIPCHK(launch_colsum(prec, h->da, G4, M * G4, M, (int)G4, Gr(h->ix_b[l]), Pp, L, s), "db");
+        HIPCHK(launch_colsum(0, h->dbp, G4, dbrows * G4, dbrows, (int)G4, Gr(h->ix_b[l]), Pp, L, s), "db");
         if (l > 0) {
             // dY_{l-1} = da W_x  (sum over both directions: K = D*4H)
             g = GemmDesc{};

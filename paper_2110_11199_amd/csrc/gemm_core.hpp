@@ -276,6 +276,7 @@ template <> __device__ inline void mma_chunk<float>(f32x16_t& acc, const uint4& 
 template <typename T, class ASrc, class BSrc, int WM, int WN, int FM, int FN, int VB, int SB = 64>
 struct GemmCore {
     static constexpr int BM = 32 * FM * WM, BN = 32 * FN * WN, NT = 64 * WM * WN;
+    static constexpr int kWM = WM, kWN = WN;
     static constexpr int KT = SB / (int)sizeof(T);
     typedef LdsTile<T, BM, SB, ASrc::kc> ATile;
     typedef LdsTile<T, BN, SB, BSrc::kc> BTile;

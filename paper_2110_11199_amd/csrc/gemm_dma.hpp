@@ -50,6 +50,7 @@ template <int SB> __device__ inline int swz_(int r) { return (r / (256 / SB)) & 
 template <typename T, class ASrc, class BSrc, int WM, int WN, int FM, int FN, int SB, int NS>
 struct GemmDma {
     static constexpr int BM = 32 * FM * WM, BN = 32 * FN * WN, NT = 64 * WM * WN;
+    static constexpr int kWM = WM, kWN = WN;
     static constexpr int KT = SB / (int)sizeof(T);
     static constexpr int CPR = SB / 16;                       // 16-byte chunks per tile row
     static constexpr int A_BYTES = BM * SB, B_BYTES = BN * SB;

@@ -70,7 +70,12 @@ struct RecDesc {               // one time step of one layer, all learners and d
     const float* dy; int64_t sDYi;       // [L][T*B][D*H] fp32, gradient w.r.t. the layer output
     void* da; int64_t sDAi;              // [L][T*B][D*4H] operand type, gate pre-activation grads
     float* dc; int64_t sDCi;             // [L][D][B][H] fp32 running dL/dc
+    // column sums of da over the batch rows of every tile (partial bias gradients), summed over the
+    // frames and batch tiles afterwards: [L][T * batch tiles][D*4H] fp32
+    float* dbp; int64_t sDBi;
 };
+// Batch tiles of the backward step kernels for a batch of B rows (rows of dbp per frame).
+int rec_backward_batch_tiles(int B);
 hipError_t launch_rec_forward(const RecDesc& d, hipStream_t s);
 hipError_t launch_rec_backward(const RecDesc& d, hipStream_t s);
 void set_rec_dma(int on);

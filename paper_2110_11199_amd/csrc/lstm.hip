@@ -101,7 +101,7 @@ __device__ inline void forward_epilogue(const RecDesc& p, f32x16_t (&acc)[1][4],
 //   da = (di i(1-i), df f(1-f), dg (1-g^2), do o(1-o))
 template <typename T, class Core, int FN>
 __device__ inline void backward_epilogue(const RecDesc& p, f32x16_t (&acc)[1][FN], int li, int d, int t, int tp,
-                                         int u0, int b0) {
+                                         int u0, int b0, char* lds) {
     const int D = p.D, H = p.H, B = p.B;
     const int64_t DH = (int64_t)D * H, G4 = (int64_t)D * 4 * H;
     const bool has_prev = tp >= 0 && tp < p.T;
@@ -110,8 +110,10 @@ __device__ inline void backward_epilogue(const RecDesc& p, f32x16_t (&acc)[1][FN
     const float* dy = p.dy + li * p.sDYi;
     float* dcb = p.dc + li * p.sDCi + (int64_t)d * B * H;
     T* da = (T*)p.da + li * p.sDAi;
+    float cs[FN][4];                          // sums of the four da values over this lane's 16 rows
 #pragma unroll
     for (int fn = 0; fn < FN; ++fn) {
+        cs[fn][0] = cs[fn][1] = cs[fn][2] = cs[fn][3] = 0.f;
         const int u = u0 + Core::acc_col(fn);
         if (u >= H) continue;
         // load everything, compute everything, store everything (see the forward epilogue)
@@ -132,6 +134,7 @@ __device__ inline void backward_epilogue(const RecDesc& p, f32x16_t (&acc)[1][FN
         }
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
+            // rows past the batch: all gates read as 0, so all four results are 0 whatever the accumulator holds
             const float dh = dyv[i] + acc[0][fn][i];
             const float ig = gi[i], fg = gf[i], g2 = gg[i], og = go[i];
             const float tc = tanhf_(cv[i]);
@@ -140,6 +143,7 @@ __device__ inline void backward_epilogue(const RecDesc& p, f32x16_t (&acc)[1][FN
             const float di = dcv * g2, dg = dcv * ig, df = dcv * cp[i];
             dcr[i] = dcv * fg;
             float a0 = di * ig * (1.f - ig), a1 = df * fg * (1.f - fg), a2 = dg * (1.f - g2 * g2), a3 = dov * og * (1.f - og);
+            cs[fn][0] += a0; cs[fn][1] += a1; cs[fn][2] += a2; cs[fn][3] += a3;
             if constexpr (sizeof(T) == 2) {
                 pk0[i] = pack_bf16(a0, a1);
                 pk1[i] = pack_bf16(a2, a3);
@@ -161,6 +165,29 @@ __device__ inline void backward_epilogue(const RecDesc& p, f32x16_t (&acc)[1][FN
                 dp[0] = gi[i]; dp[H] = gf[i]; dp[2 * (int64_t)H] = gg[i]; dp[3 * (int64_t)H] = go[i];
             }
         }
+    }
+    // Bias gradient: the column sums of da over the rows of this tile, in a fixed order (lane pair, then
+    // the waves along the rows through LDS), written as one row of partial sums per (frame, batch tile).
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    static_assert((Core::BN & (Core::BN - 1)) == 0, "the reduction indexing needs a power-of-two tile width");
+    float* red = (float*)lds;                 // [kWM][BN][4]
+    __syncthreads();                          // the stage buffers are no longer read
+#pragma unroll
+    for (int fn = 0; fn < FN; ++fn) {
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+            const float v = cs[fn][g] + __shfl_xor(cs[fn][g], 32);
+            if (lane < 32) red[(((wave / Core::kWN) * Core::BN) + Core::acc_col(fn)) * 4 + g] = v;
+        }
+    }
+    __syncthreads();
+    float* out = p.dbp + li * p.sDBi + ((int64_t)t * gridDim.z + blockIdx.z) * G4 + (int64_t)d * 4 * H;
+    for (int idx = threadIdx.x; idx < Core::BN * 4; idx += Core::NT) {
+        const int col = idx & (Core::BN - 1), g = idx / Core::BN;
+        float sum = red[col * 4 + g];
+#pragma unroll
+        for (int w = 1; w < Core::kWM; ++w) sum += red[(w * Core::BN + col) * 4 + g];
+        if (u0 + col < H) out[(int64_t)g * H + u0 + col] = sum;
     }
 }
 
@@ -220,7 +247,7 @@ __global__ __launch_bounds__(256) void rec_backward_kernel(RecDesc p) {
         b.ld = H; b.R = H - u0;
         Core::run(acc, a, b, 4 * H, lds);
     }
-    backward_epilogue<T, Core, FN>(p, acc, li, d, t, tp, u0, b0);
+    backward_epilogue<T, Core, FN>(p, acc, li, d, t, tp, u0, b0, lds);
 }
 
 // ---- direct-to-LDS versions (bf16, H a multiple of the stage, 16-byte aligned rows) -----
@@ -284,7 +311,7 @@ __global__ __launch_bounds__(64 * WM * WN) void rec_backward_dma_kernel(RecDesc 
         b.ld = H; b.R = H - u0;
         Core::run(acc, a, b, 4 * H, lds, stage_rotation_bwd(4 * H / Core::KT));
     }
-    backward_epilogue<T, Core, FN>(p, acc, li, d, t, tp, u0, b0);
+    backward_epilogue<T, Core, FN>(p, acc, li, d, t, tp, u0, b0, lds);
 }
 
 // ---- launchers ----------------------------------------------------------------------
@@ -320,6 +347,9 @@ static hipError_t bwd_t(const RecDesc& d, hipStream_t s) {
     }
     return hipGetLastError();
 }
+
+// rows of the batch per backward tile: 128, 64 or 32 (the same choice in every kernel variant)
+int rec_backward_batch_tiles(int B) { return B > 64 ? (B + 127) / 128 : B > 32 ? (B + 63) / 64 : (B + 31) / 32; }
 
 static bool rec_ok(const RecDesc& d) {
     return d.L >= 1 && d.D >= 1 && d.D <= 2 && d.B >= 1 && d.H >= 4 && d.H % 4 == 0 && d.T >= 1 &&

@@ -14,7 +14,7 @@ pytestmark = pytest.mark.gpu
 
 TOL = {0: 1e-4, 1: 2e-2}
 # bf16 mode against the oracle run with its GEMM operands rounded to bf16 as well: what is
-# left is summation order, the bf16 rounding of the bias-gradient inputs, and values that land on
+# left is summation order and values that land on
 # the other side of a bf16 rounding boundary (one bf16 ulp = 2^-8 relative).
 TOL_EMULATED = 1e-2
 
@@ -50,7 +50,8 @@ SHAPES = [
     Shape(24, 36, 2, 1, 16, 40, 33, 3),       # bottleneck, hidden not a multiple of 8/32, batch 33
     Shape(20, 64, 1, 1, 0, 300, 70, 4),       # batch 70 (64-row tiles + tail), several class tiles
     Shape(16, 32, 3, 0, 8, 36, 130, 2),       # batch 130 (128-row tiles + tail), unidirectional
-    Shape(8, 8, 1, 1, 4, 8, 2, 1),            # one frame: no recurrence
+    Shape(8, 8, 1, 1, 4, 8, 9, 1),            # one frame: no recurrence (9 rows: with 2 the bf16 rounding of a single
+                                              # operand shows up as 2.2e-2 in a bias gradient, in the oracle's own bf16 run too)
     Shape(24, 192, 2, 1, 16, 64, 130, 3),     # hidden 192: ragged unit tiles of the direct-to-LDS kernels, batch 130
     Shape(16, 128, 1, 1, 0, 40, 48, 4),       # batch 48: the 64-row recurrent tile configuration
     Shape(8, 32, 1, 0, 0, 1500, 3, 2),        # 1500 classes: softmax rows of 4 float4 per thread
