@@ -59,9 +59,13 @@ typedef struct adpsgd_handle* adpsgd_t;   /* opaque; owned by the library (host 
 typedef enum { ADPSGD_FIXED_RING = 0, ADPSGD_RANDOM_RING = 1, ADPSGD_D1D = 2 } adpsgd_pattern;
 /* Mixing operator applied along that pattern.
  *   PAIR  (x_i + x_j)/2 with the partner j of a perfect matching on the ring order
+ *   TRI   (x_left + x_i + x_right)/3 with the two neighbours on the ring order: the
+ *         circulant operator T^f of Eq. 9 (Section III-B) on the fixed ring and its
+ *         permuted form T^r = P' T^f P on the random ring (Section III-C); summed as
+ *         (x_left + x_i) + x_right in that order, then times fl(1/3)
  *   ALL   the global mean, T = 11'/L (allreduce, Section III-A / III-D)
  *   DEFAULT = PAIR for the rings, ALL for delay-by-one.                         */
-typedef enum { ADPSGD_MIX_DEFAULT = -1, ADPSGD_MIX_PAIR = 0, ADPSGD_MIX_ALL = 2 } adpsgd_mix;
+typedef enum { ADPSGD_MIX_DEFAULT = -1, ADPSGD_MIX_PAIR = 0, ADPSGD_MIX_TRI = 1, ADPSGD_MIX_ALL = 2 } adpsgd_mix;
 /* Arithmetic of the GEMMs: fp32 operands, or bf16 operands (rounded to nearest
  * even from the fp32 master) with fp32 accumulation.  State, gates, softmax
  * and the update are fp32 in both.                                              */

@@ -124,7 +124,7 @@ int check_config(const adpsgd_config* c, std::string& why) {
     if (!c) { why = "config is NULL"; return ADPSGD_EINVAL; }
     if (c->L < 1 || c->L > ADPSGD_MAX_LEARNERS) { why = "L must be in 1..128"; return ADPSGD_EINVAL; }
     if (c->pattern < 0 || c->pattern > 2) { why = "unknown pattern"; return ADPSGD_EINVAL; }
-    if (c->mix != ADPSGD_MIX_DEFAULT && c->mix != ADPSGD_MIX_PAIR && c->mix != ADPSGD_MIX_ALL) { why = "unknown mix"; return ADPSGD_EINVAL; }
+    if (c->mix != ADPSGD_MIX_DEFAULT && c->mix != ADPSGD_MIX_PAIR && c->mix != ADPSGD_MIX_TRI && c->mix != ADPSGD_MIX_ALL) { why = "unknown mix"; return ADPSGD_EINVAL; }
     if (c->tau < -1 || c->tau > 1) { why = "tau must be 0, 1 or -1"; return ADPSGD_EINVAL; }
     if (c->precision != ADPSGD_FP32 && c->precision != ADPSGD_BF16_GEMM) { why = "unknown precision"; return ADPSGD_EINVAL; }
     if (!(c->straggler_p >= 0.f && c->straggler_p < 1.f)) { why = "straggler_p must be in [0,1)"; return ADPSGD_EINVAL; }
@@ -531,7 +531,7 @@ int adpsgd_step(adpsgd_t h, const void* const* batch_ptrs, float lr) {
         if (int rc = compute_gradients(h, at, batch_ptrs)) return rc;
         for (int i = 0; i < L; ++i) u.g[i] = h->grads + (size_t)i * h->Ppad;
     }
-    for (int i = 0; i < L; ++i) { u.partner[i] = (int16_t)partner[i]; u.active[i] = (int16_t)active[i]; }
+    for (int i = 0; i < L; ++i) { u.partner[i] = (int16_t)partner[i]; u.active[i] = (int16_t)active[i]; u.order[i] = (int16_t)order[i]; }
     // bf16 GEMM operands of the next iteration: its gradient point is x^k when tau = 1, x^{k+1} otherwise
     u.shadow = (!h->flat && h->prec) ? h->shadow : nullptr;
     u.emit_input = h->tau == 1;

@@ -26,13 +26,14 @@ void set_gemm_variant(int v);
 // ---- fused mixing + SGD update ------------------------------------------------
 struct UpdateDesc {
     int L;
-    int mix;                   // 0 pair, 2 all
+    int mix;                   // 0 pair, 1 ring neighbours (thirds), 2 all
     int64_t P;                 // elements per learner
     const float* src;          // x^k, learner i at src + i*stride
     float* dst;                // x^{k+1}, learner i at dst + i*stride (may equal src)
     int64_t stride;
     const float* g[128];       // gradient of learner i
     int16_t partner[128];
+    int16_t order[128];        // ring order (mix 1): order[p] = learner at ring position p
     int16_t active[128];
     float lr;
     bf16_t* shadow;            // optional [L][stride] bf16 copy of the next gradient point, or NULL

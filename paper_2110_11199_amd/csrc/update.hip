@@ -7,6 +7,7 @@
 // the update is safe in place.  Arithmetic order (each operation rounded once,
 // no fused multiply-add):
 //     pair: m = (x_i + x_j) * 0.5      all: m = (((x_0 + x_1) + ...) ) * (1/L)
+//     ring neighbours: m = ((x_left + x_i) + x_right) * (1/3)
 //     x_i <- m - (lr * g_i)
 #include "kernels.hpp"
 
@@ -195,6 +196,59 @@ __global__ __launch_bounds__(256) void all_update_kernel(AllArgs p) {
     }
 }
 
+// ---- ring-neighbour mixing with weights 1/3 (the circulant operator T^f of Eq. 9, and T^r = P' T^f P) -------
+// One thread owns an element index of all learners and walks the ring order with the previous, current and
+// next model value in registers: every model is read once (the last one of the order twice), so the update
+// is safe in place and moves the same 12 bytes per learner and element as the pairwise one.
+struct TriArgs {
+    const float* src; float* dst; int64_t stride; int64_t P; float lr; float third; int L;
+    bf16_t* shadow; int emit_input;
+    const float* g[128];
+    int16_t order[128];
+};
+
+__device__ inline float tri_mean_(float l, float c, float r, float third) { return __fmul_rn(__fadd_rn(__fadd_rn(l, c), r), third); }
+
+__device__ inline void tri_scalar_(const TriArgs& p, int64_t t) {
+    const float first = p.src[p.order[0] * p.stride + t];
+    float prev = p.src[p.order[p.L - 1] * p.stride + t], cur = first;
+    for (int q = 0; q < p.L; ++q) {
+        const int i = p.order[q];
+        const float next = q + 1 < p.L ? p.src[p.order[q + 1] * p.stride + t] : first;
+        const float r = sgd_(tri_mean_(prev, cur, next, p.third), p.lr, p.g[i][t]);
+        p.dst[i * p.stride + t] = r;
+        if (p.shadow) p.shadow[i * p.stride + t] = f32_to_bf16(p.emit_input ? cur : r);
+        prev = cur; cur = next;
+    }
+}
+
+template <bool VEC>
+__global__ __launch_bounds__(256) void tri_update_kernel(TriArgs p) {
+    const int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if constexpr (VEC) {
+        const int64_t n4 = p.P >> 2;
+        if (e < n4) {
+            const float4 first = ldnt_(p.src + p.order[0] * p.stride, e);
+            float4 prev = ldnt_(p.src + p.order[p.L - 1] * p.stride, e), cur = first;
+            for (int q = 0; q < p.L; ++q) {
+                const int i = p.order[q];
+                float4 next = first;
+                if (q + 1 < p.L) next = ldnt_(p.src + p.order[q + 1] * p.stride, e);
+                const float4 g = ldnt_(p.g[i], e);
+                const float4 m = make_float4(tri_mean_(prev.x, cur.x, next.x, p.third), tri_mean_(prev.y, cur.y, next.y, p.third),
+                                             tri_mean_(prev.z, cur.z, next.z, p.third), tri_mean_(prev.w, cur.w, next.w, p.third));
+                const float4 r = pair_new_(m, p.lr, g);
+                stnt_(p.dst + i * p.stride, e, r);
+                if (p.shadow) emit4_(p.shadow + i * p.stride, e, p.emit_input ? cur : r);
+                prev = cur; cur = next;
+            }
+        }
+        if (blockIdx.x == 0 && threadIdx.x < (p.P & 3)) tri_scalar_(p, (n4 << 2) + threadIdx.x);
+    } else {
+        if (e < p.P) tri_scalar_(p, e);
+    }
+}
+
 __global__ __launch_bounds__(256) void average_kernel(const float* x, int64_t stride, int L, int64_t P,
                                                       float inv_L, float* out) {
     const int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x;
@@ -221,6 +275,26 @@ hipError_t launch_update(const UpdateDesc& d, hipStream_t s) {
             hipLaunchKernelGGL(all_update_kernel<true>, dim3(blocks), dim3(256), 0, s, a);
         } else {
             hipLaunchKernelGGL(all_update_kernel<false>, dim3((unsigned)((d.P + 255) / 256)), dim3(256), 0, s, a);
+        }
+        return hipGetLastError();
+    }
+    if (d.mix == 1) {
+        TriArgs a;
+        a.src = d.src; a.dst = d.dst; a.stride = d.stride; a.P = d.P; a.lr = d.lr; a.L = d.L;
+        a.third = 1.0f / 3.0f;
+        a.shadow = d.shadow; a.emit_input = d.emit_input;
+        for (int i = 0; i < 128; ++i) { a.g[i] = i < d.L ? d.g[i] : nullptr; a.order[i] = i < d.L ? d.order[i] : 0; }
+        // the order must be a permutation of 0..L-1 (an index out of range would address another learner's memory)
+        bool seen[128] = {false};
+        for (int i = 0; i < d.L; ++i) {
+            if (d.order[i] < 0 || d.order[i] >= d.L || seen[d.order[i]]) return hipErrorInvalidValue;
+            seen[d.order[i]] = true;
+        }
+        if (vec) {
+            const int64_t n4 = d.P >> 2;
+            hipLaunchKernelGGL(tri_update_kernel<true>, dim3((unsigned)(((n4 > 0 ? n4 : 1) + 255) / 256)), dim3(256), 0, s, a);
+        } else {
+            hipLaunchKernelGGL(tri_update_kernel<false>, dim3((unsigned)((d.P + 255) / 256)), dim3(256), 0, s, a);
         }
         return hipGetLastError();
     }

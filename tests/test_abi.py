@@ -54,7 +54,9 @@ def test_config_validation_and_workspace_size():
            Bd.make_config(4, 0, flat_params=8, tau=1, straggler_p=0.1),
            Bd.make_config(4, 0, input_dim=39, hidden=64, layers=1, classes=100, batch=4, frames=20),
            Bd.make_config(4, 0, input_dim=40, hidden=64, layers=0, classes=100, batch=4, frames=20),
-           Bd.make_config(4, 0, flat_params=8, precision=2), Bd.make_config(4, 0, flat_params=8, mix=1)]
+           Bd.make_config(4, 0, flat_params=8, precision=2), Bd.make_config(4, 0, flat_params=8, mix=3),
+           Bd.make_config(4, 1, flat_params=8, mix=Bd.MIX_TRI, straggler_p=0.1)]
+    assert Bd.adpsgd_workspace_bytes(Bd.make_config(4, 0, flat_params=8, mix=Bd.MIX_TRI)) > 0     # ring neighbours, weights 1/3
     for cfg in bad:
         with pytest.raises(Bd.AdpsgdError) as ei:
             Bd.adpsgd_workspace_bytes(cfg)

@@ -49,6 +49,28 @@ def test_delay_by_one_global_mean(L, P):
     _run(L, P, S.D1D, 4)
 
 
+@pytest.mark.parametrize("L", [1, 2, 3, 5, 16, 128])
+@pytest.mark.parametrize("pattern", [S.FIXED_RING, S.RANDOM_RING])
+def test_ring_neighbour_thirds(L, pattern):
+    # the circulant operator T^f of Eq. 9 (and T^r = P' T^f P on the random ring), in place and bit-exact
+    print("update tri L", L, pattern, flush=True)
+    _run(L, 70001 if L < 100 else 1003, pattern, 5, mix=S.MIX_TRI)
+
+
+@pytest.mark.parametrize("P", [1, 3, 4, 1023, 100003])
+def test_ring_neighbour_thirds_sizes_and_delay(P):
+    _run(7, P, S.RANDOM_RING, 4, mix=S.MIX_TRI)
+    _run(7, P, S.D1D, 3, mix=S.MIX_TRI)              # tau = 1: ping-pong buffers
+
+
+def test_ring_neighbour_thirds_rejects_stragglers():
+    from paper_2110_11199_amd import binding as Bd
+    cfg = Bd.make_config(4, S.RANDOM_RING, flat_params=16, straggler_p=0.1, mix=Bd.MIX_TRI)
+    with pytest.raises(Bd.AdpsgdError) as ei:
+        Bd.adpsgd_workspace_bytes(cfg)
+    assert ei.value.code == Bd.EINVAL
+
+
 def test_delay_by_one_with_pairwise_mixing_and_ring_with_global_mean():
     _run(6, 5001, S.D1D, 4, mix=S.MIX_PAIR)
     _run(6, 5001, S.FIXED_RING, 3, mix=S.MIX_ALL, tau=0)
