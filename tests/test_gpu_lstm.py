@@ -93,8 +93,8 @@ def _run_recurrence(shape, L, pattern, prec, steps, lr, seed=0, scale=0.1, **kw)
     w0 = synth.initial_model(seed, P, scale)
     eng = _engine(shape, L, pattern, prec, seed=seed, **kw)
     eng.set_params(-1, torch.from_numpy(w0).cuda())
-    ora = A.Oracle(L, pattern, seed, shape=shape, w0=w0, straggler_p=kw.get("straggler_p", 0.0))
-    emu = A.Oracle(L, pattern, seed, shape=shape, w0=w0, bf16_gemm=True) if prec else None
+    ora = A.Oracle(L, pattern, seed, shape=shape, w0=w0, straggler_p=kw.get("straggler_p", 0.0), mix=kw.get("mix"))
+    emu = A.Oracle(L, pattern, seed, shape=shape, w0=w0, bf16_gemm=True, mix=kw.get("mix")) if prec else None
     for k in range(steps):
         b = _batches(shape, L, k, seed)
         eng.step(_to_dev(b), lr)
@@ -134,6 +134,13 @@ def test_delay_by_one_small_model(prec):
     # alone reaches 2.2e-2 on the smallest tensors
     ora = _run_recurrence(Shape(12, 16, 2, 1, 8, 20, 3, 4), 4, S.D1D, prec, 4, 0.3, seed=2, scale=0.1)
     assert ora.tau == 1
+
+
+@pytest.mark.parametrize("prec", [0, 1])
+def test_ring_neighbour_mixing_small_model(prec):
+    print("ring neighbours (weights 1/3), model-bearing", prec, flush=True)
+    ora = _run_recurrence(Shape(12, 16, 2, 1, 8, 20, 5, 4), 5, S.RANDOM_RING, prec, 4, 0.3, seed=5, scale=0.1, mix=S.MIX_TRI)
+    assert ora.mix == S.MIX_TRI
 
 
 def test_library_initial_model_matches_generator_spec():
