@@ -62,6 +62,14 @@ def mix_update(x, g, mix, order, partner, active, lr):
     return out
 
 
+def consensus_distance(x):
+    """sum_i ||x_i - xbar||^2 over the rows x_i of x, xbar their mean; everything in float64."""
+    x = np.asarray(x, dtype=np.float64)
+    xbar = x.mean(axis=0)
+    d = x - xbar
+    return float((d * d).sum())
+
+
 class Oracle:
     """L learners, model-bearing (shape given) or model-free (flat_params)."""
 
@@ -111,3 +119,8 @@ class Oracle:
     def average(self):
         """Output model of Algorithm 1: the learner average (float64 mean)."""
         return self.x.astype(np.float64).mean(axis=0)
+
+    def consensus(self):
+        """Consensus distance sum_i ||x_i - xbar||^2 of the learners' models (float64): the quantity that
+        the mixing operator contracts by its second largest eigenvalue magnitude (Section II, Eq. 5-7)."""
+        return consensus_distance(self.x)

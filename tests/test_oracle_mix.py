@@ -114,3 +114,49 @@ def test_init_model_generator_range_and_mean():
     w = A.init_model(0, 4000, 0.1)
     assert w.dtype == np.float32 and np.abs(w).max() <= 0.1
     assert abs(w.mean()) < 0.01 and abs(w.std() - 0.1 / np.sqrt(3)) < 0.005
+
+
+# ---- consensus distance -------------------------------------------------------------------------
+
+def test_consensus_distance_is_the_plain_definition():
+    # brute force on a tiny case, element by element in Python floats
+    x = np.array([[1.0, 2.0, -1.0], [3.0, 2.0, 0.5], [5.0, -4.0, 0.0]], dtype=np.float32)
+    tot = 0.0
+    for e in range(3):
+        mean = sum(float(x[i, e]) for i in range(3)) / 3.0
+        tot += sum((float(x[i, e]) - mean) ** 2 for i in range(3))
+    assert abs(A.consensus_distance(x) - tot) < 1e-12
+    assert A.consensus_distance(np.ones((4, 7), np.float32) * 3.25) == 0.0          # consensus reached
+    # shifting every learner by the same vector changes nothing; scaling by c scales by c^2
+    r = np.random.default_rng(0)
+    y = r.standard_normal((5, 11))
+    assert abs(A.consensus_distance(y + r.standard_normal(11)) - A.consensus_distance(y)) < 1e-12
+    assert abs(A.consensus_distance(3.0 * y) - 9.0 * A.consensus_distance(y)) < 1e-10
+
+
+@pytest.mark.parametrize("L", [4, 5, 9, 16])
+def test_ring_mixing_contracts_the_consensus_distance_by_the_spectral_bound(L):
+    # Section II (Eq. 5-7) with the fixed-ring operator of Eq. 9: without gradients every application of
+    # T^f shrinks sum_i ||x_i - xbar||^2 by at least lambda_hat^2, lambda_hat the second largest eigenvalue
+    # magnitude of T^f, whose spectrum Eq. 10 gives in closed form: (1 + 2 cos(2 pi j / L)) / 3.
+    lam = sorted(abs((1.0 + 2.0 * np.cos(2.0 * np.pi * j / L)) / 3.0) for j in range(L))
+    lam_hat = lam[-2]
+    ora = A.Oracle(L, S.FIXED_RING, 3, flat_params=400, mix=S.MIX_TRI,
+                   x0=np.random.default_rng(L).uniform(-1, 1, (L, 400)).astype(np.float32))
+    zero = np.zeros((L, 400), np.float32)
+    prev = ora.consensus()
+    xbar0 = ora.average()
+    for k in range(6):
+        ora.step(None, 0.0, grads=zero)
+        cur = ora.consensus()
+        assert cur <= lam_hat ** 2 * prev * (1 + 1e-5) + 1e-9, (k, cur, prev)
+        prev = cur
+    assert np.abs(ora.average() - xbar0).max() < 1e-6             # doubly stochastic: the mean stays
+
+
+def test_allreduce_mixing_has_zero_consensus_distance_after_one_step():
+    L = 6
+    ora = A.Oracle(L, S.D1D, 1, flat_params=100, tau=0, x0=np.random.default_rng(1).uniform(-1, 1, (L, 100)).astype(np.float32))
+    assert ora.consensus() > 1.0
+    ora.step(None, 0.0, grads=np.zeros((L, 100), np.float32))
+    assert ora.consensus() == 0.0
