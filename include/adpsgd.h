@@ -165,6 +165,13 @@ int64_t adpsgd_iteration(adpsgd_t h);
  * learner order).  Asynchronous.                                               */
 int adpsgd_average(adpsgd_t h, float* dev_out);
 
+/* Consensus distance of the current models, sum_i ||x_i - xbar||^2 with xbar the
+ * learner average: the quantity the mixing operators contract by their second
+ * largest eigenvalue magnitude (Section II, Eq. 5-7).  Means, differences and sums
+ * in fp64, fixed summation order.  Waits for the stream; host_out[0] receives the
+ * value.                                                                        */
+int adpsgd_consensus(adpsgd_t h, double* host_out);
+
 /* Per-phase GPU time of a step, taken with HIP events recorded on the handle's
  * stream at every change of phase (no host synchronisation inside the step).
  * Phases: 0 minibatch staging + bf16 weight copy, 1 time-batched GEMMs,

@@ -58,6 +58,7 @@ _lib.adpsgd_schedule_of.argtypes = [C.c_int32, C.c_uint64, C.c_float, C.c_int32,
 _lib.adpsgd_iteration.argtypes = [_vp]
 _lib.adpsgd_iteration.restype = _i64
 _lib.adpsgd_average.argtypes = [_vp, _vp]
+_lib.adpsgd_consensus.argtypes = [_vp, C.POINTER(C.c_double)]
 _lib.adpsgd_set_profiling.argtypes = [_vp, C.c_int]
 _lib.adpsgd_profile.argtypes = [_vp, C.POINTER(C.c_float), _i32p, C.POINTER(C.c_double), C.POINTER(C.c_double)]
 _lib.adpsgd_destroy.argtypes = [_vp]
@@ -70,7 +71,7 @@ EXPORTS = ["adpsgd_workspace_bytes", "adpsgd_create", "adpsgd_step", "adpsgd_par
            "adpsgd_grads", "adpsgd_losses", "adpsgd_param_count", "adpsgd_layout_count", "adpsgd_layout",
            "adpsgd_schedule", "adpsgd_schedule_of", "adpsgd_iteration", "adpsgd_average", "adpsgd_destroy",
            "adpsgd_last_error", "adpsgd_gemm", "adpsgd_set_profiling", "adpsgd_profile",
-           "adpsgd_gemm_set_variant"]
+           "adpsgd_gemm_set_variant", "adpsgd_consensus"]
 PHASES = ["stage_cast", "batched_gemm", "recurrent_fwd", "recurrent_bwd", "softmax_ce", "bias_colsum", "mix_update"]
 
 
@@ -164,6 +165,12 @@ def adpsgd_average(h, dev_out_ptr):
     _check(_lib.adpsgd_average(h, dev_out_ptr))
 
 
+def adpsgd_consensus(h):
+    out = C.c_double(0.0)
+    _check(_lib.adpsgd_consensus(h, C.byref(out)))
+    return out.value
+
+
 def adpsgd_set_profiling(h, enable):
     _check(_lib.adpsgd_set_profiling(h, int(enable)))
 
@@ -240,6 +247,9 @@ class Adpsgd:
         out = self.torch.empty(self.P, dtype=self.torch.float32, device=self.device)
         adpsgd_average(self.h, out.data_ptr())
         return out
+
+    def consensus(self):
+        return adpsgd_consensus(self.h)
 
     def close(self):
         if self.h is not None:

@@ -106,6 +106,7 @@ struct adpsgd_handle {
     int ix_wp, ix_bp, ix_wo, ix_bo;
     // workspace regions
     float* params[2];
+    double* consensus;  // scratch of adpsgd_consensus
     float* grads;
     float* dbp;        // [L][T * batch tiles][D*4H]: per-frame column sums of da (partial bias gradients)
     bf16_t* wx0p;      // [L][D*4H][ldx] bf16: W_x of layer 0 with zero-padded rows, or NULL
@@ -191,6 +192,7 @@ size_t plan(adpsgd_handle* h, void* base) {
     const size_t L = (size_t)h->L;
     h->params[0] = (float*)w.take(L * h->Ppad * 4);
     h->params[1] = h->tau == 1 ? (float*)w.take(L * h->Ppad * 4) : h->params[0];
+    h->consensus = (double*)w.take((size_t)(kConsensusBlocks + 1) * 8);     // partial sums + the result
     if (!h->flat) {
         const size_t M = (size_t)h->M, DH = (size_t)h->D * h->H, G4 = DH * 4, e = (size_t)h->esz;
         h->grads = (float*)w.take(L * h->Ppad * 4);
@@ -609,6 +611,15 @@ int64_t adpsgd_iteration(adpsgd_t h) { return h ? h->k : -1; }
 int adpsgd_average(adpsgd_t h, float* dev_out) {
     if (!h || !dev_out) return fail(ADPSGD_EINVAL, "NULL argument");
     HIPCHK(launch_average(h->params[h->cur], h->Ppad, h->L, h->P, dev_out, h->stream), "average");
+    return ADPSGD_OK;
+}
+
+int adpsgd_consensus(adpsgd_t h, double* host_out) {
+    if (!h || !host_out) return fail(ADPSGD_EINVAL, "NULL argument");
+    HIPCHK(launch_consensus(h->params[h->cur], h->Ppad, h->L, h->P, h->consensus, h->consensus + kConsensusBlocks, h->stream),
+           "consensus distance");
+    HIPCHK(hipMemcpyAsync(host_out, h->consensus + kConsensusBlocks, 8, hipMemcpyDeviceToHost, h->stream), "consensus copy");
+    HIPCHK(hipStreamSynchronize(h->stream), "stream sync");
     return ADPSGD_OK;
 }
 

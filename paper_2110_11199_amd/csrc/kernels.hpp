@@ -41,6 +41,9 @@ struct UpdateDesc {
 };
 hipError_t launch_update(const UpdateDesc& d, hipStream_t s);
 hipError_t launch_average(const float* x, int64_t stride, int L, int64_t P, float* out, hipStream_t s);
+// out[0] = sum_i sum_e (x_i[e] - mean_i x_i[e])^2 in fp64; partial: kConsensusBlocks doubles of scratch
+constexpr int kConsensusBlocks = 2048;
+hipError_t launch_consensus(const float* x, int64_t stride, int L, int64_t P, double* partial, double* out, hipStream_t s);
 
 // ---- LSTM gradient pieces -------------------------------------------------------
 struct StageDesc {             // copy / cast the minibatches into the workspace

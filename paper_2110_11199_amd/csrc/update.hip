@@ -323,6 +323,48 @@ hipError_t launch_update(const UpdateDesc& d, hipStream_t s) {
     return hipGetLastError();
 }
 
+// Consensus distance: every thread walks element indices with the grid stride and accumulates, in fp64,
+// the squared deviations of the L models from their mean at that index; block sums through LDS, then one
+// block adds the per-block partial sums in index order (a fixed order: the result is reproducible).
+__global__ __launch_bounds__(256) void consensus_partial_kernel(const float* x, int64_t stride, int L, int64_t P, double* partial) {
+    double acc = 0.0;
+    for (int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x; e < P; e += (int64_t)gridDim.x * 256) {
+        double s = 0.0;
+        for (int j = 0; j < L; ++j) s += (double)x[j * stride + e];
+        const double mean = s / (double)L;
+        for (int j = 0; j < L; ++j) { const double d = (double)x[j * stride + e] - mean; acc += d * d; }
+    }
+    __shared__ double sh[256];
+    sh[threadIdx.x] = acc;
+    __syncthreads();
+    for (int off = 128; off > 0; off >>= 1) {
+        if ((int)threadIdx.x < off) sh[threadIdx.x] += sh[threadIdx.x + off];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) partial[blockIdx.x] = sh[0];
+}
+__global__ __launch_bounds__(256) void consensus_final_kernel(const double* partial, int n, double* out) {
+    __shared__ double sh[256];
+    double acc = 0.0;
+    for (int i = threadIdx.x; i < n; i += 256) acc += partial[i];
+    sh[threadIdx.x] = acc;
+    __syncthreads();
+    for (int off = 128; off > 0; off >>= 1) {
+        if ((int)threadIdx.x < off) sh[threadIdx.x] += sh[threadIdx.x + off];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) out[0] = sh[0];
+}
+
+hipError_t launch_consensus(const float* x, int64_t stride, int L, int64_t P, double* partial, double* out, hipStream_t s) {
+    if (L < 1 || P < 1) return hipErrorInvalidValue;
+    int64_t blocks = (P + 255) / 256;
+    if (blocks > kConsensusBlocks) blocks = kConsensusBlocks;
+    hipLaunchKernelGGL(consensus_partial_kernel, dim3((unsigned)blocks), dim3(256), 0, s, x, stride, L, P, partial);
+    hipLaunchKernelGGL(consensus_final_kernel, dim3(1), dim3(256), 0, s, partial, (int)blocks, out);
+    return hipGetLastError();
+}
+
 hipError_t launch_average(const float* x, int64_t stride, int L, int64_t P, float* out, hipStream_t s) {
     hipLaunchKernelGGL(average_kernel, dim3((unsigned)((P + 255) / 256)), dim3(256), 0, s, x, stride, L, P,
                        1.0f / (float)L, out);

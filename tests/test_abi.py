@@ -46,9 +46,10 @@ def test_config_validation_and_workspace_size():
     n = Bd.adpsgd_workspace_bytes(ok)
     assert n > 4 * 33380 * 4 * 2 and n % 256 == 0
     flat = Bd.make_config(64, Bd.RANDOM_RING, flat_params=135_000_000, straggler_p=0.1)
-    assert Bd.adpsgd_workspace_bytes(flat) == 64 * 135_000_000 * 4
+    scratch = 16640                     # 2049 doubles of the consensus-distance reduction, rounded to 256 bytes
+    assert Bd.adpsgd_workspace_bytes(flat) == 64 * 135_000_000 * 4 + scratch
     d1d = Bd.make_config(64, Bd.D1D, flat_params=1000)
-    assert Bd.adpsgd_workspace_bytes(d1d) == 2 * 64 * 1024 * 4          # two model buffers, padded stride
+    assert Bd.adpsgd_workspace_bytes(d1d) == 2 * 64 * 1024 * 4 + scratch     # two model buffers, padded stride
     bad = [Bd.make_config(0, 0, flat_params=8), Bd.make_config(129, 0, flat_params=8),
            Bd.make_config(4, 3, flat_params=8), Bd.make_config(4, Bd.D1D, flat_params=8, straggler_p=0.1),
            Bd.make_config(4, 0, flat_params=8, tau=1, straggler_p=0.1),

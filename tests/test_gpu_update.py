@@ -71,6 +71,27 @@ def test_ring_neighbour_thirds_rejects_stragglers():
     assert ei.value.code == Bd.EINVAL
 
 
+@pytest.mark.parametrize("L,P", [(1, 5), (3, 1001), (16, 70001), (64, 300000)])
+def test_consensus_distance_and_its_contraction(L, P):
+    import torch
+    from paper_2110_11199_amd import binding as Bd
+    r = np.random.default_rng(L)
+    x0 = r.uniform(-1, 1, (L, P)).astype(np.float32)
+    eng = Bd.Adpsgd(Bd.make_config(L, S.FIXED_RING, flat_params=P, mix=Bd.MIX_TRI))
+    for i in range(L):
+        eng.set_params(i, torch.from_numpy(x0[i]).cuda())
+    ora = A.Oracle(L, S.FIXED_RING, 0, flat_params=P, x0=x0, mix=S.MIX_TRI)
+    zero = np.zeros((L, P), np.float32)
+    gz = [torch.zeros(P, device="cuda") for _ in range(L)]
+    for k in range(3):
+        ref = ora.consensus()
+        got = eng.consensus()
+        assert abs(got - ref) <= 1e-11 * max(ref, 1e-30), (k, got, ref)      # both fp64, different summation order
+        eng.step(gz, 0.0)
+        ora.step(None, 0.0, grads=zero)
+    eng.close()
+
+
 def test_delay_by_one_with_pairwise_mixing_and_ring_with_global_mean():
     _run(6, 5001, S.D1D, 4, mix=S.MIX_PAIR)
     _run(6, 5001, S.FIXED_RING, 3, mix=S.MIX_ALL, tau=0)
