@@ -2,16 +2,17 @@
 // (input projections, output layers, weight gradients, input gradients).
 //
 // Three tile configurations are built:
-//   0   128x128 workgroup tile, 4 waves (64x64 each), 64-byte K stages, operands staged
-//       through registers.  Small problems, fp32 operands, rows that are only 8-byte aligned.
-//   5   256x256 tile, 8 waves (128x64 each), 128-byte stages, staged through registers.
-//       Large bf16 problems with an operand that is not K-contiguous (dW = dA' X, dX = dA W):
-//       the transposition happens between the registers and LDS.
-//   10  256x256 tile, 8 waves, 128-byte stages, direct global->LDS loads (no staging
-//       registers, no LDS store instructions).  Large bf16 problems with both operands
-//       K-contiguous and K a multiple of 64.
-// A 256x256 tile needs half the operand bytes per flop of a 128x128 one; at these sizes the
-// main loop is bound by how fast a CU can pull operands through L2, not by MFMA issue.
+//   10  256x256 workgroup tile, 8 waves (128x64 each), 128-byte K stages, direct global->LDS loads
+//       (no staging registers, no LDS store instructions); an operand that is not K-contiguous
+//       (dW = dA' X, dX = dA W) is transposed on the LDS read.  All large bf16 problems with
+//       16-byte aligned rows and K a multiple of 64.
+//   5   the same tile staged through registers, the transposition done between the registers
+//       and LDS.  Large bf16 problems that miss the conditions of 10 (ragged K, 8-byte rows).
+//   0   128x128 tile, 4 waves (64x64 each), 64-byte stages, staged through registers.  Small
+//       problems and fp32 operands.
+// A 256x256 tile needs half the operand bytes per flop of a 128x128 one.  The main loop of
+// configuration 10 is bound inside the CU: per 64-k step it reads 192 KB of fragments from LDS
+// and receives 64 KB of direct loads, which takes as long as the step's 32 MFMAs per wave.
 #include <type_traits>
 #include "gemm_core.hpp"
 #include "gemm_dma.hpp"

@@ -2,10 +2,10 @@
 // no staging registers, no LDS store instructions, NS LDS stages in flight.
 //
 // Same contract as GemmCore (gemm_core.hpp): C[m][n] = sum_k A(m,k) B(n,k) for a
-// (32*FM*WM) x (32*FN*WN) workgroup tile, both operands K-contiguous in memory,
-// K a multiple of the stage length.  Rows past the end of an operand are clamped to
-// its last row (their products land in accumulator rows/columns the caller discards),
-// so no guard and no zero fill is needed.
+// (32*FM*WM) x (32*FN*WN) workgroup tile, K a multiple of the stage length, operand rows
+// 16-byte aligned.  Rows past the end of an operand are clamped to its last row (their
+// products land in accumulator rows/columns the caller discards), so no guard and no zero
+// fill is needed.
 //
 // A wave-wide direct load writes lane l's 16 bytes to LDS at base + 16*l, i.e. 1 KB
 // contiguous per instruction.  A tile is therefore stored row-major WITHOUT padding
