@@ -95,7 +95,8 @@ typedef struct {
     int32_t            precision;    /* adpsgd_precision                          */
     uint64_t           seed;         /* seed of the schedule (and of init_scale)  */
     float              straggler_p;  /* probability that a learner sits an
-                                        iteration out (0 = never); rings only     */
+                                        iteration out (0 = never); pairwise mixing
+                                        on the rings with tau = 0 only            */
     float              init_scale;   /* > 0: all learners start from the same
                                         w_0 ~ U(-a, a) (Algorithm 1, input);
                                         0: models start as zeros, set them with
