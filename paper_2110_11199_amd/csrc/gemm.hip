@@ -102,6 +102,59 @@ __device__ inline void store_tile(f32x16_t (&acc)[FM][FN], const GemmDesc& p, in
     }
 }
 
+// Stores whose address is a wave-uniform 64-bit pointer (SGPR pair) plus a per-lane 32-bit byte offset.
+// Written as inline asm because the compiler otherwise folds the uniform part into a 64-bit vector
+// address and recomputes it with vector multiply-adds for every store.
+__device__ inline void store_u_f32_(uint32_t off, float v, const void* base_uniform) {
+    asm volatile("global_store_dword %0, %1, %2" :: "v"(off), "v"(v), "s"(base_uniform) : "memory");
+}
+__device__ inline void store_u_f32_nt_(uint32_t off, float v, const void* base_uniform) {
+    asm volatile("global_store_dword %0, %1, %2 nt" :: "v"(off), "v"(v), "s"(base_uniform) : "memory");
+}
+__device__ inline void store_u_b16_(uint32_t off, uint32_t v, const void* base_uniform) {
+    asm volatile("global_store_short %0, %1, %2" :: "v"(off), "v"(v), "s"(base_uniform) : "memory");
+}
+
+// The same for a tile that lies wholly inside C (no row or column guard): every store is one
+// instruction whose address is a wave-uniform row pointer plus a per-lane byte offset that is the
+// same for all stores of the lane, so the epilogue costs no vector address arithmetic and no branches.
+// Needs (4 * ldc + 32) * 4 bytes to fit the 32-bit offset (checked by the caller).
+template <typename T, class Core, int FM, int FN>
+__device__ inline void store_tile_interior(f32x16_t (&acc)[FM][FN], const GemmDesc& p, int m0, int n0, int gi, int gd) {
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int wave_m = wave / Core::kWN, wave_n = wave % Core::kWN;
+    const uint32_t lane_elem = (uint32_t)(4 * (lane >> 5)) * (uint32_t)p.ldc + (uint32_t)(lane & 31);
+    const int64_t tile_off = gi * p.sCi + gd * p.sCd + (int64_t)(m0 + wave_m * FM * 32) * p.ldc + n0 + wave_n * FN * 32;
+    const float* bias = p.bias ? p.bias + gi * p.sBiasI + gd * p.sBiasD + n0 + wave_n * FN * 32 + (lane & 31) : nullptr;
+    const bool narrow = p.c_elem && sizeof(T) == 2;
+    const int esz = narrow ? 2 : 4;
+    const char* cbase = (const char*)p.C + tile_off * esz;
+    const uint32_t lane_off = lane_elem * (uint32_t)esz;
+    const int64_t row_bytes = (int64_t)p.ldc * esz;
+#pragma unroll
+    for (int fn = 0; fn < FN; ++fn) {
+        const float bv = bias ? bias[fn * 32] : 0.f;
+#pragma unroll
+        for (int fm = 0; fm < FM; ++fm) {
+            const char* fbase = cbase + (int64_t)(fm * 32) * row_bytes + fn * 32 * esz;
+            if (narrow) {
+#pragma unroll
+                for (int i = 0; i < 16; ++i)
+                    store_u_b16_(lane_off, f32_to_bf16(acc[fm][fn][i] + bv), fbase + (8 * (i >> 2) + (i & 3)) * row_bytes);
+            } else if (p.c_elem) {
+#pragma unroll
+                for (int i = 0; i < 16; ++i)
+                    store_u_f32_(lane_off, acc[fm][fn][i] + bv, fbase + (8 * (i >> 2) + (i & 3)) * row_bytes);
+            } else {
+#pragma unroll
+                for (int i = 0; i < 16; ++i)   // written once, read by a later kernel: keep it out of L2
+                    store_u_f32_nt_(lane_off, acc[fm][fn][i] + bv, fbase + (8 * (i >> 2) + (i & 3)) * row_bytes);
+            }
+        }
+    }
+}
+
 template <int FM, int FN> __device__ inline void zero_tile(f32x16_t (&acc)[FM][FN]) {
 #pragma unroll
     for (int i = 0; i < FM; ++i)
@@ -165,7 +218,8 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_dma_kernel(GemmDesc p) {
     f32x16_t acc[FM][FN];
     zero_tile<FM, FN>(acc);
     Core::run(acc, a, b, p.K, lds);
-    store_tile<T, Core, FM, FN>(acc, p, m0, n0, gi, gd);
+    if (m0 + Core::BM <= p.M && n0 + Core::BN <= p.N && p.ldc < (1 << 26)) store_tile_interior<T, Core, FM, FN>(acc, p, m0, n0, gi, gd);
+    else store_tile<T, Core, FM, FN>(acc, p, m0, n0, gi, gd);
 }
 
 template <typename T, bool AKC, bool BKC, int WM, int WN, int FM, int FN, int VB, int SB>
