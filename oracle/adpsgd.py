@@ -16,6 +16,13 @@ multiply-add):
   TRI   m = ((x_left + x_i) + x_right) * (1/3)
   ALL   m = (((x_0 + x_1) + x_2) + ...) * (1/L)
   x_i^{k+1} = m - (lr * g_i)
+
+The synchronous baseline (SDPSGD: Section III-A, Algorithm 2) applies the same
+operations in the other order, W_{k+1} = (W_k - a_k g(W_k, xi_k)) T with
+T = 11'/L: every learner updates its own model, then all models are averaged,
+  u_j = x_j - (lr * g_j)
+  x_i^{k+1} = (((u_0 + u_1) + u_2) + ...) * (1/L)      for every i,
+so all learners hold the same model after every iteration.
 """
 import numpy as np
 from . import schedule as S
@@ -30,13 +37,24 @@ def init_model(seed, P, scale):
     return out
 
 
-def mix_update(x, g, mix, order, partner, active, lr):
+def mix_update(x, g, mix, order, partner, active, lr, update_first=False):
     """One application of step 3 to x [L][P] float32 with g [L][P] float32.
-    Returns the new [L][P] array; x is not modified."""
+    Returns the new [L][P] array; x is not modified.
+    update_first: the synchronous baseline's order (local update, then the
+    average of all learners); defined for the all-learner mean with nobody
+    inactive."""
     x = np.asarray(x, dtype=np.float32)
     L = x.shape[0]
     lr = np.float32(lr)
     out = np.empty_like(x)
+    if update_first:
+        if mix != S.MIX_ALL or not all(active):
+            raise ValueError("update-then-average is the all-learner mean over every learner")
+        s = x[0] - (lr * np.asarray(g[0], dtype=np.float32))
+        for j in range(1, L):
+            s = s + (x[j] - (lr * np.asarray(g[j], dtype=np.float32)))
+        out[:] = s * (np.float32(1.0) / np.float32(L))
+        return out
     if mix == S.MIX_ALL:
         s = x[0].copy()
         for j in range(1, L):
@@ -78,8 +96,11 @@ class Oracle:
         self.L, self.pattern, self.seed = L, pattern, seed
         self.shape = shape
         self.P = lstm.param_count(shape) if shape is not None else int(flat_params)
-        self.mix = mix if mix is not None else (S.MIX_ALL if pattern == S.D1D else S.MIX_PAIR)
+        self.mix = mix if mix is not None else (S.MIX_ALL if pattern in (S.D1D, S.SDPSGD) else S.MIX_PAIR)
         self.tau = tau if tau is not None else (1 if pattern == S.D1D else 0)
+        self.update_first = pattern == S.SDPSGD
+        if self.update_first and (self.mix != S.MIX_ALL or self.tau != 0 or straggler_p > 0.0):
+            raise ValueError("the synchronous baseline averages all learners, without staleness or stragglers")
         self.straggler_p = straggler_p
         self.bf16_gemm = bf16_gemm
         if x0 is not None:
@@ -111,7 +132,7 @@ class Oracle:
                                                              np.float32, self.bf16_gemm)
             self.last_losses = losses
         self.last_grads = grads
-        new = mix_update(self.x, grads, self.mix, order, partner, active, lr)
+        new = mix_update(self.x, grads, self.mix, order, partner, active, lr, self.update_first)
         self.x_prev = self.x
         self.x = new
         self.k += 1

@@ -5,7 +5,10 @@ What the paper fixes
   * fixed mixing uses the learners' ring order as is (Section III-B);
   * random mixing draws a fresh permutation of the ring each iteration with a
     Fisher-Yates shuffle (Section III-C);
-  * delay-by-one mixes with T = 11'/L (Section III-D).
+  * delay-by-one mixes with T = 11'/L (Section III-D);
+  * the synchronous baseline (SDPSGD, Section III-A, Algorithm 2) uses the same
+    T = 11'/L, applied after every learner's local update; it has no ring order
+    to choose and waits for every learner.
 
 What it leaves open, and the reading taken here
   * the random source: a stateless counter-based 64-bit generator,
@@ -26,7 +29,7 @@ STREAM_PERM = 1   # Fisher-Yates draws
 STREAM_MASK = 2   # straggler mask draws
 STREAM_INIT = 3   # initial model draws
 
-FIXED_RING, RANDOM_RING, D1D = 0, 1, 2
+FIXED_RING, RANDOM_RING, D1D, SDPSGD = 0, 1, 2, 3
 MIX_PAIR, MIX_TRI, MIX_ALL = 0, 1, 2
 
 
