@@ -30,10 +30,12 @@ PEAK_TFLOPS = {"bf16": 2500.0, "f32": 157.3}
 PEAK_HBM_GBS = 8000.0
 
 
-def _config(Bd, wl, seed, tri=False):
+def _config(Bd, wl, seed, variant=None):
     if wl.flat_params:
-        if tri:     # the paper's ring-neighbour operator (weights 1/3); defined without stragglers
+        if variant == "tri":     # the paper's ring-neighbour operator (weights 1/3); defined without stragglers
             return Bd.make_config(wl.L, wl.pattern, seed=seed, flat_params=wl.flat_params, mix=Bd.MIX_TRI)
+        if variant == "sync":    # the synchronous baseline: update, then the mean of all learners
+            return Bd.make_config(wl.L, Bd.SDPSGD, seed=seed, flat_params=wl.flat_params)
         return Bd.make_config(wl.L, wl.pattern, seed=seed, flat_params=wl.flat_params, straggler_p=wl.straggler_p)
     return Bd.make_config(wl.L, wl.pattern, seed=seed, input_dim=wl.input_dim, hidden=wl.hidden, layers=wl.layers,
                           bidirectional=wl.bidirectional, bottleneck=wl.bottleneck, classes=wl.classes,
@@ -68,10 +70,10 @@ def run_model(wl, steps, warmup, seed=0):
     return dt, prof, float(losses.mean())
 
 
-def run_flat(wl, steps, warmup, seed=0, tri=False):
+def run_flat(wl, steps, warmup, seed=0, variant=None):
     import torch
     from paper_2110_11199_amd import binding as Bd
-    eng = Bd.Adpsgd(_config(Bd, wl, seed, tri))
+    eng = Bd.Adpsgd(_config(Bd, wl, seed, variant))
     gen = torch.Generator(device="cuda")
     gen.manual_seed(seed)
     grads = []
@@ -144,6 +146,7 @@ def main():
     ap.add_argument("--mix-steps", type=int, default=20, help="timed steps of the cfg5 mixing/update leg (0 = skip)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--tri", action="store_true", help="also time the ring-neighbour (weights 1/3) mixing kernel on the cfg5 shape")
+    ap.add_argument("--sync", action="store_true", help="also time the synchronous baseline's update-then-mean kernel on the cfg5 shape")
     ap.add_argument("--tune", type=int, default=None, help="forwarded to adpsgd_gemm_set_variant (tuning only)")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -216,11 +219,17 @@ def main():
             out["mix_update"] = r5
             out["mix_update_GBps"] = r5["achieved"]
             if args.tri:
-                dt6, prof6, active6 = run_flat(w5, args.mix_steps, 2, tri=True)
+                dt6, prof6, active6 = run_flat(w5, args.mix_steps, 2, variant="tri")
                 r6 = hbm_roofline(prof6, ["mix_update"], "tri_update_kernel", "cfg5")
                 r6.update({"workload": "cfg5 with ring-neighbour mixing (weights 1/3), no stragglers", "steps": args.mix_steps,
                            "ms_per_step": dt6 / args.mix_steps * 1e3, "learner_steps_per_s": active6 / dt6})
                 out["mix_update_tri"] = r6
+            if args.sync:
+                dt7, prof7, active7 = run_flat(w5, args.mix_steps, 2, variant="sync")
+                r7 = hbm_roofline(prof7, ["mix_update"], "sync_update_kernel", "cfg5")
+                r7.update({"workload": "cfg5 as the synchronous baseline (update, then the mean of all 64 learners), no stragglers",
+                           "steps": args.mix_steps, "ms_per_step": dt7 / args.mix_steps * 1e3, "learner_steps_per_s": active7 / dt7})
+                out["mix_update_sync"] = r7
         if not args.no_cpu_baseline:
             out["cpu_baseline"] = cpu_baseline(wl)
     print(json.dumps(out))

@@ -55,8 +55,12 @@ extern "C" {
 
 typedef struct adpsgd_handle* adpsgd_t;   /* opaque; owned by the library (host memory) */
 
-/* Communication pattern (Section III-B / III-C / III-D). */
-typedef enum { ADPSGD_FIXED_RING = 0, ADPSGD_RANDOM_RING = 1, ADPSGD_D1D = 2 } adpsgd_pattern;
+/* Communication pattern (Section III-B / III-C / III-D), or the synchronous baseline
+ * SDPSGD of Section III-A (Algorithm 2): every learner updates its own model,
+ * u_j = x_j - lr * g_j, then all models are replaced by their mean
+ * (((u_0 + u_1) + ...) * fl(1/L)), W_{k+1} = (W_k - a_k g(W_k)) 11'/L.  SDPSGD fixes
+ * mix = ALL and tau = 0 and takes no stragglers.                                */
+typedef enum { ADPSGD_FIXED_RING = 0, ADPSGD_RANDOM_RING = 1, ADPSGD_D1D = 2, ADPSGD_SDPSGD = 3 } adpsgd_pattern;
 /* Mixing operator applied along that pattern.
  *   PAIR  (x_i + x_j)/2 with the partner j of a perfect matching on the ring order
  *   TRI   (x_left + x_i + x_right)/3 with the two neighbours on the ring order: the
@@ -64,7 +68,7 @@ typedef enum { ADPSGD_FIXED_RING = 0, ADPSGD_RANDOM_RING = 1, ADPSGD_D1D = 2 } a
  *         permuted form T^r = P' T^f P on the random ring (Section III-C); summed as
  *         (x_left + x_i) + x_right in that order, then times fl(1/3)
  *   ALL   the global mean, T = 11'/L (allreduce, Section III-A / III-D)
- *   DEFAULT = PAIR for the rings, ALL for delay-by-one.                         */
+ *   DEFAULT = PAIR for the rings, ALL for delay-by-one and the synchronous baseline. */
 typedef enum { ADPSGD_MIX_DEFAULT = -1, ADPSGD_MIX_PAIR = 0, ADPSGD_MIX_TRI = 1, ADPSGD_MIX_ALL = 2 } adpsgd_mix;
 /* Arithmetic of the GEMMs: fp32 operands, or bf16 operands (rounded to nearest
  * even from the fp32 master) with fp32 accumulation.  State, gates, softmax

@@ -21,7 +21,7 @@ if not os.path.exists(LIB_PATH):
 _lib = C.CDLL(LIB_PATH)
 
 OK, EINVAL, ENOMEM, EHIP = 0, -1, -2, -3
-FIXED_RING, RANDOM_RING, D1D = 0, 1, 2
+FIXED_RING, RANDOM_RING, D1D, SDPSGD = 0, 1, 2, 3
 MIX_DEFAULT, MIX_PAIR, MIX_TRI, MIX_ALL = -1, 0, 1, 2
 FP32, BF16_GEMM = 0, 1
 MAX_LEARNERS = 128

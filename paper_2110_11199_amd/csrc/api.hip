@@ -121,16 +121,22 @@ struct adpsgd_handle {
 
 namespace {
 
+bool all_by_default(int pattern) { return pattern == ADPSGD_D1D || pattern == ADPSGD_SDPSGD; }
+
 int check_config(const adpsgd_config* c, std::string& why) {
     if (!c) { why = "config is NULL"; return ADPSGD_EINVAL; }
     if (c->L < 1 || c->L > ADPSGD_MAX_LEARNERS) { why = "L must be in 1..128"; return ADPSGD_EINVAL; }
-    if (c->pattern < 0 || c->pattern > 2) { why = "unknown pattern"; return ADPSGD_EINVAL; }
+    if (c->pattern < 0 || c->pattern > 3) { why = "unknown pattern"; return ADPSGD_EINVAL; }
     if (c->mix != ADPSGD_MIX_DEFAULT && c->mix != ADPSGD_MIX_PAIR && c->mix != ADPSGD_MIX_TRI && c->mix != ADPSGD_MIX_ALL) { why = "unknown mix"; return ADPSGD_EINVAL; }
     if (c->tau < -1 || c->tau > 1) { why = "tau must be 0, 1 or -1"; return ADPSGD_EINVAL; }
     if (c->precision != ADPSGD_FP32 && c->precision != ADPSGD_BF16_GEMM) { why = "unknown precision"; return ADPSGD_EINVAL; }
     if (!(c->straggler_p >= 0.f && c->straggler_p < 1.f)) { why = "straggler_p must be in [0,1)"; return ADPSGD_EINVAL; }
     const int tau = c->tau >= 0 ? c->tau : (c->pattern == ADPSGD_D1D ? 1 : 0);
-    const int mix = c->mix != ADPSGD_MIX_DEFAULT ? c->mix : (c->pattern == ADPSGD_D1D ? ADPSGD_MIX_ALL : ADPSGD_MIX_PAIR);
+    const int mix = c->mix != ADPSGD_MIX_DEFAULT ? c->mix : (all_by_default(c->pattern) ? ADPSGD_MIX_ALL : ADPSGD_MIX_PAIR);
+    if (c->pattern == ADPSGD_SDPSGD && (mix != ADPSGD_MIX_ALL || tau != 0 || c->straggler_p > 0.f)) {
+        why = "the synchronous baseline averages all learners (mix ALL), with tau = 0 and no stragglers";
+        return ADPSGD_EINVAL;
+    }
     if (c->straggler_p > 0.f && (c->pattern == ADPSGD_D1D || tau != 0 || mix != ADPSGD_MIX_PAIR)) {
         why = "stragglers need a ring pattern with pairwise mixing and tau = 0 (delay-by-one waits for every learner)";
         return ADPSGD_EINVAL;
@@ -155,7 +161,7 @@ size_t plan(adpsgd_handle* h, void* base) {
     const adpsgd_model_shape& s = c.shape;
     h->L = c.L;
     h->tau = c.tau >= 0 ? c.tau : (c.pattern == ADPSGD_D1D ? 1 : 0);
-    h->mix = c.mix != ADPSGD_MIX_DEFAULT ? c.mix : (c.pattern == ADPSGD_D1D ? ADPSGD_MIX_ALL : ADPSGD_MIX_PAIR);
+    h->mix = c.mix != ADPSGD_MIX_DEFAULT ? c.mix : (all_by_default(c.pattern) ? ADPSGD_MIX_ALL : ADPSGD_MIX_PAIR);
     h->prec = c.precision; h->esz = c.precision ? 2 : 4;
     h->flat = s.flat_params > 0;
     h->tensors.clear(); h->ix_wx.clear(); h->ix_wh.clear(); h->ix_b.clear();
@@ -525,6 +531,7 @@ int adpsgd_step(adpsgd_t h, const void* const* batch_ptrs, float lr) {
     float* xnext = h->tau == 1 ? h->params[1 - h->cur] : xk;
     UpdateDesc u{};
     u.L = L; u.mix = h->mix; u.P = h->P; u.src = xk; u.dst = xnext; u.stride = h->Ppad; u.lr = lr;
+    u.update_first = h->cfg.pattern == ADPSGD_SDPSGD;
     if (h->flat) {
         for (int i = 0; i < L; ++i) u.g[i] = (const float*)batch_ptrs[i];
     } else {
@@ -592,7 +599,7 @@ int adpsgd_layout(adpsgd_t h, int idx, int64_t* offset, int64_t* rows, int64_t* 
 
 int adpsgd_schedule_of(int32_t pattern, uint64_t seed, float straggler_p, int32_t L, int64_t k,
                        int32_t* order, int32_t* partner, int32_t* active) {
-    if (L < 1 || L > ADPSGD_MAX_LEARNERS || pattern < 0 || pattern > 2 || k < 0) return fail(ADPSGD_EINVAL, "bad argument");
+    if (L < 1 || L > ADPSGD_MAX_LEARNERS || pattern < 0 || pattern > 3 || k < 0) return fail(ADPSGD_EINVAL, "bad argument");
     int32_t o[ADPSGD_MAX_LEARNERS], p[ADPSGD_MAX_LEARNERS], a[ADPSGD_MAX_LEARNERS];
     make_schedule(pattern, seed, straggler_p, L, k, o, p, a);
     if (order) memcpy(order, o, (size_t)L * 4);

@@ -9,6 +9,8 @@
 //     pair: m = (x_i + x_j) * 0.5      all: m = (((x_0 + x_1) + ...) ) * (1/L)
 //     ring neighbours: m = ((x_left + x_i) + x_right) * (1/3)
 //     x_i <- m - (lr * g_i)
+// Synchronous baseline (Section III-A, Algorithm 2), the same operations in the other order:
+//     u_j = x_j - (lr * g_j);   x_i <- (((u_0 + u_1) + ...)) * (1/L) for every i
 #include "kernels.hpp"
 
 namespace adpsgd {
@@ -145,6 +147,45 @@ struct AllArgs {
     const float* g[128];
 };
 
+// synchronous baseline: one element of all learners
+__device__ inline void sync_scalar_(const AllArgs& p, int64_t t) {
+    float s = sgd_(p.src[t], p.lr, p.g[0][t]);
+    for (int j = 1; j < p.L; ++j) s = __fadd_rn(s, sgd_(p.src[j * p.stride + t], p.lr, p.g[j][t]));
+    const float m = __fmul_rn(s, p.inv_L);
+    for (int i = 0; i < p.L; ++i) {
+        p.dst[i * p.stride + t] = m;
+        if (p.shadow) p.shadow[i * p.stride + t] = f32_to_bf16(m);
+    }
+}
+
+// Synchronous baseline: one thread owns an element index of all learners, reads L models and L
+// gradients, and writes the mean of the updated models to all L learners (12 bytes per learner and
+// element, as the other updates).  The bf16 copy, if any, is of the output (tau = 0).
+template <bool VEC>
+__global__ __launch_bounds__(256) void sync_update_kernel(AllArgs p) {
+    const int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if constexpr (VEC) {
+        const int64_t n4 = p.P >> 2;
+        if (e < n4) {
+            float4 s = pair_new_(ldnt_(p.src, e), p.lr, ldnt_(p.g[0], e));
+#pragma unroll 8
+            for (int j = 1; j < p.L; ++j) {
+                const float4 u = pair_new_(ldnt_(p.src + j * p.stride, e), p.lr, ldnt_(p.g[j], e));
+                s.x = __fadd_rn(s.x, u.x); s.y = __fadd_rn(s.y, u.y); s.z = __fadd_rn(s.z, u.z); s.w = __fadd_rn(s.w, u.w);
+            }
+            const float4 m = make_float4(__fmul_rn(s.x, p.inv_L), __fmul_rn(s.y, p.inv_L), __fmul_rn(s.z, p.inv_L), __fmul_rn(s.w, p.inv_L));
+#pragma unroll 8
+            for (int i = 0; i < p.L; ++i) {
+                stnt_(p.dst + i * p.stride, e, m);
+                if (p.shadow) emit4_(p.shadow + i * p.stride, e, m);
+            }
+        }
+        if (blockIdx.x == 0 && threadIdx.x < (p.P & 3)) sync_scalar_(p, (n4 << 2) + threadIdx.x);
+    } else {
+        if (e < p.P) sync_scalar_(p, e);
+    }
+}
+
 __device__ inline void all_scalar_(const AllArgs& p, int64_t t) {
     float s = p.src[t];
     if (p.shadow && p.emit_input) p.shadow[t] = f32_to_bf16(s);
@@ -263,18 +304,27 @@ hipError_t launch_update(const UpdateDesc& d, hipStream_t s) {
     bool vec = ((uintptr_t)d.src % 16 == 0) && ((uintptr_t)d.dst % 16 == 0) && (d.stride % 4 == 0);
     for (int i = 0; i < d.L; ++i)
         if ((uintptr_t)d.g[i] % 16 != 0) vec = false;
+    if (d.update_first && d.mix != 2) return hipErrorInvalidValue;
     if (d.mix == 2) {
         AllArgs a;
         a.src = d.src; a.dst = d.dst; a.stride = d.stride; a.P = d.P; a.lr = d.lr; a.L = d.L;
         a.inv_L = 1.0f / (float)d.L;
         a.shadow = d.shadow; a.emit_input = d.emit_input;
         for (int i = 0; i < 128; ++i) a.g[i] = i < d.L ? d.g[i] : nullptr;
+        if (d.update_first) {
+            for (int i = 0; i < d.L; ++i)
+                if (!d.active[i]) return hipErrorInvalidValue;     // the baseline waits for every learner
+            if (d.emit_input) return hipErrorInvalidValue;         // and has no staleness
+        }
         if (vec) {
             const int64_t n4 = d.P >> 2;
             const unsigned blocks = (unsigned)((n4 > 0 ? n4 : 1) + 255) / 256;
-            hipLaunchKernelGGL(all_update_kernel<true>, dim3(blocks), dim3(256), 0, s, a);
+            if (d.update_first) hipLaunchKernelGGL(sync_update_kernel<true>, dim3(blocks), dim3(256), 0, s, a);
+            else hipLaunchKernelGGL(all_update_kernel<true>, dim3(blocks), dim3(256), 0, s, a);
         } else {
-            hipLaunchKernelGGL(all_update_kernel<false>, dim3((unsigned)((d.P + 255) / 256)), dim3(256), 0, s, a);
+            const unsigned blocks = (unsigned)((d.P + 255) / 256);
+            if (d.update_first) hipLaunchKernelGGL(sync_update_kernel<false>, dim3(blocks), dim3(256), 0, s, a);
+            else hipLaunchKernelGGL(all_update_kernel<false>, dim3(blocks), dim3(256), 0, s, a);
         }
         return hipGetLastError();
     }

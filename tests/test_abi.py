@@ -51,13 +51,18 @@ def test_config_validation_and_workspace_size():
     d1d = Bd.make_config(64, Bd.D1D, flat_params=1000)
     assert Bd.adpsgd_workspace_bytes(d1d) == 2 * 64 * 1024 * 4 + scratch     # two model buffers, padded stride
     bad = [Bd.make_config(0, 0, flat_params=8), Bd.make_config(129, 0, flat_params=8),
-           Bd.make_config(4, 3, flat_params=8), Bd.make_config(4, Bd.D1D, flat_params=8, straggler_p=0.1),
+           Bd.make_config(4, 4, flat_params=8), Bd.make_config(4, Bd.D1D, flat_params=8, straggler_p=0.1),
+           Bd.make_config(4, Bd.SDPSGD, flat_params=8, straggler_p=0.1), Bd.make_config(4, Bd.SDPSGD, flat_params=8, tau=1),
+           Bd.make_config(4, Bd.SDPSGD, flat_params=8, mix=Bd.MIX_PAIR),
            Bd.make_config(4, 0, flat_params=8, tau=1, straggler_p=0.1),
            Bd.make_config(4, 0, input_dim=39, hidden=64, layers=1, classes=100, batch=4, frames=20),
            Bd.make_config(4, 0, input_dim=40, hidden=64, layers=0, classes=100, batch=4, frames=20),
            Bd.make_config(4, 0, flat_params=8, precision=2), Bd.make_config(4, 0, flat_params=8, mix=3),
            Bd.make_config(4, 1, flat_params=8, mix=Bd.MIX_TRI, straggler_p=0.1)]
     assert Bd.adpsgd_workspace_bytes(Bd.make_config(4, 0, flat_params=8, mix=Bd.MIX_TRI)) > 0     # ring neighbours, weights 1/3
+    # the synchronous baseline: one model buffer, the all-learner mean by default
+    assert Bd.adpsgd_workspace_bytes(Bd.make_config(64, Bd.SDPSGD, flat_params=1000)) == 64 * 1024 * 4 + scratch
+    assert Bd.adpsgd_workspace_bytes(Bd.make_config(4, Bd.SDPSGD, flat_params=8, mix=Bd.MIX_ALL, tau=0)) > 0
     for cfg in bad:
         with pytest.raises(Bd.AdpsgdError) as ei:
             Bd.adpsgd_workspace_bytes(cfg)

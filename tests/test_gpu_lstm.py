@@ -143,6 +143,13 @@ def test_ring_neighbour_mixing_small_model(prec):
     assert ora.mix == S.MIX_TRI
 
 
+@pytest.mark.parametrize("prec", [0, 1])
+def test_synchronous_baseline_small_model(prec):
+    print("sdpsgd small, model-bearing", prec, flush=True)
+    ora = _run_recurrence(Shape(12, 16, 2, 1, 8, 20, 5, 4), 4, S.SDPSGD, prec, 4, 0.3, seed=6, scale=0.1)
+    assert ora.update_first and ora.consensus() == 0.0
+
+
 def test_library_initial_model_matches_generator_spec():
     import torch
     shape = Shape(8, 8, 1, 0, 0, 8, 2, 2)

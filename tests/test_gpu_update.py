@@ -120,3 +120,27 @@ def test_all_stragglers_is_identity_and_average_is_learner_mean():
         s = s + cur[j]
     assert (eng.average().cpu().numpy() == s * (np.float32(1) / np.float32(L))).all()
     eng.close()
+
+
+@pytest.mark.parametrize("L,P", [(1, 5), (3, 2), (4, 70001), (16, 4096), (128, 1003), (8, 1 << 20)])
+def test_synchronous_baseline_update_then_mean(L, P):
+    print("update sdpsgd", L, P, flush=True)
+    _run(L, P, S.SDPSGD, 4)
+
+
+def test_synchronous_baseline_keeps_the_learners_identical():
+    import torch
+    from paper_2110_11199_amd import binding as Bd
+    L, P = 6, 10007
+    r = np.random.default_rng(8)
+    x0 = r.uniform(-1, 1, (L, P)).astype(np.float32)
+    eng = Bd.Adpsgd(Bd.make_config(L, S.SDPSGD, flat_params=P))
+    for i in range(L):
+        eng.set_params(i, torch.from_numpy(x0[i]).cuda())
+    g = [torch.from_numpy((r.standard_normal(P) * 1e-2).astype(np.float32)).cuda() for _ in range(L)]
+    eng.step(g, 0.1)
+    first = eng.params(0).cpu().numpy().view(np.uint32)
+    for i in range(1, L):
+        assert (eng.params(i).cpu().numpy().view(np.uint32) == first).all()
+    assert eng.consensus() == 0.0
+    eng.close()
