@@ -1,11 +1,15 @@
 // Grouped MFMA GEMM kernels: the time-batched GEMMs of the LSTM gradient
 // (input projections, output layers, weight gradients, input gradients).
 //
-// Three tile configurations are built:
+// Four tile configurations are built:
 //   10  256x256 workgroup tile, 8 waves (128x64 each), 128-byte K stages, direct global->LDS loads
 //       (no staging registers, no LDS store instructions); an operand that is not K-contiguous
 //       (dW = dA' X, dX = dA W) is transposed on the LDS read.  All large bf16 problems with
 //       16-byte aligned rows and K a multiple of 64.
+//   11  the same tile and loads on 4 waves (128x128 each, one wave per SIMD, accumulators in AGPRs):
+//       a third fewer LDS fragment bytes per flop; with no second wave per SIMD to hide latencies the
+//       main loop is software-pipelined by hand (GemmDma::run_deep).  Chosen for K >= 512 on outputs
+//       of at least 512 x 512.
 //   5   the same tile staged through registers, the transposition done between the registers
 //       and LDS.  Large bf16 problems that miss the conditions of 10 (ragged K, 8-byte rows).
 //   0   128x128 tile, 4 waves (64x64 each), 64-byte stages, staged through registers.  Small
@@ -217,7 +221,8 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_dma_kernel(GemmDesc p) {
 
     f32x16_t acc[FM][FN];
     zero_tile<FM, FN>(acc);
-    Core::run(acc, a, b, p.K, lds);
+    if constexpr (WM * WN == 4 && FM * FN == 16) Core::run_deep(acc, a, b, p.K, lds);
+    else Core::run(acc, a, b, p.K, lds);
     if (m0 + Core::BM <= p.M && n0 + Core::BN <= p.N && p.ldc < (1 << 26)) store_tile_interior<T, Core, FM, FN>(acc, p, m0, n0, gi, gd);
     else store_tile<T, Core, FM, FN>(acc, p, m0, n0, gi, gd);
 }
@@ -288,6 +293,9 @@ hipError_t launch_gemm(const GemmDesc& d, hipStream_t s) {
         // 256x256 tiles once there are enough of them to fill the 256 CUs
         const int64_t big_tiles = (int64_t)((d.M + 255) / 256) * ((d.N + 255) / 256) * d.groupsI * d.groupsD;
         v = big_tiles >= 128 ? 10 : 0;
+        // long K loops on large outputs: one wave per SIMD with 128x128 wave tiles (measured 3-7% faster there;
+        // with few K stages or narrow outputs the epilogue of its four waves costs more than the loop gains)
+        if (v == 10 && d.K >= 512 && d.M >= 512 && d.N >= 512) v = 11;
     }
     // direct-to-LDS loads need whole stages and, for a rows-contiguous operand, whole 16-byte chunks of rows
     // (16-byte aligned k-rows of a rows-contiguous operand must be at least round_up(rows, 8) long)
@@ -295,6 +303,7 @@ hipError_t launch_gemm(const GemmDesc& d, hipStream_t s) {
     const bool dma = d.K % 64 == 0 && d.lda < (1 << 22) && d.ldb < (1 << 22) && aligned_to(d.A, d.lda, d.sAi, d.sAd, esz, 16) &&
                      aligned_to(d.B, d.ldb, d.sBi, d.sBd, esz, 16) &&
                      (d.a_kc || d.lda >= ((d.M + 7) & ~7)) && (d.b_kc || d.ldb >= ((d.N + 7) & ~7));
+    if (v == 11 && dma) return launch_dma<bf16_t, 2, 2, 4, 4, 128, 2>(d, s);
     if (v == 10 && dma) return launch_dma<bf16_t, 2, 4, 4, 2, 128, 2>(d, s);
     if (v >= 5) return launch_layout<bf16_t, 2, 4, 4, 2, 16, 128>(d, s);
     return launch_layout<bf16_t, 2, 2, 2, 2, 16, 64>(d, s);

@@ -23,6 +23,7 @@
 // slot s of k-row k holds chunk s ^ 4*(k mod 4) of that row: the 32 lanes served in one LDS
 // cycle (4 k-rows x 64 bytes, twice) then cover all 64 banks once.
 #pragma once
+#include <type_traits>
 #include "gemm_core.hpp"
 
 namespace adpsgd {
@@ -178,6 +179,148 @@ struct GemmDma {
                     for (int fn = 0; fn < FN; ++fn) mma_chunk<T>(acc[fm][fn], af[fm], bfr[fn]);
             }
         }
+    }
+
+    // One fragment of k-chunk C for run_deep: fragment index F counts a0, b0, a1, b1, ... (A and B alternate
+    // while both remain) so that the first MFMAs of a chunk can start before all of its fragments have arrived.
+    template <int C, int F>
+    __device__ static void load_one(const char* cur, int wave_m, int wave_n, int g, int lane, uint4 (&af)[FM], uint4 (&bfr)[FN]) {
+        constexpr int kBoth = FM < FN ? FM : FN;
+        constexpr bool is_a = F < 2 * kBoth ? (F % 2 == 0) : (FM > FN);
+        constexpr int idx = F < 2 * kBoth ? F / 2 : F - kBoth;
+        const int ch = 2 * C + g;
+        if constexpr (is_a) af[idx] = frag<BM, ASrc::kc>(cur, (wave_m * FM + idx) * 32, ch, lane);
+        else bfr[idx] = frag<BN, BSrc::kc>(cur + A_BYTES, (wave_n * FN + idx) * 32, ch, lane);
+    }
+    template <int C, int F = 0>
+    __device__ static void load_all(const char* cur, int wave_m, int wave_n, int g, int lane, uint4 (&af)[FM], uint4 (&bfr)[FN]) {
+        if constexpr (F < FM + FN) {
+            load_one<C, F>(cur, wave_m, wave_n, g, lane, af, bfr);
+            load_all<C, F + 1>(cur, wave_m, wave_n, g, lane, af, bfr);
+        }
+    }
+
+    // MFMA number I of a chunk works on tile (fm, fn) = order(I): tiles whose fragments arrive first come first
+    // (all tiles with max(fm, fn) = 0, then 1, ...).
+    __device__ static constexpr int order_fm(int I) {
+        int n = 0;
+        for (int r = 0; r < (FM > FN ? FM : FN); ++r) {
+            for (int j = 0; j <= r; ++j) {          // (r, j) for j < r, (j, r) for j <= r
+                if (j < r && r < FM && j < FN) { if (n == I) return r; ++n; }
+                if (j < FM && r < FN) { if (n == I) return j; ++n; }
+            }
+        }
+        return 0;
+    }
+    __device__ static constexpr int order_fn(int I) {
+        int n = 0;
+        for (int r = 0; r < (FM > FN ? FM : FN); ++r) {
+            for (int j = 0; j <= r; ++j) {
+                if (j < r && r < FM && j < FN) { if (n == I) return j; ++n; }
+                if (j < FM && r < FN) { if (n == I) return r; ++n; }
+            }
+        }
+        return 0;
+    }
+
+    template <int LO, int HI, class Fn> __device__ static void static_for(Fn&& f) {
+        if constexpr (LO < HI) { f(std::integral_constant<int, LO>{}); static_for<LO + 1, HI>(f); }
+    }
+    __device__ static constexpr int min_(int x, int y) { return x < y ? x : y; }
+
+    // Direct load number D of a stage (the LA loads of the A tile, then the LB loads of the B tile).
+    template <int D>
+    __device__ static void issue_one(const ASrc& a, const BSrc& b, const uint32_t (&aoff)[LA], const uint32_t (&boff)[LB],
+                                     int k0, char* stage, int wave) {
+        if constexpr (D < LA) {
+            const T* sbase = ASrc::kc ? a.base + k0 : a.base + (int64_t)k0 * a.ld;
+            dma16_(aoff[D], sbase, lds_addr_(stage) + (uint32_t)wave * 1024u + (uint32_t)(D * NT) * 16u);
+        } else {
+            const T* sbase = BSrc::kc ? b.base + k0 : b.base + (int64_t)k0 * b.ld;
+            dma16_(boff[D - LA], sbase, lds_addr_(stage + A_BYTES) + (uint32_t)wave * 1024u + (uint32_t)((D - LA) * NT) * 16u);
+        }
+    }
+
+    // One K stage of run_deep.  Register set (C & 1) holds the fragments of chunk C; while the MFMAs of chunk C
+    // run, the fragments of the next chunk are read into the other set: from this stage's buffer, or (last
+    // chunk, NEXT) chunk 0 of the next stage's buffer.  The one barrier of the stage sits before the last chunk:
+    // by then every wave has its last fragments of this stage in registers (their reads are issued in the first
+    // half of the chunk before, and waited for), and its share of the next stage has landed, so that after it
+    // the next stage may be read and this stage's buffer may be overwritten by the loads of the stage after next
+    // (DMA), which are issued one per MFMA of the last chunk.  The scheduling barriers keep this order.
+    template <bool NEXT, bool DMA>
+    __device__ static void deep_stage(f32x16_t (&acc)[FM][FN], const ASrc& a, const BSrc& b, const uint32_t (&aoff)[LA],
+                                      const uint32_t (&boff)[LB], char* cur, const char* nxt, int dma_k0, int wave, int wave_m,
+                                      int wave_n, int g, int lane, uint4 (&af)[2][FM], uint4 (&bfr)[2][FN]) {
+        constexpr int NC = SB / 32, NM = FM * FN, NF = FM + FN, ND = LA + LB;
+        static_assert(NC % 2 == 0 && NC >= 2, "the register sets alternate per chunk and must line up across stages");
+        static_for<0, NC>([&](auto cc) {
+            constexpr int C = decltype(cc)::value;
+            constexpr bool last = C == NC - 1;
+            if constexpr (last) {
+                asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+                __builtin_amdgcn_s_barrier();
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            constexpr int R = (C >= NC - 2) ? 2 : 1;   // front-loaded before the barrier and before the loop's back edge
+            static_for<0, NM>([&](auto ii) {
+                constexpr int I = decltype(ii)::value;
+                if constexpr (!last || NEXT) {
+                    constexpr int f0 = min_(I * NF * R / NM, NF), f1 = min_((I + 1) * NF * R / NM, NF);
+                    static_for<f0, f1>([&](auto ff) {
+                        load_one<(C + 1) % NC, decltype(ff)::value>(last ? nxt : (const char*)cur, wave_m, wave_n, g, lane,
+                                                                    af[(C + 1) & 1], bfr[(C + 1) & 1]);
+                    });
+                }
+                if constexpr (last && DMA) {
+                    constexpr int d0 = I * ND / NM, d1 = (I + 1) * ND / NM;
+                    static_for<d0, d1>([&](auto dd) { issue_one<decltype(dd)::value>(a, b, aoff, boff, dma_k0, cur, wave); });
+                }
+                constexpr int fm = order_fm(I), fn = order_fn(I);
+                mma_chunk<T>(acc[fm][fn], af[C & 1][fm], bfr[C & 1][fn]);
+                __builtin_amdgcn_sched_barrier(0);
+            });
+        });
+    }
+
+    // The same main loop for one wave per SIMD (large wave tiles: fewer LDS bytes per flop, but no second
+    // wave to hide latencies): software-pipelined by hand, two LDS stages.
+    __device__ static void run_deep(f32x16_t (&acc)[FM][FN], const ASrc& a, const BSrc& b, int K, char* lds, int rot = 0) {
+        static_assert(NS == 2, "two stages");
+        constexpr int LPT = LA + LB;
+        const int tid = threadIdx.x;
+        const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+        const int wave_m = wave / WN, wave_n = wave % WN;
+        const int g = lane >> 5;
+        const int nk = K / KT;
+        uint32_t aoff[LA], boff[LB];
+        lane_offsets<BM, LA>(a, tid, aoff);
+        lane_offsets<BN, LB>(b, tid, boff);
+        auto kblock = [&](int s) { int kb = s + rot; return (kb >= nk ? kb - nk : kb) * KT; };
+        issue<LA>(a, aoff, kblock(0), lds, wave);
+        issue<LB>(b, boff, kblock(0), lds + A_BYTES, wave);
+        if (nk > 1) {
+            issue<LA>(a, aoff, kblock(1), lds + STAGE_BYTES, wave);
+            issue<LB>(b, boff, kblock(1), lds + STAGE_BYTES + A_BYTES, wave);
+            wait_vm<LPT>();
+        } else {
+            wait_vm<0>();
+        }
+        __builtin_amdgcn_s_barrier();
+        uint4 af[2][FM], bfr[2][FN];
+        load_all<0>(lds, wave_m, wave_n, g, lane, af[0], bfr[0]);
+        __builtin_amdgcn_sched_barrier(0);
+        int kt = 0;
+        for (; kt + 2 < nk; ++kt) {
+            char* cur = lds + (kt & 1) * STAGE_BYTES;
+            deep_stage<true, true>(acc, a, b, aoff, boff, cur, lds + ((kt + 1) & 1) * STAGE_BYTES, kblock(kt + 2), wave, wave_m, wave_n, g, lane, af, bfr);
+        }
+        if (kt + 1 < nk) {
+            char* cur = lds + (kt & 1) * STAGE_BYTES;
+            deep_stage<true, false>(acc, a, b, aoff, boff, cur, lds + ((kt + 1) & 1) * STAGE_BYTES, 0, wave, wave_m, wave_n, g, lane, af, bfr);
+            ++kt;
+        }
+        deep_stage<false, false>(acc, a, b, aoff, boff, lds + (kt & 1) * STAGE_BYTES, lds, 0, wave, wave_m, wave_n, g, lane, af, bfr);
     }
 
     __device__ static int acc_row(int fm, int i) {
