@@ -150,6 +150,20 @@ def test_synchronous_baseline_small_model(prec):
     assert ora.update_first and ora.consensus() == 0.0
 
 
+@pytest.mark.parametrize("groups", [2, 3, 5])
+def test_forward_recurrence_in_learner_groups(groups):
+    # large models run the forward recurrence group of learners by group of learners (all frames of a group
+    # first); forced here on a small one, 5 learners in 2 + 3, 1 + 1 + 3 and 1 + 1 + 1 + 1 + 1
+    from paper_2110_11199_amd import binding as Bd
+    print("forward recurrence in learner groups", groups, flush=True)
+    Bd.adpsgd_gemm_set_variant(300 + groups)
+    try:
+        for prec in (0, 1):
+            _run_recurrence(Shape(12, 64, 2, 1, 0, 20, 40, 3), 5, S.RANDOM_RING, prec, 2, 0.2, seed=7, scale=0.1)
+    finally:
+        Bd.adpsgd_gemm_set_variant(300)
+
+
 def test_library_initial_model_matches_generator_spec():
     import torch
     shape = Shape(8, 8, 1, 0, 0, 8, 2, 2)
