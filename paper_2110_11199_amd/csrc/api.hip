@@ -329,7 +329,7 @@ int compute_gradients(adpsgd_handle* h, const float* at, const void* const* batc
         r.y = Y(l); r.sYi = M * DH;
         r.wh = W(h->ix_wh[l]); r.sWi = Pp; r.sWd = (int64_t)4 * H * H;
         // per frame and (learner, direction): W_h once, h in and out, 4 gates in and out (fp32), c in and out
-        if (int rc = mark(h, 2, T, 2.0 * B * H * 4 * H * (T - 1) * L * D,
+        if (int rc = mark(h, 2, T * rec_forward_parts(h), 2.0 * B * H * 4 * H * (T - 1) * L * D,
                           (double)T * L * D * (4.0 * H * H * esz + (double)B * H * (2 * esz + 8 * 4 + 2 * 4)))) return rc;
         // Learners in groups, all T steps of a group before the next group: a step re-reads W_h of its learners,
         // and a group whose per-step traffic fits the 256 MB memory-side cache finds it there (measured on the
