@@ -13,7 +13,11 @@
  *   (b) the mixing term W_k T_k for the fixed ring (Section III-B), the
  *       randomly permuted ring (Section III-C, Fisher-Yates) or the
  *       delay-by-one scheme (Section III-D: T = 11'/L, gradient one iterate behind);
+ *       on the rings either pairwise (weights 1/2) or with both ring neighbours
+ *       (weights 1/3, the operator T^f of Eq. 9);
  *   (c) the fused mixing + SGD update  w <- (mixed model) - lr * g  (Algorithm 1).
+ * The synchronous baseline of Section III-A (Algorithm 2: update, then the mean
+ * of all learners) runs on the same engine as a fourth pattern.
  *
  * Conventions
  *   - Every function returns ADPSGD_OK (0) or a negative ADPSGD_E* code; the
@@ -118,8 +122,9 @@ int adpsgd_workspace_bytes(const adpsgd_config* cfg, size_t* out);
 int adpsgd_create(const adpsgd_config* cfg, void* dev_workspace, size_t bytes,
                   void* hip_stream, adpsgd_t* out);
 
-/* One iteration k -> k+1 (Algorithm 3 / Algorithm 4 on every learner at once):
- * schedule, gradients at x^{k-tau}, mixing, update.  Asynchronous.
+/* One iteration k -> k+1 (Algorithm 3 / Algorithm 4, or Algorithm 2 for the
+ * synchronous baseline, on every learner at once): schedule, gradients at
+ * x^{k-tau}, mixing, update.  Asynchronous.
  * batch_ptrs: host array of device pointers.
  *   model mode: [2L], batch_ptrs[2i] = features of learner i ([T][B][I] fp32),
  *               batch_ptrs[2i+1] = labels of learner i ([T][B] int32);
