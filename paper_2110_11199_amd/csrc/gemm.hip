@@ -1,17 +1,20 @@
 // Grouped MFMA GEMM kernels: the time-batched GEMMs of the LSTM gradient
 // (input projections, output layers, weight gradients, input gradients).
 //
-// Four tile configurations are built:
-//   10  256x256 workgroup tile, 8 waves (128x64 each), 128-byte K stages, direct global->LDS loads
-//       (no staging registers, no LDS store instructions); an operand that is not K-contiguous
-//       (dW = dA' X, dX = dA W) is transposed on the LDS read.  All large bf16 problems with
-//       16-byte aligned rows and K a multiple of 64.
-//   11  the same tile and loads on 4 waves (128x128 each, one wave per SIMD, accumulators in AGPRs):
-//       a third fewer LDS fragment bytes per flop; with no second wave per SIMD to hide latencies the
-//       main loop is software-pipelined by hand (GemmDma::run_deep).  Chosen for K >= 512 on outputs
-//       of at least 512 x 512.
-//   5   the same tile staged through registers, the transposition done between the registers
-//       and LDS.  Large bf16 problems that miss the conditions of 10 (ragged K, 8-byte rows).
+// Five tile configurations are built; 10-12 share the 256x256 workgroup tile brought in by direct global->LDS
+// loads (no staging registers, no LDS store instructions), with an operand that is not K-contiguous
+// (dW = dA' X, dX = dA W) transposed on the LDS read; they need bf16, 16-byte aligned rows and K a multiple of 64:
+//   12  4 waves (128x128 each, one wave per SIMD, accumulators in AGPRs), three 64-byte K stages.  With no
+//       second wave per SIMD to hide latencies the main loop is software-pipelined by hand
+//       (GemmDma::run_deep).  Problems with a rows-contiguous operand (dW, dX).
+//   11  the same with two 128-byte stages: when both operands are K-contiguous (input projections) their rows
+//       are fetched in whole 128-byte lines, which 64-byte stages split in two requests (measured inside the
+//       training step: 1.40 against 1.48 ms per input projection, and the reverse, 1.32 against 1.25 ms, for dX).
+//   10  8 waves (128x64 each), two 128-byte stages, compiler-scheduled loop (GemmDma::run): K-contiguous
+//       operands with K < 512 or a narrow output, where the epilogue of only four waves costs more than the
+//       pipelined loop gains (output layer: 1.49 against 1.59 ms).
+//   5   the 8-wave tile staged through registers, the transposition done between the registers
+//       and LDS.  Large bf16 problems that miss the conditions of 10-12 (ragged K, 8-byte rows).
 //   0   128x128 tile, 4 waves (64x64 each), 64-byte stages, staged through registers.  Small
 //       problems and fp32 operands.
 // A 256x256 tile needs half the operand bytes per flop of a 128x128 one.  The main loop of
@@ -292,10 +295,7 @@ hipError_t launch_gemm(const GemmDesc& d, hipStream_t s) {
     if (v < 0) {
         // 256x256 tiles once there are enough of them to fill the 256 CUs
         const int64_t big_tiles = (int64_t)((d.M + 255) / 256) * ((d.N + 255) / 256) * d.groupsI * d.groupsD;
-        v = big_tiles >= 128 ? 10 : 0;
-        // long K loops on large outputs: one wave per SIMD with 128x128 wave tiles (measured 3-7% faster there;
-        // with few K stages or narrow outputs the epilogue of its four waves costs more than the loop gains)
-        if (v == 10 && d.K >= 512 && d.M >= 512 && d.N >= 512) v = 11;
+        v = big_tiles < 128 ? 0 : !(d.a_kc && d.b_kc) ? 12 : (d.K >= 512 && d.M >= 512 && d.N >= 512) ? 11 : 10;
     }
     // direct-to-LDS loads need whole stages and, for a rows-contiguous operand, whole 16-byte chunks of rows
     // (16-byte aligned k-rows of a rows-contiguous operand must be at least round_up(rows, 8) long)
@@ -303,6 +303,7 @@ hipError_t launch_gemm(const GemmDesc& d, hipStream_t s) {
     const bool dma = d.K % 64 == 0 && d.lda < (1 << 22) && d.ldb < (1 << 22) && aligned_to(d.A, d.lda, d.sAi, d.sAd, esz, 16) &&
                      aligned_to(d.B, d.ldb, d.sBi, d.sBd, esz, 16) &&
                      (d.a_kc || d.lda >= ((d.M + 7) & ~7)) && (d.b_kc || d.ldb >= ((d.N + 7) & ~7));
+    if (v == 12 && dma) return launch_dma<bf16_t, 2, 2, 4, 4, 64, 3>(d, s);
     if (v == 11 && dma) return launch_dma<bf16_t, 2, 2, 4, 4, 128, 2>(d, s);
     if (v == 10 && dma) return launch_dma<bf16_t, 2, 4, 4, 2, 128, 2>(d, s);
     if (v >= 5) return launch_layout<bf16_t, 2, 4, 4, 2, 16, 128>(d, s);

@@ -248,7 +248,7 @@ struct GemmDma {
     // half of the chunk before, and waited for), and its share of the next stage has landed, so that after it
     // the next stage may be read and this stage's buffer may be overwritten by the loads of the stage after next
     // (DMA), which are issued one per MFMA of the last chunk.  The scheduling barriers keep this order.
-    template <bool NEXT, bool DMA>
+    template <bool NEXT, bool DMA, int OUT>
     __device__ static void deep_stage(f32x16_t (&acc)[FM][FN], const ASrc& a, const BSrc& b, const uint32_t (&aoff)[LA],
                                       const uint32_t (&boff)[LB], char* cur, const char* nxt, int dma_k0, int wave, int wave_m,
                                       int wave_n, int g, int lane, uint4 (&af)[2][FM], uint4 (&bfr)[2][FN]) {
@@ -258,7 +258,8 @@ struct GemmDma {
             constexpr int C = decltype(cc)::value;
             constexpr bool last = C == NC - 1;
             if constexpr (last) {
-                asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+                wait_vm<OUT * (LA + LB)>();          // the next stage has landed; OUT later stages may be in flight
+                asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
                 __builtin_amdgcn_s_barrier();
                 __builtin_amdgcn_sched_barrier(0);
             }
@@ -284,9 +285,10 @@ struct GemmDma {
     }
 
     // The same main loop for one wave per SIMD (large wave tiles: fewer LDS bytes per flop, but no second
-    // wave to hide latencies): software-pipelined by hand, two LDS stages.
+    // wave to hide latencies): software-pipelined by hand, NS LDS stages (the loads of stage kt + NS are issued
+    // during the last chunk of stage kt, into the buffer that stage has just finished with).
     __device__ static void run_deep(f32x16_t (&acc)[FM][FN], const ASrc& a, const BSrc& b, int K, char* lds, int rot = 0) {
-        static_assert(NS == 2, "two stages");
+        static_assert(NS >= 2 && NS <= 4, "two to four stages");
         constexpr int LPT = LA + LB;
         const int tid = threadIdx.x;
         const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -297,30 +299,37 @@ struct GemmDma {
         lane_offsets<BM, LA>(a, tid, aoff);
         lane_offsets<BN, LB>(b, tid, boff);
         auto kblock = [&](int s) { int kb = s + rot; return (kb >= nk ? kb - nk : kb) * KT; };
-        issue<LA>(a, aoff, kblock(0), lds, wave);
-        issue<LB>(b, boff, kblock(0), lds + A_BYTES, wave);
-        if (nk > 1) {
-            issue<LA>(a, aoff, kblock(1), lds + STAGE_BYTES, wave);
-            issue<LB>(b, boff, kblock(1), lds + STAGE_BYTES + A_BYTES, wave);
-            wait_vm<LPT>();
-        } else {
-            wait_vm<0>();
+#pragma unroll
+        for (int s = 0; s < NS; ++s) {
+            if (s < nk) {
+                issue<LA>(a, aoff, kblock(s), lds + s * STAGE_BYTES, wave);
+                issue<LB>(b, boff, kblock(s), lds + s * STAGE_BYTES + A_BYTES, wave);
+            }
         }
+        const int later = (nk < NS ? nk : NS) - 1;          // stages issued after stage 0
+        if (NS >= 4 && later >= 3) wait_vm<(NS >= 4 ? 3 : 0) * LPT>();
+        else if (NS >= 3 && later == 2) wait_vm<(NS >= 3 ? 2 : 0) * LPT>();
+        else if (later == 1) wait_vm<LPT>();
+        else wait_vm<0>();
         __builtin_amdgcn_s_barrier();
         uint4 af[2][FM], bfr[2][FN];
         load_all<0>(lds, wave_m, wave_n, g, lane, af[0], bfr[0]);
         __builtin_amdgcn_sched_barrier(0);
-        int kt = 0;
-        for (; kt + 2 < nk; ++kt) {
-            char* cur = lds + (kt & 1) * STAGE_BYTES;
-            deep_stage<true, true>(acc, a, b, aoff, boff, cur, lds + ((kt + 1) & 1) * STAGE_BYTES, kblock(kt + 2), wave, wave_m, wave_n, g, lane, af, bfr);
+        int kt = 0, buf = 0;
+        auto next_buf = [](int x) { return x + 1 == NS ? 0 : x + 1; };
+        for (; kt + NS < nk; ++kt) {
+            deep_stage<true, true, NS - 2>(acc, a, b, aoff, boff, lds + buf * STAGE_BYTES, lds + next_buf(buf) * STAGE_BYTES,
+                                           kblock(kt + NS), wave, wave_m, wave_n, g, lane, af, bfr);
+            buf = next_buf(buf);
         }
-        if (kt + 1 < nk) {
-            char* cur = lds + (kt & 1) * STAGE_BYTES;
-            deep_stage<true, false>(acc, a, b, aoff, boff, cur, lds + ((kt + 1) & 1) * STAGE_BYTES, 0, wave, wave_m, wave_n, g, lane, af, bfr);
-            ++kt;
+        for (; kt + 1 < nk; ++kt) {
+            char* cur = lds + buf * STAGE_BYTES;
+            const char* nxt = lds + next_buf(buf) * STAGE_BYTES;
+            // the last NS - 1 stages wait for everything in flight (issued at least a stage ago)
+            deep_stage<true, false, 0>(acc, a, b, aoff, boff, cur, nxt, 0, wave, wave_m, wave_n, g, lane, af, bfr);
+            buf = next_buf(buf);
         }
-        deep_stage<false, false>(acc, a, b, aoff, boff, lds + (kt & 1) * STAGE_BYTES, lds, 0, wave, wave_m, wave_n, g, lane, af, bfr);
+        deep_stage<false, false, 0>(acc, a, b, aoff, boff, lds + buf * STAGE_BYTES, lds, 0, wave, wave_m, wave_n, g, lane, af, bfr);
     }
 
     __device__ static int acc_row(int fm, int i) {

@@ -72,7 +72,7 @@ def test_gemm_bf16(a_k, b_k, M, N, K):
 def test_gemm_bf16_large_tiles(a_k, b_k, M, N, K, pad):
     # enough 256x256 tiles (>= 128 over the groups) for the large-tile kernels: direct-to-LDS loads
     # when K is a multiple of 64 and all rows are 16-byte aligned (row counts need not be multiples of 8: pad=4
-    # makes the k-rows of a 516-row operand 520 long), else register staging; K = 64 ... 448 is 1 ... 7 stages of
+    # makes the k-rows of a 516-row operand 520 long), else register staging; K = 64 ... 448 is 2 ... 14 stages of
     # the direct-to-LDS main loop (its first, steady-state and last stages are separate code)
     print("gemm bf16 large", a_k, b_k, M, N, K, pad, flush=True)
     groups = 16 if N < 600 else 22
@@ -83,21 +83,22 @@ def test_gemm_bf16_large_tiles(a_k, b_k, M, N, K, pad):
 @pytest.mark.parametrize("a_k,b_k", LAYOUTS)
 @pytest.mark.parametrize("M,N,K,pad", [(520, 516, 512, 0), (776, 520, 576, 8)])
 def test_gemm_bf16_long_k_loop(a_k, b_k, M, N, K, pad):
-    # K >= 512 on outputs of at least 512 x 512 selects the one-wave-per-SIMD configuration with the
-    # hand-pipelined main loop (8 and 9 K stages here)
+    # 16 and 18 K stages of the hand-pipelined main loop (its steady state)
     print("gemm bf16 long K", a_k, b_k, M, N, K, pad, flush=True)
     assert _run(1, a_k, b_k, 0, M, N, K, 16, True, pad=pad) < 2e-6
     assert _run(1, a_k, b_k, 1, M, N, K, 16, False, pad=pad) < 6e-3
 
 
+@pytest.mark.parametrize("variant", [10, 11, 12])
 @pytest.mark.parametrize("a_k,b_k", LAYOUTS)
 @pytest.mark.parametrize("K", [64, 128, 192, 256])
-def test_gemm_bf16_pipelined_loop_with_few_stages(a_k, b_k, K):
-    # the pipelined main loop has separate code for its last two stages and its first one: force that
-    # configuration on 1 .. 4 stages
+def test_gemm_bf16_forced_large_tile_configurations(variant, a_k, b_k, K):
+    # the pipelined main loops (11: 64-k stages, 12: 32-k stages) have separate code for their first stages,
+    # their steady state and their last stages: 1 .. 4 and 2 .. 8 stages here, in every operand layout
+    # (the automatic choice uses 10 and 11 for K-contiguous operands only, 12 for the others)
     from paper_2110_11199_amd import binding as Bd
-    print("gemm bf16 pipelined, few stages", a_k, b_k, K, flush=True)
-    Bd.adpsgd_gemm_set_variant(11)
+    print("gemm bf16 forced configuration", variant, a_k, b_k, K, flush=True)
+    Bd.adpsgd_gemm_set_variant(variant)
     try:
         assert _run(1, a_k, b_k, 0, 300, 264, K, 3, True, pad=8) < 2e-6
     finally:
