@@ -61,15 +61,26 @@ __device__ inline void map_tile(int bid, int total, int tiles_m, int tiles_n, in
 // Every store reads its data from a register of its own (the bias is added in place, the
 // bf16 values are converted into a separate array first): with one temporary register
 // reused for all stores the compiler has to wait for each store before the next one.
-template <typename T, class Core, int FM, int FN>
-__device__ inline void store_tile(f32x16_t (&acc)[FM][FN], const GemmDesc& p, int m0, int n0, int gi, int gd) {
+// Bias of this lane's FN accumulator columns (0 without a bias or past the last column).  Loaded before the
+// main loop: in the epilogue the load's latency would stand in front of the stores of every tile.
+template <class Core, int FN>
+__device__ inline void load_bias(float (&bv)[FN], const GemmDesc& p, int n0, int gi, int gd) {
     const float* bias = p.bias ? p.bias + gi * p.sBiasI + gd * p.sBiasD : nullptr;
+#pragma unroll
+    for (int fn = 0; fn < FN; ++fn) {
+        const int col = n0 + Core::acc_col(fn);
+        bv[fn] = (bias && col < p.N) ? bias[col] : 0.f;
+    }
+}
+
+template <typename T, class Core, int FM, int FN>
+__device__ inline void store_tile(f32x16_t (&acc)[FM][FN], const float (&bias)[FN], const GemmDesc& p, int m0, int n0, int gi, int gd) {
     const int64_t coff = gi * p.sCi + gd * p.sCd;
 #pragma unroll
     for (int fn = 0; fn < FN; ++fn) {
         const int col = n0 + Core::acc_col(fn);
         if (col >= p.N) continue;
-        const float bv = bias ? bias[col] : 0.f;
+        const float bv = bias[fn];
 #pragma unroll
         for (int fm = 0; fm < FM; ++fm) {
             const int row0 = m0 + Core::acc_row(fm, 0);          // rows of this lane: row0 + 8*(i/4) + i%4
@@ -127,13 +138,12 @@ __device__ inline void store_u_b16_(uint32_t off, uint32_t v, const void* base_u
 // same for all stores of the lane, so the epilogue costs no vector address arithmetic and no branches.
 // Needs (4 * ldc + 32) * 4 bytes to fit the 32-bit offset (checked by the caller).
 template <typename T, class Core, int FM, int FN>
-__device__ inline void store_tile_interior(f32x16_t (&acc)[FM][FN], const GemmDesc& p, int m0, int n0, int gi, int gd) {
+__device__ inline void store_tile_interior(f32x16_t (&acc)[FM][FN], const float (&bias)[FN], const GemmDesc& p, int m0, int n0, int gi, int gd) {
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int wave_m = wave / Core::kWN, wave_n = wave % Core::kWN;
     const uint32_t lane_elem = (uint32_t)(4 * (lane >> 5)) * (uint32_t)p.ldc + (uint32_t)(lane & 31);
     const int64_t tile_off = gi * p.sCi + gd * p.sCd + (int64_t)(m0 + wave_m * FM * 32) * p.ldc + n0 + wave_n * FN * 32;
-    const float* bias = p.bias ? p.bias + gi * p.sBiasI + gd * p.sBiasD + n0 + wave_n * FN * 32 + (lane & 31) : nullptr;
     const bool narrow = p.c_elem && sizeof(T) == 2;
     const int esz = narrow ? 2 : 4;
     const char* cbase = (const char*)p.C + tile_off * esz;
@@ -141,7 +151,7 @@ __device__ inline void store_tile_interior(f32x16_t (&acc)[FM][FN], const GemmDe
     const int64_t row_bytes = (int64_t)p.ldc * esz;
 #pragma unroll
     for (int fn = 0; fn < FN; ++fn) {
-        const float bv = bias ? bias[fn * 32] : 0.f;
+        const float bv = bias[fn];
 #pragma unroll
         for (int fm = 0; fm < FM; ++fm) {
             const char* fbase = cbase + (int64_t)(fm * 32) * row_bytes + fn * 32 * esz;
@@ -195,7 +205,9 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_kernel(GemmDesc p) {
     f32x16_t acc[FM][FN];
     zero_tile<FM, FN>(acc);
     Core::run(acc, a, b, p.K, lds);
-    store_tile<T, Core, FM, FN>(acc, p, m0, n0, gi, gd);
+    float bias[FN];          // (this register-staged loop has no registers to spare for an early load)
+    load_bias<Core, FN>(bias, p, n0, gi, gd);
+    store_tile<T, Core, FM, FN>(acc, bias, p, m0, n0, gi, gd);
 }
 
 // Same tile bookkeeping with the direct-to-LDS main loop (16-byte aligned operands, K a multiple of
@@ -222,12 +234,14 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_dma_kernel(GemmDesc p) {
     if constexpr (BKC) { b.base = B + (int64_t)n0 * p.ldb; b.R = p.N - n0; } else { b.base = B + n0; b.R = (p.N - n0 + 7) & ~7; }
     b.ld = p.ldb;
 
+    float bias[FN];
+    load_bias<Core, FN>(bias, p, n0, gi, gd);
     f32x16_t acc[FM][FN];
     zero_tile<FM, FN>(acc);
     if constexpr (WM * WN == 4 && FM * FN == 16) Core::run_deep(acc, a, b, p.K, lds);
     else Core::run(acc, a, b, p.K, lds);
-    if (m0 + Core::BM <= p.M && n0 + Core::BN <= p.N && p.ldc < (1 << 26)) store_tile_interior<T, Core, FM, FN>(acc, p, m0, n0, gi, gd);
-    else store_tile<T, Core, FM, FN>(acc, p, m0, n0, gi, gd);
+    if (m0 + Core::BM <= p.M && n0 + Core::BN <= p.N && p.ldc < (1 << 26)) store_tile_interior<T, Core, FM, FN>(acc, bias, p, m0, n0, gi, gd);
+    else store_tile<T, Core, FM, FN>(acc, bias, p, m0, n0, gi, gd);
 }
 
 template <typename T, bool AKC, bool BKC, int WM, int WN, int FM, int FN, int VB, int SB>
