@@ -145,6 +145,37 @@ def test_tri_random_ring_expected_gram_and_consensus_bound():
         assert norms[k] <= math.sqrt(L - 1) / math.sqrt(3) ** (k + 1) * 1.02
 
 
+@pytest.mark.parametrize("L", [16, 32, 64])
+def test_decay_to_consensus_at_the_learner_counts_of_the_figure(L):
+    # Section IV (the figure on convergence speed to consensus, L = 16, 32, 64): the fixed ring's distance
+    # to consensus is exactly lambda-hat^k (T^f is symmetric, so the bound of Section III-B is attained),
+    # the random ring's mean distance stays below sqrt(L-1)/sqrt(3)^k (Section III-C) and falls below
+    # the fixed ring's within a few iterations; allreduce is at consensus after one.
+    U = np.full((L, L), 1.0 / L)
+    lam_hat = 1 / 3 + 2 / 3 * math.cos(2 * math.pi / L)
+    order, partner, active = S.schedule(S.FIXED_RING, 0, 0, L)
+    Tf = S.mixing_matrix(S.MIX_TRI, order, partner, active)
+    steps, runs = 10, 30
+    fixed = np.zeros(steps)
+    Pf = np.eye(L)
+    for k in range(steps):
+        Pf = Pf @ Tf
+        fixed[k] = np.linalg.norm(Pf - U, 2)
+        assert abs(fixed[k] - lam_hat ** (k + 1)) < 1e-12
+    rand = np.zeros(steps)
+    for r in range(runs):
+        Pm = np.eye(L)
+        for k in range(steps):
+            order, partner, active = S.schedule(S.RANDOM_RING, 500 + r, k, L)
+            Pm = Pm @ S.mixing_matrix(S.MIX_TRI, order, partner, active)
+            rand[k] += np.linalg.norm(Pm - U, 2) / runs
+    for k in range(steps):
+        assert rand[k] <= math.sqrt(L - 1) / math.sqrt(3) ** (k + 1) * 1.05
+    assert rand[-1] < 0.1 * fixed[-1]              # random mixing is far ahead after ten iterations
+    order, partner, active = S.schedule(S.D1D, 0, 0, L)
+    assert np.linalg.norm(S.mixing_matrix(S.MIX_ALL, order, partner, active) - U, 2) < 1e-15
+
+
 def test_all_matrix_is_uniform():
     order, partner, active = S.schedule(S.D1D, 0, 3, 16)
     T = S.mixing_matrix(S.MIX_ALL, order, partner, active)
