@@ -110,21 +110,8 @@ struct GemmDma {
     }
 
     template <int N> __device__ static void wait_vm() {
-        if constexpr (N == 0) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        else if constexpr (N == 2) asm volatile("s_waitcnt vmcnt(2)" ::: "memory");
-        else if constexpr (N == 3) asm volatile("s_waitcnt vmcnt(3)" ::: "memory");
-        else if constexpr (N == 4) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
-        else if constexpr (N == 6) asm volatile("s_waitcnt vmcnt(6)" ::: "memory");
-        else if constexpr (N == 8) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
-        else if constexpr (N == 9) asm volatile("s_waitcnt vmcnt(9)" ::: "memory");
-        else if constexpr (N == 10) asm volatile("s_waitcnt vmcnt(10)" ::: "memory");
-        else if constexpr (N == 5) asm volatile("s_waitcnt vmcnt(5)" ::: "memory");
-        else if constexpr (N == 20) asm volatile("s_waitcnt vmcnt(20)" ::: "memory");
-        else if constexpr (N == 12) asm volatile("s_waitcnt vmcnt(12)" ::: "memory");
-        else if constexpr (N == 16) asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
-        else if constexpr (N == 18) asm volatile("s_waitcnt vmcnt(18)" ::: "memory");
-        else if constexpr (N == 24) asm volatile("s_waitcnt vmcnt(24)" ::: "memory");
-        else static_assert(N < 0, "add the immediate");
+        static_assert(N >= 0 && N <= 63, "vmcnt is a 6-bit counter");
+        asm volatile("s_waitcnt vmcnt(%0)" :: "n"(N) : "memory");
     }
 
     // K must be a multiple of KT (checked by the host).  acc must be initialised.
