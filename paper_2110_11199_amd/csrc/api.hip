@@ -130,7 +130,10 @@ int rec_forward_parts(const adpsgd_handle* h) {
     const double cache = 256e6;
     // workgroups of one launch: (learner, direction) x 32-unit slices x 128-row batch tiles
     const int64_t wgs = (int64_t)h->L * h->D * ((h->H + 31) / 32) * ((h->B + 127) / 128);
-    if (per_step > cache && per_step / 2 <= cache && h->L >= 2 && wgs / 2 >= 512) return 2;
+    if (per_step <= cache) return 1;
+    // the fewest groups whose step fits the cache, as long as a group's launch still fills the chip twice over
+    for (int parts = 2; parts <= h->L && wgs / parts >= 512; ++parts)
+        if (per_step / parts <= cache) return parts;
     return 1;
 }
 
