@@ -130,7 +130,7 @@ def cpu_baseline(wl, seed=0, budget_s=12.0):
 # the same counters read for cast_bf16_kernel, whose size is known (FETCH_SIZE reads 0.5x its bytes, WRITE_SIZE
 # 1.0x): profiles/hbm_traffic_cfg4_cfg5.txt.  Keyed by workload; bytes per launch of the named kernel class.
 TRAFFIC = {
-    ("cfg4", "batched_gemm"): 2.81e9,     # mean over the 29 time-batched GEMM launches of one iteration
+    ("cfg4", "batched_gemm"): 2.78e9,     # mean over the 29 time-batched GEMM launches of one iteration
     ("cfg4", "recurrent"): 0.306e9,       # mean over 2 x 126 rec_forward_dma_kernel launches (0.220, half the learners each:
                                           # part of it is served by the memory-side cache) and 126 rec_backward_dma_kernel (0.478)
     ("cfg4", "mix_update"): 32.5e9,       # all_update_kernel with the bf16 copy written along

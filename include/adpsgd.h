@@ -224,7 +224,7 @@ int adpsgd_gemm(int precision, int a_kmajor, int b_kmajor, int c_is_elem,
                 int groups, void* hip_stream);
 
 /* Tuning knob for benchmarks: force the GEMM tile configuration of this process
- * (0, 5, 10, 11 or 12, see csrc/gemm.hip; 100 / 101 switch the direct-to-LDS recurrent
+ * (0, 5, 11, 12 or 13, see csrc/gemm.hip; 100 / 101 switch the direct-to-LDS recurrent
  * kernels off / on; 300 + S runs the forward recurrence in S groups of learners,
  * 300 = automatic); -1 restores the automatic tile choice.  Not thread-safe.    */
 int adpsgd_gemm_set_variant(int variant);

@@ -717,7 +717,7 @@ int adpsgd_gemm(int precision, int a_kmajor, int b_kmajor, int c_is_elem, int M,
 int adpsgd_gemm_set_variant(int variant) {
     if (variant == 100 || variant == 101) { set_rec_dma(variant - 100); return ADPSGD_OK; }
     if (variant >= 300 && variant <= 316) { g_rec_split = variant - 300; return ADPSGD_OK; }
-    if (variant != -1 && variant != 0 && variant != 5 && variant != 10 && variant != 11 && variant != 12) return fail(ADPSGD_EINVAL, "variant must be -1, 0, 5, 10, 11 or 12");
+    if (variant != -1 && variant != 0 && variant != 5 && (variant < 11 || variant > 13)) return fail(ADPSGD_EINVAL, "variant must be -1, 0, 5, 11, 12 or 13");
     set_gemm_variant(variant);
     return ADPSGD_OK;
 }

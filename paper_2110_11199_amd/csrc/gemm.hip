@@ -1,25 +1,23 @@
 // Grouped MFMA GEMM kernels: the time-batched GEMMs of the LSTM gradient
 // (input projections, output layers, weight gradients, input gradients).
 //
-// Five tile configurations are built; 10-12 share the 256x256 workgroup tile brought in by direct global->LDS
-// loads (no staging registers, no LDS store instructions), with an operand that is not K-contiguous
-// (dW = dA' X, dX = dA W) transposed on the LDS read; they need bf16, 16-byte aligned rows and K a multiple of 64:
-//   12  4 waves (128x128 each, one wave per SIMD, accumulators in AGPRs), three 64-byte K stages.  With no
-//       second wave per SIMD to hide latencies the main loop is software-pipelined by hand
-//       (GemmDma::run_deep).  Problems with a rows-contiguous operand (dW, dX).
+// Five tile configurations are built; 11-13 bring their operands in by direct global->LDS loads (no staging
+// registers, no LDS store instructions), transpose an operand that is not K-contiguous (dW = dA' X, dX = dA W)
+// on the LDS read, and run a main loop that is software-pipelined by hand (GemmDma::run_deep); they need bf16,
+// 16-byte aligned rows and K a multiple of 64:
+//   12  256x256 tile on 4 waves (128x128 each, one wave per SIMD, accumulators in AGPRs), three 64-byte K
+//       stages.  Problems with a rows-contiguous operand (dW, dX).
 //   11  the same with two 128-byte stages: when both operands are K-contiguous (input projections) their rows
 //       are fetched in whole 128-byte lines, which 64-byte stages split in two requests (measured inside the
 //       training step: 1.40 against 1.48 ms per input projection, and the reverse, 1.32 against 1.25 ms, for dX).
-//   10  8 waves (128x64 each), two 128-byte stages, compiler-scheduled loop (GemmDma::run): K-contiguous
-//       operands with K < 512 or a narrow output, where the epilogue of only four waves costs more than the
-//       pipelined loop gains (output layer: 1.49 against 1.59 ms).
-//   5   the 8-wave tile staged through registers, the transposition done between the registers
-//       and LDS.  Large bf16 problems that miss the conditions of 10-12 (ragged K, 8-byte rows).
+//   13  128x256 tile on 4 waves (64x128 each), three 64-byte stages, two workgroups per CU: K-contiguous
+//       operands with K < 512 or a narrow output (output layer, layer-0 input projection), whose tiles spend
+//       as long storing as computing; the second workgroup's loop runs during the first one's epilogue.
+//   5   256x256 tile on 8 waves (128x64 each) staged through registers, the transposition done between
+//       the registers and LDS.  Large bf16 problems that miss the conditions of 11-13 (ragged K, 8-byte rows).
 //   0   128x128 tile, 4 waves (64x64 each), 64-byte stages, staged through registers.  Small
 //       problems and fp32 operands.
-// A 256x256 tile needs half the operand bytes per flop of a 128x128 one.  The main loop of
-// configuration 10 is bound inside the CU: per 64-k step it reads 192 KB of fragments from LDS
-// and receives 64 KB of direct loads, which takes as long as the step's 32 MFMAs per wave.
+// A 256x256 tile needs half the operand bytes per flop of a 128x128 one.
 #include <type_traits>
 #include "gemm_core.hpp"
 #include "gemm_dma.hpp"
@@ -213,7 +211,7 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_kernel(GemmDesc p) {
 // Same tile bookkeeping with the direct-to-LDS main loop (16-byte aligned operands, K a multiple of
 // the stage length).
 template <typename T, bool AKC, bool BKC, int WM, int WN, int FM, int FN, int SB, int NS>
-__global__ __launch_bounds__(64 * WM * WN) void gemm_dma_kernel(GemmDesc p) {
+__global__ __launch_bounds__(64 * WM * WN, (WM * WN == 4 && FM * FN == 8) ? 2 : 1) void gemm_dma_kernel(GemmDesc p) {
     typedef typename std::conditional<AKC, KcSrc<T>, McSrc<T>>::type ASrc;
     typedef typename std::conditional<BKC, KcSrc<T>, McSrc<T>>::type BSrc;
     typedef GemmDma<T, ASrc, BSrc, WM, WN, FM, FN, SB, NS> Core;
@@ -238,7 +236,7 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_dma_kernel(GemmDesc p) {
     load_bias<Core, FN>(bias, p, n0, gi, gd);
     f32x16_t acc[FM][FN];
     zero_tile<FM, FN>(acc);
-    if constexpr (WM * WN == 4 && FM * FN == 16) Core::run_deep(acc, a, b, p.K, lds);
+    if constexpr (WM * WN == 4 && (FM * FN == 16 || FM * FN == 8)) Core::run_deep(acc, a, b, p.K, lds);
     else Core::run(acc, a, b, p.K, lds);
     if (m0 + Core::BM <= p.M && n0 + Core::BN <= p.N && p.ldc < (1 << 26)) store_tile_interior<T, Core, FM, FN>(acc, bias, p, m0, n0, gi, gd);
     else store_tile<T, Core, FM, FN>(acc, bias, p, m0, n0, gi, gd);
@@ -309,7 +307,7 @@ hipError_t launch_gemm(const GemmDesc& d, hipStream_t s) {
     if (v < 0) {
         // 256x256 tiles once there are enough of them to fill the 256 CUs
         const int64_t big_tiles = (int64_t)((d.M + 255) / 256) * ((d.N + 255) / 256) * d.groupsI * d.groupsD;
-        v = big_tiles < 128 ? 0 : !(d.a_kc && d.b_kc) ? 12 : (d.K >= 512 && d.M >= 512 && d.N >= 512) ? 11 : 10;
+        v = big_tiles < 128 ? 0 : !(d.a_kc && d.b_kc) ? 12 : (d.K >= 512 && d.M >= 512 && d.N >= 512) ? 11 : 13;
     }
     // direct-to-LDS loads need whole stages and, for a rows-contiguous operand, whole 16-byte chunks of rows
     // (16-byte aligned k-rows of a rows-contiguous operand must be at least round_up(rows, 8) long)
@@ -317,9 +315,9 @@ hipError_t launch_gemm(const GemmDesc& d, hipStream_t s) {
     const bool dma = d.K % 64 == 0 && d.lda < (1 << 22) && d.ldb < (1 << 22) && aligned_to(d.A, d.lda, d.sAi, d.sAd, esz, 16) &&
                      aligned_to(d.B, d.ldb, d.sBi, d.sBd, esz, 16) &&
                      (d.a_kc || d.lda >= ((d.M + 7) & ~7)) && (d.b_kc || d.ldb >= ((d.N + 7) & ~7));
+    if (v == 13 && dma) return launch_dma<bf16_t, 2, 2, 2, 4, 64, 3>(d, s);
     if (v == 12 && dma) return launch_dma<bf16_t, 2, 2, 4, 4, 64, 3>(d, s);
     if (v == 11 && dma) return launch_dma<bf16_t, 2, 2, 4, 4, 128, 2>(d, s);
-    if (v == 10 && dma) return launch_dma<bf16_t, 2, 4, 4, 2, 128, 2>(d, s);
     if (v >= 5) return launch_layout<bf16_t, 2, 4, 4, 2, 16, 128>(d, s);
     return launch_layout<bf16_t, 2, 2, 2, 2, 16, 64>(d, s);
 }

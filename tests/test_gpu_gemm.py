@@ -89,13 +89,13 @@ def test_gemm_bf16_long_k_loop(a_k, b_k, M, N, K, pad):
     assert _run(1, a_k, b_k, 1, M, N, K, 16, False, pad=pad) < 6e-3
 
 
-@pytest.mark.parametrize("variant", [10, 11, 12])
+@pytest.mark.parametrize("variant", [11, 12, 13])
 @pytest.mark.parametrize("a_k,b_k", LAYOUTS)
 @pytest.mark.parametrize("K", [64, 128, 192, 256])
 def test_gemm_bf16_forced_large_tile_configurations(variant, a_k, b_k, K):
-    # the pipelined main loops (11: 64-k stages, 12: 32-k stages) have separate code for their first stages,
-    # their steady state and their last stages: 1 .. 4 and 2 .. 8 stages here, in every operand layout
-    # (the automatic choice uses 10 and 11 for K-contiguous operands only, 12 for the others)
+    # the pipelined main loops (11: 64-k stages, 12 and 13: 32-k stages) have separate code for their first
+    # stages, their steady state and their last stages: 1 .. 4 and 2 .. 8 stages here, in every operand layout
+    # (the automatic choice uses 11 and 13 for K-contiguous operands only, 12 for the others)
     from paper_2110_11199_amd import binding as Bd
     print("gemm bf16 forced configuration", variant, a_k, b_k, K, flush=True)
     Bd.adpsgd_gemm_set_variant(variant)
