@@ -8,8 +8,9 @@ delay-by-one, 6-layer BLSTM with 1024 cells per direction, 256-wide linear
 bottleneck, 32000 classes, 128 segments x 21 frames per learner, bf16 GEMM
 operands), the only one that exercises every kernel of the path.  A second,
 short leg times the model-free mixing/update stress workload ("cfg5") for the
-HBM part of the metric.  Inputs are seeded synthetic data, resident in HBM
-before the timed region.
+HBM part of the metric, and a third the smaller delay-by-one model ("cfg3") for
+the MFMA fraction of its GEMM phases.  Inputs are seeded synthetic data, resident
+in HBM before the timed region.
 
 Prints ONE JSON line.  `roofline` describes the kernel that dominates the step
 (the time-batched MFMA GEMM): algorithmic flops / its GPU time measured with HIP
@@ -42,10 +43,12 @@ def _config(Bd, wl, seed, variant=None):
                           batch=wl.batch, frames=wl.frames, precision=wl.precision)
 
 
-def run_model(wl, steps, warmup, seed=0):
+def run_model(wl, steps, warmup, seed=0, tune=()):
     import torch
     from paper_2110_11199_amd import binding as Bd, synth
     eng = Bd.Adpsgd(_config(Bd, wl, seed))
+    for key, value in tune:
+        eng.tune(key, value)
     w0 = synth.initial_model(seed, eng.P, wl.init_scale)
     eng.set_params(-1, torch.from_numpy(w0).cuda())
     cdf = synth.zipf_cdf(wl.classes) if wl.label_dist == "zipf" else None
@@ -100,15 +103,18 @@ def run_flat(wl, steps, warmup, seed=0, variant=None):
 
 
 def cpu_baseline(wl, seed=0, budget_s=12.0):
-    """The numpy oracle, as it stands, on learner minibatches of the workload until about budget_s
-    seconds of CPU work are spent."""
+    """The numpy oracle, as it stands, timed on this host.  Two figures: with the threads its BLAS takes by
+    itself, on whole learner minibatches of the workload until about budget_s seconds are spent; and pinned to
+    one thread, on the first segments of one learner's minibatch (a bounded sample: one whole cfg4 minibatch
+    takes most of a minute on one core)."""
     import numpy as np
     from paper_2110_11199_amd import synth
     from oracle import lstm
     try:
-        from threadpoolctl import threadpool_info
+        from threadpoolctl import threadpool_info, threadpool_limits
         cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
     except Exception:
+        threadpool_limits = None
         cores = os.cpu_count() or 1
     shape = lstm.Shape(wl.input_dim, wl.hidden, wl.layers, wl.bidirectional, wl.bottleneck, wl.classes,
                        wl.batch, wl.frames)
@@ -121,21 +127,57 @@ def cpu_baseline(wl, seed=0, budget_s=12.0):
         lstm.loss_and_grad(shape, w0, f, y, np.float32)
         dt += time.perf_counter() - t0
         done += 1
-    return {"value": done * wl.batch * wl.frames / dt, "unit": "frames/s", "cores": int(cores), "kind": "oracle",
-            "sample": "gradients of %d of the %d learner minibatches of one %s iteration (%.1f s of oracle time); the "
-                      "mixing/update part of the oracle is elementwise and under 1%% of that" % (done, wl.L, wl.name, dt)}
+    out = {"value": done * wl.batch * wl.frames / dt, "unit": "frames/s", "cores": int(cores), "kind": "oracle",
+           "sample": "gradients of %d of the %d learner minibatches of one %s iteration (%.1f s of oracle time, BLAS on "
+                     "%d threads); the mixing/update part of the oracle is elementwise and under 1%% of that"
+                     % (done, wl.L, wl.name, dt, cores)}
+    if threadpool_limits is not None:
+        # one thread: the first nb segments of learner 0's minibatch (the segments of a minibatch are independent
+        # of each other, so this is the same arithmetic per frame), sized to a few seconds
+        per_frame = dt / (done * wl.batch * wl.frames) * cores           # rough single-thread cost per frame
+        nb = max(1, min(wl.batch, int(6.0 / max(per_frame * wl.frames, 1e-9))))
+        f, y = synth.batch(wl, seed, 0, 0, cdf)
+        sub = shape._replace(batch=nb)
+        with threadpool_limits(limits=1):
+            t0 = time.perf_counter()
+            lstm.loss_and_grad(sub, w0, np.ascontiguousarray(f[:, :nb]), np.ascontiguousarray(y[:, :nb]), np.float32)
+            dt1 = time.perf_counter() - t0
+        out["one_thread"] = {"value": nb * wl.frames / dt1, "unit": "frames/s", "cores": 1,
+                             "sample": "gradient of the first %d of the %d segments of learner 0's minibatch (%.1f s, "
+                                       "BLAS pinned to one thread)" % (nb, wl.batch, dt1)}
+    return out
 
 
-# HBM traffic per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (KiB per dispatch), scaled by what
-# the same counters read for cast_bf16_kernel, whose size is known (FETCH_SIZE reads 0.5x its bytes, WRITE_SIZE
-# 1.0x): profiles/hbm_traffic_cfg4_cfg5.txt.  Keyed by workload; bytes per launch of the named kernel class.
-TRAFFIC = {
-    ("cfg4", "batched_gemm"): 2.78e9,     # mean over the 29 time-batched GEMM launches of one iteration
-    ("cfg4", "recurrent"): 0.306e9,       # mean over 2 x 126 rec_forward_dma_kernel launches (0.220, half the learners each:
-                                          # part of it is served by the memory-side cache) and 126 rec_backward_dma_kernel (0.478)
-    ("cfg4", "mix_update"): 32.5e9,       # all_update_kernel with the bf16 copy written along
-    ("cfg5", "mix_update"): 93.2e9,       # pair_update_kernel, mean over the profiled iterations
-}
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "hbm_traffic_cfg4_cfg5.txt")
+
+
+def load_traffic(path=TRAFFIC_FILE):
+    """HBM bytes per launch by kernel class, read from the committed counter summary (rocprofv3 --pmc FETCH_SIZE /
+    WRITE_SIZE, calibrated on a kernel of known size; the file states its commands).  Returns {class: bytes per
+    launch} with the classes bench.py reports, a class being absent when the table holds no kernel of it."""
+    rows = []
+    try:
+        with open(path) as fh:
+            for ln in fh:
+                parts = ln.rstrip().rsplit(None, 4)
+                if ln.startswith("#") or len(parts) != 5 or not parts[0].startswith("adpsgd::"):
+                    continue
+                try:
+                    rows.append((parts[0].strip(), int(parts[1]), float(parts[4]) * 1e9))
+                except ValueError:
+                    continue
+    except OSError:
+        return {}
+
+    def mean(pred):
+        sel = [(n, b) for name, n, b in rows if pred(name)]
+        cnt = sum(n for n, _ in sel)
+        return sum(n * b for n, b in sel) / cnt if cnt else None
+    out = {"cfg4/batched_gemm": mean(lambda k: "::gemm_" in k),
+           "cfg4/recurrent": mean(lambda k: "::rec_" in k),
+           "cfg4/mix_update": mean(lambda k: "::all_update_kernel" in k),
+           "cfg5/mix_update": mean(lambda k: "::pair_update_kernel" in k)}
+    return {k: v for k, v in out.items() if v is not None}
 
 
 def main():
@@ -148,16 +190,17 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--tri", action="store_true", help="also time the ring-neighbour (weights 1/3) mixing kernel on the cfg5 shape")
     ap.add_argument("--sync", action="store_true", help="also time the synchronous baseline's update-then-mean kernel on the cfg5 shape")
-    ap.add_argument("--tune", type=int, default=None, help="forwarded to adpsgd_gemm_set_variant (tuning only)")
+    ap.add_argument("--cfg3-steps", type=int, default=5, help="timed steps of the cfg3 leg (0 = skip)")
+    ap.add_argument("--tune", action="append", default=[], metavar="KEY:VALUE",
+                    help="forwarded to adpsgd_set_tuning of the model handles (tuning only), e.g. 0:12")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (L learners are replicas resident on one MI355X); "
               "--gpus %d is not supported" % args.gpus, file=sys.stderr)
         sys.exit(2)
     from paper_2110_11199_amd import synth
-    if args.tune is not None:
-        from paper_2110_11199_amd import binding as _Bd
-        _Bd.adpsgd_gemm_set_variant(args.tune)
+    tune = [tuple(int(v) for v in t.split(":")) for t in args.tune]
+    traffic = load_traffic()
     wl = synth.WORKLOADS[args.workload]
     out = {"metric": METRIC, "unit": "frames/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
            "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "data": "synthetic"}
@@ -168,7 +211,7 @@ def main():
         launches = max(sum(prof[p]["launches"] for p in phases), 1)
         gbs = nbytes / (ms * 1e-3) / 1e9 if ms > 0 else 0.0
         return {"bound": "hbm", "achieved": gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": gbs / PEAK_HBM_GBS,
-                "traffic": TRAFFIC.get((workload, traffic_key)) if traffic_key else None, "kernel": kernel,
+                "traffic": traffic.get("%s/%s" % (workload, traffic_key)) if traffic_key else None, "kernel": kernel,
                 "avg_launch_ms": ms / launches, "algorithmic_bytes_per_launch": nbytes / launches}
 
     if wl.flat_params:
@@ -181,7 +224,7 @@ def main():
                     "roofline": hbm_roofline(prof, ["mix_update"], "pair_update_kernel", wl.name, "mix_update")})
         out["mix_update_GBps"] = out["roofline"]["achieved"]
     else:
-        dt, prof, loss = run_model(wl, args.steps, args.warmup)
+        dt, prof, loss = run_model(wl, args.steps, args.warmup, tune=tune)
         ms = dt / args.steps * 1e3
         frames = wl.L * wl.batch * wl.frames
         dtype = "bf16" if wl.precision else "f32"
@@ -202,7 +245,9 @@ def main():
             "mean_loss_last_step": loss,
             "phases_ms_per_step": {k: v["ms"] / args.steps for k, v in prof.items()},
             "roofline": {"bound": "mfma", "achieved": tf, "peak": peak, "unit": "TFLOP/s", "frac": tf / peak,
-                         "traffic": TRAFFIC.get((wl.name, "batched_gemm")),
+                         "traffic": traffic.get("%s/batched_gemm" % wl.name),
+                         "traffic_source": "profiles/hbm_traffic_cfg4_cfg5.txt (rocprofv3 counter runs of this command; not "
+                                           "measured in this run)",
                          "kernel": "gemm_dma_kernel (time-batched GEMMs)",
                          "launches_per_step": g["launches"] / args.steps,
                          "avg_launch_ms": g["ms"] / max(g["launches"], 1),
@@ -231,6 +276,25 @@ def main():
                 r7.update({"workload": "cfg5 as the synchronous baseline (update, then the mean of all 64 learners), no stragglers",
                            "steps": args.mix_steps, "ms_per_step": dt7 / args.mix_steps * 1e3, "learner_steps_per_s": active7 / dt7})
                 out["mix_update_sync"] = r7
+        if args.cfg3_steps > 0 and wl.name != "cfg3":
+            # the smaller delay-by-one model: its GEMM phases against the same peak (short K loops, M = 1344)
+            w3 = synth.WORKLOADS["cfg3"]
+            dt3, prof3, _ = run_model(w3, args.cfg3_steps, 2, tune=tune)
+            g3 = prof3["batched_gemm"]
+            tf3 = g3["work"] / (g3["ms"] * 1e-3) / 1e12 if g3["ms"] > 0 else 0.0
+            r3ms = prof3["recurrent_fwd"]["ms"] + prof3["recurrent_bwd"]["ms"]
+            r3 = hbm_roofline(prof3, ["recurrent_fwd", "recurrent_bwd"], "recurrent step kernels", "cfg3")
+            r3["mfma_TFLOPs"] = (prof3["recurrent_fwd"]["work"] + prof3["recurrent_bwd"]["work"]) / (r3ms * 1e-3) / 1e12 if r3ms > 0 else 0.0
+            ms3 = dt3 / args.cfg3_steps * 1e3
+            out["roofline_cfg3"] = {
+                "bound": "mfma", "achieved": tf3, "peak": PEAK_TFLOPS["bf16"], "unit": "TFLOP/s", "frac": tf3 / PEAK_TFLOPS["bf16"],
+                "traffic": None, "kernel": "gemm_dma_kernel (time-batched GEMMs)", "workload": "cfg3", "steps": args.cfg3_steps,
+                "ms_per_step": ms3, "frames_per_s": w3.L * w3.batch * w3.frames / (ms3 * 1e-3),
+                "launches_per_step": g3["launches"] / args.cfg3_steps, "avg_launch_ms": g3["ms"] / max(g3["launches"], 1),
+                "flops_per_launch": g3["work"] / max(g3["launches"], 1),
+                "phases_ms_per_step": {k: v["ms"] / args.cfg3_steps for k, v in prof3.items()},
+                "recurrent": r3,
+                "update": hbm_roofline(prof3, ["mix_update"], "all_update_kernel", "cfg3")}
         if not args.no_cpu_baseline:
             out["cpu_baseline"] = cpu_baseline(wl)
     print(json.dumps(out))

@@ -38,7 +38,11 @@
  *         W_o [C][F], b_o [C]                         F = Bn or D*H
  *     input_dim, hidden, bottleneck and classes must be multiples of 4.
  *   - Batch layout: features [T][B][I] fp32 (time-major), labels [T][B] int32
- *     in [0, classes).
+ *     in [0, classes).  Labels are device data, so they are checked on the device: a
+ *     label outside the range is clamped (it is never used as an index) and raises a
+ *     sticky error flag of the handle; the first adpsgd_losses / adpsgd_status call
+ *     after that step, and every adpsgd_step issued once that step has completed,
+ *     return ADPSGD_EINVAL.
  */
 #ifndef ADPSGD_H
 #define ADPSGD_H
@@ -70,7 +74,8 @@ typedef enum { ADPSGD_FIXED_RING = 0, ADPSGD_RANDOM_RING = 1, ADPSGD_D1D = 2, AD
  *   TRI   (x_left + x_i + x_right)/3 with the two neighbours on the ring order: the
  *         circulant operator T^f of Eq. 9 (Section III-B) on the fixed ring and its
  *         permuted form T^r = P' T^f P on the random ring (Section III-C); summed as
- *         (x_left + x_i) + x_right in that order, then times fl(1/3)
+ *         (x_left + x_i) + x_right in that order, then times fl(1/3); needs L >= 3
+ *         (with fewer learners the three ring positions are not distinct)
  *   ALL   the global mean, T = 11'/L (allreduce, Section III-A / III-D)
  *   DEFAULT = PAIR for the rings, ALL for delay-by-one and the synchronous baseline. */
 typedef enum { ADPSGD_MIX_DEFAULT = -1, ADPSGD_MIX_PAIR = 0, ADPSGD_MIX_TRI = 1, ADPSGD_MIX_ALL = 2 } adpsgd_mix;
@@ -130,7 +135,11 @@ int adpsgd_create(const adpsgd_config* cfg, void* dev_workspace, size_t bytes,
  *               batch_ptrs[2i+1] = labels of learner i ([T][B] int32);
  *   flat mode:  [L],  batch_ptrs[i] = gradient of learner i ([flat_params] fp32).
  * The buffers are read during the call's stream work and never written.
- * A straggler's model is left bit-unchanged.                                   */
+ * A straggler (Section IV-D: a learner that sits the iteration out) computes nothing:
+ * its model is left bit-unchanged, its pointers are not read and may be NULL, its loss
+ * is reported as 0 and its slot of adpsgd_grads keeps the gradient it computed last.
+ * Returns the sticky error of an earlier step (see the conventions above) instead of
+ * enqueuing work once that error has reached the host.                          */
 int adpsgd_step(adpsgd_t h, const void* const* batch_ptrs, float lr);
 
 /* Device pointer to learner i's current model x_i^k ([P] fp32), borrowed.  With
@@ -147,9 +156,14 @@ int adpsgd_set_params(adpsgd_t h, int i, const float* dev_src);
  * model mode only), borrowed.  NULL on a bad argument.                         */
 float* adpsgd_grads(adpsgd_t h, int i);
 
-/* Mean cross-entropy of every learner's last minibatch, host_out [L].
- * Waits for the stream.                                                        */
+/* Mean cross-entropy of every learner's last minibatch (0 for a straggler), host_out [L].
+ * Waits for the stream; returns the handle's sticky error if a kernel has raised one.  */
 int adpsgd_losses(adpsgd_t h, float* host_out);
+
+/* Waits for the stream and returns ADPSGD_OK or the handle's sticky error: ADPSGD_EINVAL
+ * after a label outside [0, classes), ADPSGD_EHIP after a bounded wait between the
+ * workgroups of a kernel has run out.                                            */
+int adpsgd_status(adpsgd_t h);
 
 /* Number of parameters P of one learner.                                       */
 int64_t adpsgd_param_count(adpsgd_t h);
@@ -213,21 +227,27 @@ const char* adpsgd_last_error(void);
  *   a_kmajor != 0: A is [M][K] (row stride lda); else A is stored [K][M].
  *   b_kmajor != 0: B is [N][K] (row stride ldb); else B is stored [K][N].
  * bias (fp32 [N], or NULL) is added to every row.  Strides are in elements.
- * All pointers: device.  M, N, K >= 1; lda, ldb and the group strides must be
- * multiples of 4.                                                              */
+ * All pointers: device.  M, N, K >= 1; groups in 1..128; lda, ldb and the group
+ * strides must be multiples of 4.  tile_config: -1 = automatic choice, or one of the
+ * tile configurations 0, 5, 11, 12, 13 of csrc/gemm.hip (a configuration whose
+ * alignment rules the operands do not meet falls back to one that fits).        */
 int adpsgd_gemm(int precision, int a_kmajor, int b_kmajor, int c_is_elem,
                 int M, int N, int K,
                 const void* A, int64_t lda, int64_t strideA,
                 const void* B, int64_t ldb, int64_t strideB,
                 void* C, int64_t ldc, int64_t strideC,
                 const float* bias, int64_t strideBias,
-                int groups, void* hip_stream);
+                int groups, int tile_config, void* hip_stream);
 
-/* Tuning knob for benchmarks: force the GEMM tile configuration of this process
- * (0, 5, 11, 12 or 13, see csrc/gemm.hip; 100 / 101 switch the direct-to-LDS recurrent
- * kernels off / on; 300 + S runs the forward recurrence in S groups of learners,
- * 300 = automatic); -1 restores the automatic tile choice.  Not thread-safe.    */
-int adpsgd_gemm_set_variant(int variant);
+/* Tuning of ONE handle (benchmarks and tests; the defaults are the measured best):
+ *   ADPSGD_TUNE_GEMM_TILE        tile configuration of the time-batched GEMMs, as tile_config above
+ *   ADPSGD_TUNE_REC_DIRECT       1 (default) / 0: direct-to-LDS recurrent step kernels allowed or not
+ *   ADPSGD_TUNE_REC_FWD_GROUPS   learner groups the forward recurrence is run in, 0 = automatic
+ * Takes effect from the next adpsgd_step of that handle; other handles are not touched. */
+#define ADPSGD_TUNE_GEMM_TILE       0
+#define ADPSGD_TUNE_REC_DIRECT      1
+#define ADPSGD_TUNE_REC_FWD_GROUPS  2
+int adpsgd_set_tuning(adpsgd_t h, int key, int value);
 
 #ifdef __cplusplus
 }

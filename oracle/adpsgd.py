@@ -55,6 +55,8 @@ def mix_update(x, g, mix, order, partner, active, lr, update_first=False):
             s = s + (x[j] - (lr * np.asarray(g[j], dtype=np.float32)))
         out[:] = s * (np.float32(1.0) / np.float32(L))
         return out
+    if mix == S.MIX_TRI and L < 3:
+        raise ValueError("ring-neighbour mixing (weights 1/3, Eq. 9) needs at least 3 learners")
     if mix == S.MIX_ALL:
         s = x[0].copy()
         for j in range(1, L):
@@ -116,20 +118,31 @@ class Oracle:
     def gradient_point(self):
         return self.x_prev if self.tau == 1 else self.x
 
-    def step(self, batches, lr, grads=None):
+    def step(self, batches, lr, grads=None, workers=1):
         """batches: list of (feats, labels) per learner; or grads [L][P] given
-        directly in model-free mode."""
+        directly in model-free mode.  workers > 1 spreads the outer loop over the
+        learners, whose gradients are independent of each other (Algorithm 1: the
+        learners run concurrently), over that many threads; every learner's
+        arithmetic is unchanged, so the result is the same as with one."""
         order, partner, active = S.schedule(self.pattern, self.seed, self.k, self.L, self.straggler_p)
         self.last_schedule = (order, partner, active)
         if grads is None:
             at = self.gradient_point()
             grads = np.zeros((self.L, self.P), dtype=np.float32)
             losses = np.zeros(self.L, dtype=np.float32)
-            for i in range(self.L):
-                if active[i]:
-                    feats, labels = batches[i]
-                    losses[i], grads[i] = lstm.loss_and_grad(self.shape, at[i], feats, labels,
-                                                             np.float32, self.bf16_gemm)
+
+            def one(i):
+                feats, labels = batches[i]
+                losses[i], grads[i] = lstm.loss_and_grad(self.shape, at[i], feats, labels,
+                                                         np.float32, self.bf16_gemm)
+            todo = [i for i in range(self.L) if active[i]]
+            if workers > 1:
+                from concurrent.futures import ThreadPoolExecutor
+                with ThreadPoolExecutor(max_workers=workers) as ex:
+                    list(ex.map(one, todo))
+            else:
+                for i in todo:
+                    one(i)
             self.last_losses = losses
         self.last_grads = grads
         new = mix_update(self.x, grads, self.mix, order, partner, active, lr, self.update_first)

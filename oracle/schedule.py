@@ -109,7 +109,10 @@ def mixing_matrix(mix, order, partner, active):
                 T[i, i] = 0.5
                 T[i, j] = 0.5
     elif mix == MIX_TRI:
-        # Eq. (T^f) on the ring order: T^r = P' T^f P (Section III-C)
+        # Eq. (T^f) on the ring order: T^r = P' T^f P (Section III-C).  The circulant of Eq. 9 has three
+        # distinct positions per row (left neighbour, self, right neighbour): it is defined for L >= 3.
+        if L < 3:
+            raise ValueError("ring-neighbour mixing (weights 1/3) needs at least 3 learners")
         for p in range(L):
             i = order[p]
             for q in (p - 1, p, p + 1):

@@ -65,13 +65,16 @@ _lib.adpsgd_destroy.argtypes = [_vp]
 _lib.adpsgd_destroy.restype = None
 _lib.adpsgd_last_error.restype = C.c_char_p
 _lib.adpsgd_gemm.argtypes = [C.c_int] * 7 + [_vp, _i64, _i64, _vp, _i64, _i64, _vp, _i64, _i64, _vp, _i64,
-                                             C.c_int, _vp]
+                                             C.c_int, C.c_int, _vp]
+_lib.adpsgd_set_tuning.argtypes = [_vp, C.c_int, C.c_int]
+_lib.adpsgd_status.argtypes = [_vp]
 
 EXPORTS = ["adpsgd_workspace_bytes", "adpsgd_create", "adpsgd_step", "adpsgd_params", "adpsgd_set_params",
            "adpsgd_grads", "adpsgd_losses", "adpsgd_param_count", "adpsgd_layout_count", "adpsgd_layout",
            "adpsgd_schedule", "adpsgd_schedule_of", "adpsgd_iteration", "adpsgd_average", "adpsgd_destroy",
            "adpsgd_last_error", "adpsgd_gemm", "adpsgd_set_profiling", "adpsgd_profile",
-           "adpsgd_gemm_set_variant", "adpsgd_consensus"]
+           "adpsgd_set_tuning", "adpsgd_consensus", "adpsgd_status"]
+TUNE_GEMM_TILE, TUNE_REC_DIRECT, TUNE_REC_FWD_GROUPS = 0, 1, 2
 PHASES = ["stage_cast", "batched_gemm", "recurrent_fwd", "recurrent_bwd", "softmax_ce", "bias_colsum", "mix_update"]
 
 
@@ -182,8 +185,12 @@ def adpsgd_profile(h):
     return {PHASES[i]: {"ms": ms[i], "launches": cnt[i], "work": work[i], "bytes": nbytes[i]} for i in range(n)}
 
 
-def adpsgd_gemm_set_variant(v):
-    _check(_lib.adpsgd_gemm_set_variant(int(v)))
+def adpsgd_set_tuning(h, key, value):
+    _check(_lib.adpsgd_set_tuning(h, int(key), int(value)))
+
+
+def adpsgd_status(h):
+    _check(_lib.adpsgd_status(h))
 
 
 def adpsgd_destroy(h):
@@ -191,9 +198,9 @@ def adpsgd_destroy(h):
 
 
 def adpsgd_gemm(precision, a_kmajor, b_kmajor, c_is_elem, M, N, K, A, lda, strideA, B, ldb, strideB,
-                Cp, ldc, strideC, bias, strideBias, groups, stream_ptr):
+                Cp, ldc, strideC, bias, strideBias, groups, stream_ptr, tile_config=-1):
     _check(_lib.adpsgd_gemm(precision, a_kmajor, b_kmajor, c_is_elem, M, N, K, A, lda, strideA, B, ldb,
-                            strideB, Cp, ldc, strideC, bias, strideBias, groups, stream_ptr))
+                            strideB, Cp, ldc, strideC, bias, strideBias, groups, tile_config, stream_ptr))
 
 
 class Adpsgd:
@@ -218,13 +225,14 @@ class Adpsgd:
         return self.workspace[off:off + 4 * n].view(self.torch.float32)
 
     def step(self, batch_tensors, lr):
-        """batch_tensors: model mode [(feats, labels)] per learner; flat mode [grad] per learner."""
+        """batch_tensors: model mode [(feats, labels)] per learner; flat mode [grad] per learner.
+        An entry may be None (a straggler's batch is not read)."""
         ptrs = []
         for b in batch_tensors:
             if isinstance(b, (tuple, list)):
-                ptrs += [b[0].data_ptr(), b[1].data_ptr()]
+                ptrs += [b[0].data_ptr() if b[0] is not None else None, b[1].data_ptr() if b[1] is not None else None]
             else:
-                ptrs.append(b.data_ptr())
+                ptrs.append(b.data_ptr() if b is not None else None)
         adpsgd_step(self.h, ptrs, lr)
 
     def params(self, i):
@@ -250,6 +258,12 @@ class Adpsgd:
 
     def consensus(self):
         return adpsgd_consensus(self.h)
+
+    def status(self):
+        adpsgd_status(self.h)
+
+    def tune(self, key, value):
+        adpsgd_set_tuning(self.h, key, value)
 
     def close(self):
         if self.h is not None:

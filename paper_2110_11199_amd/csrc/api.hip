@@ -3,6 +3,8 @@
 #include <cmath>
 #include <cstdio>
 #include <cstring>
+#include <new>
+#include <stdexcept>
 #include <string>
 #include <vector>
 #include "../../include/adpsgd.h"
@@ -94,6 +96,14 @@ struct adpsgd_handle {
     Profiler prof;
     adpsgd_config cfg;
     hipStream_t stream;
+    // tuning (adpsgd_set_tuning): per handle, so that two handles of a process cannot interfere
+    int tune_gemm_tile = -1;               // forced GEMM tile configuration, -1 = automatic
+    int tune_rec_direct = 1;               // direct-to-LDS recurrent kernels allowed
+    int tune_rec_fwd_groups = 0;           // learner groups of the forward recurrence, 0 = automatic
+    // device status word (kStatus* bits, sticky) and its pinned host mirror, refreshed by an asynchronous
+    // copy at the end of every step
+    uint32_t* status = nullptr;
+    volatile uint32_t* status_host = nullptr;
     int L, D, H, T, B, I, C, Bn, layers, F, ldx;
     int mix, tau, prec, esz;
     bool flat;
@@ -121,20 +131,30 @@ struct adpsgd_handle {
 
 namespace {
 
-int g_rec_split = 0;     // tuning knob: > 0 forces the number of learner groups of the forward recurrence
-
-// Number of learner groups the forward recurrence is run in (see compute_gradients).
-int rec_forward_parts(const adpsgd_handle* h) {
-    if (g_rec_split > 0) return g_rec_split < h->L ? g_rec_split : h->L;
-    const double per_step = (double)h->L * h->D * (4.0 * h->H * h->H * h->esz + (double)h->B * h->H * (2 * h->esz + 8 * 4 + 2 * 4));
+// Number of learner groups the forward recurrence of n learners is run in (see compute_gradients).
+int rec_forward_parts(const adpsgd_handle* h, int n) {
+    if (h->tune_rec_fwd_groups > 0) return h->tune_rec_fwd_groups < n ? h->tune_rec_fwd_groups : n;
+    const double per_step = (double)n * h->D * (4.0 * h->H * h->H * h->esz + (double)h->B * h->H * (2 * h->esz + 8 * 4 + 2 * 4));
     const double cache = 256e6;
     // workgroups of one launch: (learner, direction) x 32-unit slices x 128-row batch tiles
-    const int64_t wgs = (int64_t)h->L * h->D * ((h->H + 31) / 32) * ((h->B + 127) / 128);
+    const int64_t wgs = (int64_t)n * h->D * ((h->H + 31) / 32) * ((h->B + 127) / 128);
     if (per_step <= cache) return 1;
     // the fewest groups whose step fits the cache, as long as a group's launch still fills the chip twice over
-    for (int parts = 2; parts <= h->L && wgs / parts >= 512; ++parts)
+    for (int parts = 2; parts <= n && wgs / parts >= 512; ++parts)
         if (per_step / parts <= cache) return parts;
     return 1;
+}
+
+// Turns the status bits a kernel has raised (as last copied to the host) into an error.
+int status_error(const adpsgd_handle* h) {
+    const uint32_t st = h->status_host ? *h->status_host : 0u;
+    if (st & kStatusWaitExpired)
+        return fail(ADPSGD_EHIP, "a bounded wait between the workgroups of a persistent recurrent kernel ran out in an earlier "
+                                 "step; the results of this handle are not valid");
+    if (st & kStatusBadLabel)
+        return fail(ADPSGD_EINVAL, "a label outside [0, classes) was met in an earlier step (it was clamped); the models of "
+                                   "this handle have taken an update from it");
+    return ADPSGD_OK;
 }
 
 bool all_by_default(int pattern) { return pattern == ADPSGD_D1D || pattern == ADPSGD_SDPSGD; }
@@ -149,6 +169,9 @@ int check_config(const adpsgd_config* c, std::string& why) {
     if (!(c->straggler_p >= 0.f && c->straggler_p < 1.f)) { why = "straggler_p must be in [0,1)"; return ADPSGD_EINVAL; }
     const int tau = c->tau >= 0 ? c->tau : (c->pattern == ADPSGD_D1D ? 1 : 0);
     const int mix = c->mix != ADPSGD_MIX_DEFAULT ? c->mix : (all_by_default(c->pattern) ? ADPSGD_MIX_ALL : ADPSGD_MIX_PAIR);
+    if (mix == ADPSGD_MIX_TRI && c->L < 3) {
+        why = "ring-neighbour mixing (weights 1/3, Eq. 9) needs at least 3 learners"; return ADPSGD_EINVAL;
+    }
     if (c->pattern == ADPSGD_SDPSGD && (mix != ADPSGD_MIX_ALL || tau != 0 || c->straggler_p > 0.f)) {
         why = "the synchronous baseline averages all learners (mix ALL), with tau = 0 and no stragglers";
         return ADPSGD_EINVAL;
@@ -215,6 +238,7 @@ size_t plan(adpsgd_handle* h, void* base) {
     h->params[0] = (float*)w.take(L * h->Ppad * 4);
     h->params[1] = h->tau == 1 ? (float*)w.take(L * h->Ppad * 4) : h->params[0];
     h->consensus = (double*)w.take((size_t)(kConsensusBlocks + 1) * 8);     // partial sums + the result
+    h->status = (uint32_t*)w.take(256);
     if (!h->flat) {
         const size_t M = (size_t)h->M, DH = (size_t)h->D * h->H, G4 = DH * 4, e = (size_t)h->esz;
         h->grads = (float*)w.take(L * h->Ppad * 4);
@@ -271,16 +295,31 @@ int gemm(adpsgd_handle* h, const GemmDesc& d, const char* what, int k_alg = 0) {
     const double K = k_alg > 0 ? k_alg : d.K;
     if (int rc = mark(h, 1, 1, 2.0 * d.M * d.N * K * g,
                       g * (((double)d.M + d.N) * K * esz + (double)d.M * d.N * (d.c_elem ? esz : 4.0)))) return rc;
-    HIPCHK(launch_gemm(d, h->stream), what);
+    GemmDesc q = d;
+    q.tile = h->tune_gemm_tile;
+    HIPCHK(launch_gemm(q, h->stream), what);
     return ADPSGD_OK;
 }
 
-// Gradient of every learner's minibatch loss at the models in `at` (A1-A8).
-int compute_gradients(adpsgd_handle* h, const float* at, const void* const* batch_ptrs) {
+// Gradient of every active learner's minibatch loss at the models in `at` (A1-A8).  A straggler
+// (active[i] == 0) computes nothing: it is left out of every launch, its loss is reported as 0 and its
+// slot of the gradient buffer keeps whatever it held.
+int compute_gradients(adpsgd_handle* h, const float* at, const void* const* batch_ptrs, const int32_t* active) {
     const int L = h->L, D = h->D, H = h->H, T = h->T, B = h->B, prec = h->prec;
     const int64_t M = h->M, DH = (int64_t)D * H, G4 = DH * 4, Pp = h->Ppad;
     const int esz = h->esz;
     hipStream_t s = h->stream;
+    LearnerMap act, ident;
+    ident.identity(); act.identity();
+    int n = 0;
+    uint32_t bits[4] = {0, 0, 0, 0};
+    for (int i = 0; i < L; ++i)
+        if (active[i]) { act.idx[n++] = (uint8_t)i; bits[i >> 5] |= 1u << (i & 31); }
+    if (n == 0) {
+        if (int rc = mark(h, 4, 1)) return rc;
+        HIPCHK(launch_zero(h->loss, 0, L, 1, ident, s), "zero losses");
+        return ADPSGD_OK;
+    }
     // weights as GEMM operands: the fp32 models themselves, or their bf16 copy
     const char* wbase = (const char*)at;
     if (int rc = mark(h, 0, prec ? (h->wx0p ? 3 : 2) : 1)) return rc;
@@ -297,24 +336,26 @@ int compute_gradients(adpsgd_handle* h, const float* at, const void* const* batc
     auto Gr = [&](int ix) { return h->grads + h->tensors[ix].off; };
 
     StageDesc st;
-    st.L = L; st.precision = prec; st.rows = M; st.I = h->I; st.ldx = h->ldx;
+    st.L = n; st.lmap = act; st.precision = prec; st.rows = M; st.I = h->I; st.ldx = h->ldx;
     st.x0 = h->x0; st.sX0 = M * h->ldx; st.y = h->labels; st.sY = M;
-    for (int i = 0; i < L; ++i) {
-        st.feats[i] = (const float*)batch_ptrs[2 * i];
-        st.labels[i] = (const int32_t*)batch_ptrs[2 * i + 1];
+    for (int i = 0; i < 128; ++i) {
+        st.feats[i] = i < L ? (const float*)batch_ptrs[2 * i] : nullptr;
+        st.labels[i] = i < L ? (const int32_t*)batch_ptrs[2 * i + 1] : nullptr;
     }
     HIPCHK(launch_stage(st, s), "stage minibatches");
 
     auto Y = [&](int l) { return (void*)((char*)h->ybuf + (size_t)l * L * M * DH * esz); };
     auto Gates = [&](int l) { return h->gates + (size_t)l * L * M * G4; };
     auto Cb = [&](int l) { return h->cbuf + (size_t)l * L * M * DH; };
+    // a GEMM over the active learners, one group per learner (and direction)
+    auto G = [&]() { GemmDesc g{}; g.precision = prec; g.groupsI = n; g.groupsD = 1; g.lmap = act; return g; };
 
     GemmDesc g;
     // ---- forward ----
     for (int l = 0; l < h->layers; ++l) {
         const int64_t Il = l == 0 ? h->I : DH;
-        g = GemmDesc{};
-        g.precision = prec; g.a_kc = 1; g.b_kc = 1; g.c_elem = 0;
+        g = G();
+        g.a_kc = 1; g.b_kc = 1; g.c_elem = 0;
         g.M = (int)M; g.N = (int)G4; g.K = (int)Il;
         g.A = l == 0 ? h->x0 : Y(l - 1); g.lda = l == 0 ? h->ldx : DH; g.sAi = M * g.lda;
         g.B = W(h->ix_wx[l]); g.ldb = Il; g.sBi = Pp;
@@ -323,28 +364,26 @@ int compute_gradients(adpsgd_handle* h, const float* at, const void* const* batc
         }
         g.C = Gates(l); g.ldc = G4; g.sCi = M * G4;
         g.bias = Bias(h->ix_b[l]); g.sBiasI = Pp;
-        g.groupsI = L; g.groupsD = 1;
         if (int rc = gemm(h, g, "input projection GEMM", (int)Il)) return rc;
         RecDesc r{};
-        r.precision = prec; r.L = L; r.D = D; r.B = B; r.H = H; r.T = T;
+        r.precision = prec; r.L = n; r.lmap = act; r.direct = h->tune_rec_direct; r.D = D; r.B = B; r.H = H; r.T = T;
         r.gates = Gates(l); r.sGi = M * G4;
         r.c = Cb(l); r.sCi = M * DH;
         r.y = Y(l); r.sYi = M * DH;
         r.wh = W(h->ix_wh[l]); r.sWi = Pp; r.sWd = (int64_t)4 * H * H;
-        // per frame and (learner, direction): W_h once, h in and out, 4 gates in and out (fp32), c in and out
-        if (int rc = mark(h, 2, T * rec_forward_parts(h), 2.0 * B * H * 4 * H * (T - 1) * L * D,
-                          (double)T * L * D * (4.0 * H * H * esz + (double)B * H * (2 * esz + 8 * 4 + 2 * 4)))) return rc;
         // Learners in groups, all T steps of a group before the next group: a step re-reads W_h of its learners,
         // and a group whose per-step traffic fits the 256 MB memory-side cache finds it there (measured on the
         // 16 x 1024-unit workload: 10.7 -> 8.9 ms per iteration in two groups; three or four groups leave too
         // few workgroups per launch and are slower than one).
-        const int parts = rec_forward_parts(h);
+        const int parts = rec_forward_parts(h, n);
+        // per frame and (learner, direction): W_h once, h in and out, 4 gates in and out (fp32), c in and out
+        if (int rc = mark(h, 2, T * parts, 2.0 * B * H * 4 * H * (T - 1) * n * D,
+                          (double)T * n * D * (4.0 * H * H * esz + (double)B * H * (2 * esz + 8 * 4 + 2 * 4)))) return rc;
         for (int part = 0; part < parts; ++part) {
-            const int n = L / parts, l0 = part * n;
+            const int per = n / parts, l0 = part * per;
             RecDesc q = r;
-            q.L = part == parts - 1 ? L - l0 : n;
-            q.gates = r.gates + l0 * r.sGi; q.c = r.c + l0 * r.sCi;
-            q.y = (char*)r.y + l0 * r.sYi * h->esz; q.wh = (const char*)r.wh + l0 * r.sWi * h->esz;
+            q.L = part == parts - 1 ? n - l0 : per;
+            for (int j = 0; j < q.L; ++j) q.lmap.idx[j] = act.idx[l0 + j];
             for (int t = 0; t < T; ++t) {
                 q.step = t;
                 HIPCHK(launch_rec_forward(q, s), "recurrent forward step");
@@ -354,30 +393,30 @@ int compute_gradients(adpsgd_handle* h, const float* at, const void* const* batc
     const void* top = Y(h->layers - 1);
     const void* zin = top; int64_t ldz = DH;
     if (h->Bn) {
-        g = GemmDesc{};
-        g.precision = prec; g.a_kc = 1; g.b_kc = 1; g.c_elem = 1;
+        g = G();
+        g.a_kc = 1; g.b_kc = 1; g.c_elem = 1;
         g.M = (int)M; g.N = h->Bn; g.K = (int)DH;
         g.A = top; g.lda = DH; g.sAi = M * DH;
         g.B = W(h->ix_wp); g.ldb = DH; g.sBi = Pp;
         g.C = h->z; g.ldc = h->Bn; g.sCi = M * h->Bn;
         g.bias = Bias(h->ix_bp); g.sBiasI = Pp;
-        g.groupsI = L; g.groupsD = 1;
         if (int rc = gemm(h, g, "bottleneck GEMM")) return rc;
         zin = h->z; ldz = h->Bn;
     }
     const int F = h->F, C = h->C;
-    g = GemmDesc{};
-    g.precision = prec; g.a_kc = 1; g.b_kc = 1; g.c_elem = 0;
+    g = G();
+    g.a_kc = 1; g.b_kc = 1; g.c_elem = 0;
     g.M = (int)M; g.N = C; g.K = F;
     g.A = zin; g.lda = ldz; g.sAi = M * ldz;
     g.B = W(h->ix_wo); g.ldb = F; g.sBi = Pp;
     g.C = h->logits; g.ldc = C; g.sCi = M * C;
     g.bias = Bias(h->ix_bo); g.sBiasI = Pp;
-    g.groupsI = L; g.groupsD = 1;
     if (int rc = gemm(h, g, "output GEMM")) return rc;
 
     SoftmaxDesc sm{};
-    sm.precision = prec; sm.L = L; sm.rows = M; sm.C = C;
+    sm.precision = prec; sm.L = n; sm.lmap = act; sm.L_all = L; sm.rows = M; sm.C = C;
+    for (int i = 0; i < 4; ++i) sm.active_bits[i] = bits[i];
+    sm.status = h->status;
     sm.logits = h->logits; sm.sLi = M * C; sm.y = h->labels; sm.sYi = M;
     sm.dlogits = h->dlogits; sm.sDi = M * C; sm.row_loss = h->row_loss; sm.loss = h->loss;
     if (int rc = mark(h, 4, 2)) return rc;
@@ -385,43 +424,39 @@ int compute_gradients(adpsgd_handle* h, const float* at, const void* const* batc
 
     // ---- backward: output layer(s) ----
     // dW_o = dlogits' z
-    g = GemmDesc{};
-    g.precision = prec; g.a_kc = 0; g.b_kc = 0; g.c_elem = 0;
+    g = G();
+    g.a_kc = 0; g.b_kc = 0; g.c_elem = 0;
     g.M = C; g.N = F; g.K = (int)M;
     g.A = h->dlogits; g.lda = C; g.sAi = M * C;
     g.B = zin; g.ldb = ldz; g.sBi = M * ldz;
     g.C = Gr(h->ix_wo); g.ldc = F; g.sCi = Pp;
-    g.groupsI = L; g.groupsD = 1;
     if (int rc = gemm(h, g, "dW_o GEMM")) return rc;
     if (int rc = mark(h, 5, 1)) return rc;
-    HIPCHK(launch_colsum(prec, h->dlogits, C, M * C, M, C, Gr(h->ix_bo), Pp, L, s), "db_o");
+    HIPCHK(launch_colsum(prec, h->dlogits, C, M * C, M, C, Gr(h->ix_bo), Pp, n, act, s), "db_o");
     // d(z) = dlogits W_o
-    g = GemmDesc{};
-    g.precision = prec; g.a_kc = 1; g.b_kc = 0; g.c_elem = h->Bn ? 1 : 0;
+    g = G();
+    g.a_kc = 1; g.b_kc = 0; g.c_elem = h->Bn ? 1 : 0;
     g.M = (int)M; g.N = F; g.K = C;
     g.A = h->dlogits; g.lda = C; g.sAi = M * C;
     g.B = W(h->ix_wo); g.ldb = F; g.sBi = Pp;
     g.C = h->Bn ? h->dz : (void*)h->dy; g.ldc = F; g.sCi = M * F;
-    g.groupsI = L; g.groupsD = 1;
     if (int rc = gemm(h, g, "dz GEMM")) return rc;
     if (h->Bn) {
-        g = GemmDesc{};
-        g.precision = prec; g.a_kc = 0; g.b_kc = 0; g.c_elem = 0;
+        g = G();
+        g.a_kc = 0; g.b_kc = 0; g.c_elem = 0;
         g.M = h->Bn; g.N = (int)DH; g.K = (int)M;
         g.A = h->dz; g.lda = h->Bn; g.sAi = M * h->Bn;
         g.B = top; g.ldb = DH; g.sBi = M * DH;
         g.C = Gr(h->ix_wp); g.ldc = DH; g.sCi = Pp;
-        g.groupsI = L; g.groupsD = 1;
         if (int rc = gemm(h, g, "dW_p GEMM")) return rc;
         if (int rc = mark(h, 5, 1)) return rc;
-        HIPCHK(launch_colsum(prec, h->dz, h->Bn, M * h->Bn, M, h->Bn, Gr(h->ix_bp), Pp, L, s), "db_p");
-        g = GemmDesc{};
-        g.precision = prec; g.a_kc = 1; g.b_kc = 0; g.c_elem = 0;
+        HIPCHK(launch_colsum(prec, h->dz, h->Bn, M * h->Bn, M, h->Bn, Gr(h->ix_bp), Pp, n, act, s), "db_p");
+        g = G();
+        g.a_kc = 1; g.b_kc = 0; g.c_elem = 0;
         g.M = (int)M; g.N = (int)DH; g.K = h->Bn;
         g.A = h->dz; g.lda = h->Bn; g.sAi = M * h->Bn;
         g.B = W(h->ix_wp); g.ldb = DH; g.sBi = Pp;
         g.C = h->dy; g.ldc = DH; g.sCi = M * DH;
-        g.groupsI = L; g.groupsD = 1;
         if (int rc = gemm(h, g, "dY GEMM")) return rc;
     }
     // ---- backward through the LSTM layers ----
@@ -430,7 +465,7 @@ int compute_gradients(adpsgd_handle* h, const float* at, const void* const* batc
         const void* in = l == 0 ? h->x0 : Y(l - 1);
         const int64_t ldin = l == 0 ? h->ldx : DH;
         RecDesc r{};
-        r.precision = prec; r.L = L; r.D = D; r.B = B; r.H = H; r.T = T;
+        r.precision = prec; r.L = n; r.lmap = act; r.direct = h->tune_rec_direct; r.D = D; r.B = B; r.H = H; r.T = T;
         r.gates = Gates(l); r.sGi = M * G4;
         r.c = Cb(l); r.sCi = M * DH;
         r.y = Y(l); r.sYi = M * DH;
@@ -441,25 +476,24 @@ int compute_gradients(adpsgd_handle* h, const float* at, const void* const* batc
         const int64_t dbrows = (int64_t)T * rec_backward_batch_tiles(B);
         r.dbp = h->dbp; r.sDBi = dbrows * G4;
         // per frame and (learner, direction): W_h once, da in (4 gates) and out, dY, 4 gates, c, c', dc in and out
-        if (int rc = mark(h, 3, T, 2.0 * B * H * 4 * H * (T - 1) * L * D,
-                          (double)T * L * D * (4.0 * H * H * esz + (double)B * H * (8 * esz + 4 + 16 + 8 + 8)))) return rc;
+        if (int rc = mark(h, 3, T, 2.0 * B * H * 4 * H * (T - 1) * n * D,
+                          (double)T * n * D * (4.0 * H * H * esz + (double)B * H * (8 * esz + 4 + 16 + 8 + 8)))) return rc;
         for (int t = 0; t < T; ++t) {
             r.step = t;
             HIPCHK(launch_rec_backward(r, s), "recurrent backward step");
         }
         // dW_x = da' x  (both directions at once: rows of W_x are [D][4H])
-        g = GemmDesc{};
-        g.precision = prec; g.a_kc = 0; g.b_kc = 0; g.c_elem = 0;
+        g = G();
+        g.a_kc = 0; g.b_kc = 0; g.c_elem = 0;
         g.M = (int)G4; g.N = (int)Il; g.K = (int)M;
         g.A = h->da; g.lda = G4; g.sAi = M * G4;
         g.B = in; g.ldb = ldin; g.sBi = M * ldin;
         g.C = Gr(h->ix_wx[l]); g.ldc = Il; g.sCi = Pp;
-        g.groupsI = L; g.groupsD = 1;
         if (int rc = gemm(h, g, "dW_x GEMM")) return rc;
         // dW_h[d] = da_d' h_{t'}: frames with a predecessor only (T-1 of them)
         if (T > 1) {
-            g = GemmDesc{};
-            g.precision = prec; g.a_kc = 0; g.b_kc = 0; g.c_elem = 0;
+            g = G();
+            g.a_kc = 0; g.b_kc = 0; g.c_elem = 0;
             g.M = 4 * H; g.N = H; g.K = (int)((int64_t)(T - 1) * B);
             // d = 0: da rows of frames 1..T-1 against h of frames 0..T-2
             // d = 1: da rows of frames 0..T-2 (columns 4H..) against h of frames 1..T-1 (columns H..)
@@ -467,25 +501,24 @@ int compute_gradients(adpsgd_handle* h, const float* at, const void* const* batc
             g.sAd = (int64_t)4 * H - (int64_t)B * G4;
             g.B = Y(l); g.ldb = DH; g.sBi = M * DH; g.sBd = (int64_t)B * DH + H;
             g.C = Gr(h->ix_wh[l]); g.ldc = H; g.sCi = Pp; g.sCd = (int64_t)4 * H * H;
-            g.groupsI = L; g.groupsD = D;
+            g.groupsD = D;
             if (int rc = gemm(h, g, "dW_h GEMM")) return rc;
         } else {
-            if (int rc = mark(h, 5, L)) return rc;
-            for (int i = 0; i < L; ++i)
-                HIPCHK(hipMemsetAsync(Gr(h->ix_wh[l]) + (size_t)i * Pp, 0, (size_t)G4 * H * 4, s), "zero dW_h");
+            // a single frame has no predecessor: dW_h = 0 (a fill kernel, so that the step holds no memset node)
+            if (int rc = mark(h, 5, 1)) return rc;
+            HIPCHK(launch_zero(Gr(h->ix_wh[l]), Pp, G4 * H, n, act, s), "zero dW_h");
         }
         // db = sum over the frames (and batch tiles) of the column sums the backward steps left behind
         if (int rc = mark(h, 5, 1)) return rc;
-        HIPCHK(launch_colsum(0, h->dbp, G4, dbrows * G4, dbrows, (int)G4, Gr(h->ix_b[l]), Pp, L, s), "db");
+        HIPCHK(launch_colsum(0, h->dbp, G4, dbrows * G4, dbrows, (int)G4, Gr(h->ix_b[l]), Pp, n, act, s), "db");
         if (l > 0) {
             // dY_{l-1} = da W_x  (sum over both directions: K = D*4H)
-            g = GemmDesc{};
-            g.precision = prec; g.a_kc = 1; g.b_kc = 0; g.c_elem = 0;
+            g = G();
+            g.a_kc = 1; g.b_kc = 0; g.c_elem = 0;
             g.M = (int)M; g.N = (int)DH; g.K = (int)G4;
             g.A = h->da; g.lda = G4; g.sAi = M * G4;
             g.B = W(h->ix_wx[l]); g.ldb = DH; g.sBi = Pp;
             g.C = h->dy; g.ldc = DH; g.sCi = M * DH;
-            g.groupsI = L; g.groupsD = 1;
             if (int rc = gemm(h, g, "dX GEMM")) return rc;
         }
     }
@@ -506,7 +539,7 @@ int adpsgd_workspace_bytes(const adpsgd_config* cfg, size_t* out) {
     return ADPSGD_OK;
 }
 
-int adpsgd_create(const adpsgd_config* cfg, void* dev_workspace, size_t bytes, void* hip_stream, adpsgd_t* out) {
+static int create_impl(const adpsgd_config* cfg, void* dev_workspace, size_t bytes, void* hip_stream, adpsgd_t* out) {
     std::string why;
     if (int rc = check_config(cfg, why)) return fail(rc, why);
     if (!out) return fail(ADPSGD_EINVAL, "out is NULL");
@@ -522,10 +555,16 @@ int adpsgd_create(const adpsgd_config* cfg, void* dev_workspace, size_t bytes, v
     h->k = 0; h->cur = 0; h->shadow_valid = false;
     hipStream_t s = h->stream;
     const size_t slab = (size_t)h->L * h->Ppad * 4;
-    hipError_t e = hipMemsetAsync(h->params[0], 0, slab, s);
+    void* mirror = nullptr;                       // pinned host word the status is copied to after every step
+    hipError_t e = hipHostMalloc(&mirror, 64, hipHostMallocDefault);
+    if (e != hipSuccess) { delete h; return hipfail(e, "pinned status word"); }
+    h->status_host = (volatile uint32_t*)mirror;
+    *h->status_host = 0u;
+    e = hipMemsetAsync(h->status, 0, 256, s);
+    if (e == hipSuccess) e = hipMemsetAsync(h->params[0], 0, slab, s);
     if (e == hipSuccess && h->tau == 1) e = hipMemsetAsync(h->params[1], 0, slab, s);
     if (e == hipSuccess && !h->flat) e = hipMemsetAsync(h->grads, 0, slab, s);
-    if (e != hipSuccess) { delete h; return hipfail(e, "clear models"); }
+    if (e != hipSuccess) { (void)hipHostFree(mirror); delete h; return hipfail(e, "clear models"); }
     if (cfg->init_scale > 0.f) {
         // same w_0 on every learner (Algorithm 1, input)
         std::vector<float> w0((size_t)h->P);
@@ -536,24 +575,37 @@ int adpsgd_create(const adpsgd_config* cfg, void* dev_workspace, size_t bytes, v
             for (int i = 0; i < h->L && e == hipSuccess; ++i)
                 e = hipMemcpyAsync(h->params[b] + (size_t)i * h->Ppad, w0.data(), (size_t)h->P * 4, hipMemcpyHostToDevice, s);
         if (e == hipSuccess) e = hipStreamSynchronize(s);
-        if (e != hipSuccess) { delete h; return hipfail(e, "initial model upload"); }
+        if (e != hipSuccess) { (void)hipHostFree(mirror); delete h; return hipfail(e, "initial model upload"); }
     } else {
         e = hipStreamSynchronize(s);
-        if (e != hipSuccess) { delete h; return hipfail(e, "stream sync"); }
+        if (e != hipSuccess) { (void)hipHostFree(mirror); delete h; return hipfail(e, "stream sync"); }
     }
     *out = h;
     return ADPSGD_OK;
 }
 
-int adpsgd_step(adpsgd_t h, const void* const* batch_ptrs, float lr) {
+int adpsgd_create(const adpsgd_config* cfg, void* dev_workspace, size_t bytes, void* hip_stream, adpsgd_t* out) {
+    try {
+        return create_impl(cfg, dev_workspace, bytes, hip_stream, out);
+    } catch (const std::bad_alloc&) {
+        return fail(ADPSGD_ENOMEM, "out of host memory");
+    } catch (const std::exception& ex) {
+        return fail(ADPSGD_EINVAL, std::string("unexpected failure: ") + ex.what());
+    } catch (...) {
+        return fail(ADPSGD_EINVAL, "unexpected failure");
+    }
+}
+
+static int step_impl(adpsgd_t h, const void* const* batch_ptrs, float lr) {
     if (!h || !batch_ptrs) return fail(ADPSGD_EINVAL, "NULL argument");
+    if (int rc = status_error(h)) return rc;
     const int L = h->L;
     int32_t order[ADPSGD_MAX_LEARNERS], partner[ADPSGD_MAX_LEARNERS], active[ADPSGD_MAX_LEARNERS];
     make_schedule(h->cfg.pattern, h->cfg.seed, h->cfg.straggler_p, L, h->k, order, partner, active);
     const int nptr = h->flat ? L : 2 * L;
     for (int i = 0; i < nptr; ++i) {
         const int li = h->flat ? i : i / 2;
-        if (!batch_ptrs[i] && (active[li] || !h->flat)) return fail(ADPSGD_EINVAL, "batch_ptrs[" + std::to_string(i) + "] is NULL");
+        if (!batch_ptrs[i] && active[li]) return fail(ADPSGD_EINVAL, "batch_ptrs[" + std::to_string(i) + "] is NULL");
     }
     float* xk = h->params[h->cur];
     float* xnext = h->tau == 1 ? h->params[1 - h->cur] : xk;
@@ -565,7 +617,7 @@ int adpsgd_step(adpsgd_t h, const void* const* batch_ptrs, float lr) {
     } else {
         // the gradient is evaluated at x^{k-tau}: the other buffer holds x^{k-1}
         const float* at = h->tau == 1 ? h->params[1 - h->cur] : xk;
-        if (int rc = compute_gradients(h, at, batch_ptrs)) return rc;
+        if (int rc = compute_gradients(h, at, batch_ptrs, active)) return rc;
         for (int i = 0; i < L; ++i) u.g[i] = h->grads + (size_t)i * h->Ppad;
     }
     for (int i = 0; i < L; ++i) { u.partner[i] = (int16_t)partner[i]; u.active[i] = (int16_t)active[i]; u.order[i] = (int16_t)order[i]; }
@@ -580,10 +632,24 @@ int adpsgd_step(adpsgd_t h, const void* const* batch_ptrs, float lr) {
     }
     HIPCHK(launch_update(u, h->stream), "mix + update");
     if (int rc = mark(h, -1)) return rc;
+    if (!h->flat)    // what the kernels of this step have reported reaches the host with the stream, without a wait
+        HIPCHK(hipMemcpyAsync((void*)h->status_host, h->status, 4, hipMemcpyDeviceToHost, h->stream), "status copy");
     if (h->tau == 1) h->cur = 1 - h->cur;
     if (u.shadow) h->shadow_valid = true;
     h->k += 1;
     return ADPSGD_OK;
+}
+
+int adpsgd_step(adpsgd_t h, const void* const* batch_ptrs, float lr) {
+    try {
+        return step_impl(h, batch_ptrs, lr);
+    } catch (const std::bad_alloc&) {
+        return fail(ADPSGD_ENOMEM, "out of host memory");
+    } catch (const std::exception& ex) {
+        return fail(ADPSGD_EINVAL, std::string("unexpected failure: ") + ex.what());
+    } catch (...) {
+        return fail(ADPSGD_EINVAL, "unexpected failure");
+    }
 }
 
 float* adpsgd_params(adpsgd_t h, int i) {
@@ -610,7 +676,14 @@ int adpsgd_losses(adpsgd_t h, float* host_out) {
     if (!h || !host_out || h->flat) return fail(ADPSGD_EINVAL, "bad argument");
     HIPCHK(hipMemcpyAsync(host_out, h->loss, (size_t)h->L * 4, hipMemcpyDeviceToHost, h->stream), "loss copy");
     HIPCHK(hipStreamSynchronize(h->stream), "stream sync");
-    return ADPSGD_OK;
+    return status_error(h);
+}
+
+int adpsgd_status(adpsgd_t h) {
+    if (!h) return fail(ADPSGD_EINVAL, "NULL handle");
+    if (!h->flat) HIPCHK(hipMemcpyAsync((void*)h->status_host, h->status, 4, hipMemcpyDeviceToHost, h->stream), "status copy");
+    HIPCHK(hipStreamSynchronize(h->stream), "stream sync");
+    return status_error(h);
 }
 
 int64_t adpsgd_param_count(adpsgd_t h) { return h ? h->P : -1; }
@@ -690,6 +763,10 @@ int adpsgd_profile(adpsgd_t h, float* host_ms, int32_t* host_launches, double* h
 void adpsgd_destroy(adpsgd_t h) {
     if (!h) return;
     for (hipEvent_t e : h->prof.ev) (void)hipEventDestroy(e);
+    if (h->status_host) {
+        (void)hipStreamSynchronize(h->stream);       // the last status copy may still be in flight
+        (void)hipHostFree((void*)h->status_host);
+    }
     delete h;
 }
 
@@ -698,9 +775,11 @@ const char* adpsgd_last_error(void) { return g_err.c_str(); }
 int adpsgd_gemm(int precision, int a_kmajor, int b_kmajor, int c_is_elem, int M, int N, int K,
                 const void* A, int64_t lda, int64_t strideA, const void* B, int64_t ldb, int64_t strideB,
                 void* C, int64_t ldc, int64_t strideC, const float* bias, int64_t strideBias,
-                int groups, void* hip_stream) {
+                int groups, int tile_config, void* hip_stream) {
     if (!A || !B || !C || (precision != 0 && precision != 1)) return fail(ADPSGD_EINVAL, "bad argument");
+    if (groups < 1 || groups > ADPSGD_MAX_LEARNERS) return fail(ADPSGD_EINVAL, "groups must be in 1..128");
     GemmDesc g{};
+    g.tile = tile_config; g.lmap.identity();
     g.precision = precision; g.a_kc = a_kmajor != 0; g.b_kc = b_kmajor != 0; g.c_elem = c_is_elem != 0;
     g.M = M; g.N = N; g.K = K;
     g.A = A; g.lda = lda; g.sAi = strideA;
@@ -714,12 +793,21 @@ int adpsgd_gemm(int precision, int a_kmajor, int b_kmajor, int c_is_elem, int M,
     return ADPSGD_OK;
 }
 
-int adpsgd_gemm_set_variant(int variant) {
-    if (variant == 100 || variant == 101) { set_rec_dma(variant - 100); return ADPSGD_OK; }
-    if (variant >= 300 && variant <= 316) { g_rec_split = variant - 300; return ADPSGD_OK; }
-    if (variant != -1 && variant != 0 && variant != 5 && (variant < 11 || variant > 13)) return fail(ADPSGD_EINVAL, "variant must be -1, 0, 5, 11, 12 or 13");
-    set_gemm_variant(variant);
-    return ADPSGD_OK;
+int adpsgd_set_tuning(adpsgd_t h, int key, int value) {
+    if (!h) return fail(ADPSGD_EINVAL, "NULL handle");
+    switch (key) {
+        case ADPSGD_TUNE_GEMM_TILE:
+            if (value != -1 && value != 0 && value != 5 && (value < 11 || value > 13))
+                return fail(ADPSGD_EINVAL, "GEMM tile configuration must be -1, 0, 5, 11, 12 or 13");
+            h->tune_gemm_tile = value; return ADPSGD_OK;
+        case ADPSGD_TUNE_REC_DIRECT:
+            if (value != 0 && value != 1) return fail(ADPSGD_EINVAL, "0 or 1");
+            h->tune_rec_direct = value; return ADPSGD_OK;
+        case ADPSGD_TUNE_REC_FWD_GROUPS:
+            if (value < 0 || value > ADPSGD_MAX_LEARNERS) return fail(ADPSGD_EINVAL, "0 (automatic) or 1..128 groups");
+            h->tune_rec_fwd_groups = value; return ADPSGD_OK;
+        default: return fail(ADPSGD_EINVAL, "unknown tuning key");
+    }
 }
 
 }  // extern "C"

@@ -6,6 +6,7 @@
 namespace adpsgd {
 
 struct StageArgs {
+    LearnerMap lmap;
     int64_t rows; int I, ldx;
     void* x0; int64_t sX0; int32_t* y; int64_t sY;
     const float* feats[128];
@@ -14,7 +15,7 @@ struct StageArgs {
 
 template <typename T>
 __global__ __launch_bounds__(256) void stage_kernel(StageArgs p) {
-    const int li = blockIdx.y;
+    const int li = p.lmap.idx[blockIdx.y];
     const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
     const int64_t n = p.rows * p.ldx;
     if (idx < n) {
@@ -27,9 +28,11 @@ __global__ __launch_bounds__(256) void stage_kernel(StageArgs p) {
 }
 
 hipError_t launch_stage(const StageDesc& d, hipStream_t s) {
+    if (d.L < 1 || d.L > 128) return hipErrorInvalidValue;
     StageArgs a;
+    a.lmap = d.lmap;
     a.rows = d.rows; a.I = d.I; a.ldx = d.ldx; a.x0 = d.x0; a.sX0 = d.sX0; a.y = d.y; a.sY = d.sY;
-    for (int i = 0; i < 128; ++i) { a.feats[i] = i < d.L ? d.feats[i] : nullptr; a.labels[i] = i < d.L ? d.labels[i] : nullptr; }
+    for (int i = 0; i < 128; ++i) { a.feats[i] = d.feats[i]; a.labels[i] = d.labels[i]; }     // indexed by learner
     dim3 grid((unsigned)((d.rows * d.ldx + 255) / 256), (unsigned)d.L);
     if (d.precision == 0) hipLaunchKernelGGL(stage_kernel<float>, grid, dim3(256), 0, s, a);
     else hipLaunchKernelGGL(stage_kernel<bf16_t>, grid, dim3(256), 0, s, a);
@@ -85,14 +88,22 @@ __device__ inline void lse_merge_(float& m, float& s, float m2, float s2) {
     m = mm;
 }
 
+// Label of a frame.  A label outside [0, C) is reported through the status word (the host turns it
+// into an error) and clamped, so that it is never used as an index.
+__device__ inline int checked_label_(const SoftmaxDesc& p, int li, int64_t row) {
+    const int y = p.y[li * p.sYi + row];
+    if (y >= 0 && y < p.C) return y;
+    if (threadIdx.x == 0 && p.status) atomicOr(p.status, kStatusBadLabel);
+    return y < 0 ? 0 : p.C - 1;
+}
+
 template <typename T>
 __global__ __launch_bounds__(256) void softmax_ce_kernel(SoftmaxDesc p) {
-    const int li = blockIdx.y;
+    const int li = p.lmap.idx[blockIdx.y];
     const int64_t row = blockIdx.x;
     const float* z = p.logits + li * p.sLi + row * p.C;
     T* dz = (T*)p.dlogits + li * p.sDi + row * p.C;
-    int y = p.y[li * p.sYi + row];
-    y = y < 0 ? 0 : (y >= p.C ? p.C - 1 : y);      // labels outside [0, C) are clamped, never dereferenced
+    const int y = checked_label_(p, li, row);
     float m = -INFINITY, s = 0.f;
     for (int c = threadIdx.x; c < p.C; c += 256) {
         const float v = z[c];
@@ -119,8 +130,13 @@ __global__ __launch_bounds__(256) void softmax_ce_kernel(SoftmaxDesc p) {
     if (threadIdx.x == 0) p.row_loss[li * p.rows + row] = -((z[y] - m) - logf(s));
 }
 
-__global__ __launch_bounds__(256) void loss_reduce_kernel(const float* row_loss, int64_t rows, float* loss) {
+// One workgroup per learner of the handle; a learner that took no part in the iteration reports 0.
+__global__ __launch_bounds__(256) void loss_reduce_kernel(const float* row_loss, int64_t rows, float* loss, SoftmaxDesc p) {
     const int li = blockIdx.x;
+    if (!((p.active_bits[li >> 5] >> (li & 31)) & 1u)) {
+        if (threadIdx.x == 0) loss[li] = 0.f;
+        return;
+    }
     float s = 0.f;
     for (int64_t r = threadIdx.x; r < rows; r += 256) s += row_loss[li * rows + r];
     __shared__ float sh[256];
@@ -140,13 +156,12 @@ typedef uint32_t vu2_t __attribute__((ext_vector_type(2)));
 
 template <typename T, int NV, int NT = 256>
 __global__ __launch_bounds__(NT) void softmax_ce_row_kernel(SoftmaxDesc p) {
-    const int li = blockIdx.y;
+    const int li = p.lmap.idx[blockIdx.y];
     const int64_t row = blockIdx.x;
     const float4* z4 = (const float4*)(p.logits + li * p.sLi + row * p.C);
     T* dz = (T*)p.dlogits + li * p.sDi + row * p.C;
     const int C4 = p.C >> 2;
-    int y = p.y[li * p.sYi + row];
-    y = y < 0 ? 0 : (y >= p.C ? p.C - 1 : y);
+    const int y = checked_label_(p, li, row);
     float4 v[NV];
     float m = -INFINITY;
 #pragma unroll
@@ -221,11 +236,12 @@ static void launch_softmax_t(const SoftmaxDesc& d, hipStream_t s) {
 }
 
 hipError_t launch_softmax_ce(const SoftmaxDesc& d, hipStream_t s) {
+    if (d.L < 1 || d.L > d.L_all || d.L_all > 128) return hipErrorInvalidValue;
     if (d.precision == 0) launch_softmax_t<float>(d, s);
     else launch_softmax_t<bf16_t>(d, s);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(loss_reduce_kernel, dim3((unsigned)d.L), dim3(256), 0, s, d.row_loss, d.rows, d.loss);
+    hipLaunchKernelGGL(loss_reduce_kernel, dim3((unsigned)d.L_all), dim3(256), 0, s, d.row_loss, d.rows, d.loss, d);
     return hipGetLastError();
 }
 
@@ -233,8 +249,8 @@ hipError_t launch_softmax_ce(const SoftmaxDesc& d, hipStream_t s) {
 // Workgroup = 64 columns x 4 row slices; fixed summation order (deterministic).
 template <typename T>
 __global__ __launch_bounds__(256) void colsum_kernel(const T* in, int64_t ld, int64_t sIi, int64_t rows, int N,
-                                                     float* out, int64_t sOi) {
-    const int li = blockIdx.y;
+                                                     float* out, int64_t sOi, LearnerMap lmap) {
+    const int li = lmap.idx[blockIdx.y];
     const int col = blockIdx.x * 64 + (threadIdx.x & 63);
     const int slice = threadIdx.x >> 6;
     const T* src = in + li * sIi;
@@ -257,12 +273,26 @@ __global__ __launch_bounds__(256) void colsum_kernel(const T* in, int64_t ld, in
 }
 
 hipError_t launch_colsum(int precision, const void* in, int64_t ld, int64_t sIi, int64_t rows, int N,
-                         float* out, int64_t sOi, int L, hipStream_t s) {
+                         float* out, int64_t sOi, int L, const LearnerMap& lmap, hipStream_t s) {
+    if (L < 1 || L > 128) return hipErrorInvalidValue;
     dim3 grid((unsigned)((N + 63) / 64), (unsigned)L);
     if (precision == 0)
-        hipLaunchKernelGGL(colsum_kernel<float>, grid, dim3(256), 0, s, (const float*)in, ld, sIi, rows, N, out, sOi);
+        hipLaunchKernelGGL(colsum_kernel<float>, grid, dim3(256), 0, s, (const float*)in, ld, sIi, rows, N, out, sOi, lmap);
     else
-        hipLaunchKernelGGL(colsum_kernel<bf16_t>, grid, dim3(256), 0, s, (const bf16_t*)in, ld, sIi, rows, N, out, sOi);
+        hipLaunchKernelGGL(colsum_kernel<bf16_t>, grid, dim3(256), 0, s, (const bf16_t*)in, ld, sIi, rows, N, out, sOi, lmap);
+    return hipGetLastError();
+}
+
+__global__ __launch_bounds__(256) void zero_kernel(float* dst, int64_t sDi, int64_t n, LearnerMap lmap) {
+    float* p = dst + lmap.idx[blockIdx.y] * sDi;
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256) p[i] = 0.f;
+}
+
+hipError_t launch_zero(float* dst, int64_t sDi, int64_t n, int L, const LearnerMap& lmap, hipStream_t s) {
+    if (L < 1 || L > 128 || n < 1) return hipErrorInvalidValue;
+    int64_t blocks = (n + 255) / 256;
+    if (blocks > 4096) blocks = 4096;
+    hipLaunchKernelGGL(zero_kernel, dim3((unsigned)blocks, (unsigned)L), dim3(256), 0, s, dst, sDi, n, lmap);
     return hipGetLastError();
 }
 

@@ -189,7 +189,7 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_kernel(GemmDesc p) {
     const int tiles_m = (p.M + Core::BM - 1) / Core::BM, tiles_n = (p.N + Core::BN - 1) / Core::BN;
     int grp, tm, tn;
     map_tile(blockIdx.x, gridDim.x, tiles_m, tiles_n, grp, tm, tn);
-    const int gi = grp / p.groupsD, gd = grp % p.groupsD;
+    const int gi = p.lmap.idx[grp / p.groupsD], gd = grp % p.groupsD;
     const int m0 = tm * Core::BM, n0 = tn * Core::BN;
     const T* A = (const T*)p.A + gi * p.sAi + gd * p.sAd;
     const T* B = (const T*)p.B + gi * p.sBi + gd * p.sBd;
@@ -220,7 +220,7 @@ __global__ __launch_bounds__(64 * WM * WN, (WM * WN == 4 && FM * FN == 8) ? 2 : 
     const int tiles_m = (p.M + Core::BM - 1) / Core::BM, tiles_n = (p.N + Core::BN - 1) / Core::BN;
     int grp, tm, tn;
     map_tile(blockIdx.x, gridDim.x, tiles_m, tiles_n, grp, tm, tn);
-    const int gi = grp / p.groupsD, gd = grp % p.groupsD;
+    const int gi = p.lmap.idx[grp / p.groupsD], gd = grp % p.groupsD;
     const int m0 = tm * Core::BM, n0 = tn * Core::BN;
     const T* A = (const T*)p.A + gi * p.sAi + gd * p.sAd;
     const T* B = (const T*)p.B + gi * p.sBi + gd * p.sBd;
@@ -282,16 +282,14 @@ static hipError_t launch_dma(const GemmDesc& d, hipStream_t s) {
     }
 }
 
-static int g_variant = -1;   // tuning knob: forces a tile configuration (-1 = automatic)
-void set_gemm_variant(int v) { g_variant = v; }
-
 static bool aligned_to(const void* p, int64_t ld, int64_t s1, int64_t s2, int esz, int bytes) {
     return ((uintptr_t)p % bytes == 0) && ((ld * esz) % bytes == 0) && ((s1 * esz) % bytes == 0) &&
            ((s2 * esz) % bytes == 0);
 }
 
 hipError_t launch_gemm(const GemmDesc& d, hipStream_t s) {
-    if (d.M < 1 || d.N < 1 || d.K < 1 || d.groupsI < 1 || d.groupsD < 1) return hipErrorInvalidValue;
+    if (d.M < 1 || d.N < 1 || d.K < 1 || d.groupsI < 1 || d.groupsI > 128 || d.groupsD < 1) return hipErrorInvalidValue;
+    if (d.tile != -1 && d.tile != 0 && d.tile != 5 && (d.tile < 11 || d.tile > 13)) return hipErrorInvalidValue;
     // one-dimensional grid over all tiles of all groups (smallest tile 128 x 128)
     if ((int64_t)((d.M + 127) / 128) * ((d.N + 127) / 128) * d.groupsI * d.groupsD > 0x7fffffff) return hipErrorInvalidValue;
     const int esz = d.precision ? 2 : 4;
@@ -303,7 +301,7 @@ hipError_t launch_gemm(const GemmDesc& d, hipStream_t s) {
     if (d.a_kc && !aligned_to(d.A, d.lda, d.sAi, d.sAd, esz, 16)) wide = false;
     if (d.b_kc && !aligned_to(d.B, d.ldb, d.sBi, d.sBd, esz, 16)) wide = false;
     if (!wide) return launch_layout<bf16_t, 2, 2, 2, 2, 8, 64>(d, s);
-    int v = g_variant;
+    int v = d.tile;
     if (v < 0) {
         // 256x256 tiles once there are enough of them to fill the 256 CUs
         const int64_t big_tiles = (int64_t)((d.M + 255) / 256) * ((d.N + 255) / 256) * d.groupsI * d.groupsD;

@@ -4,9 +4,17 @@
 
 namespace adpsgd {
 
+// Compacted list of the learners a launch works on: entry j of the launch is learner idx[j].
+// Stragglers (Section IV-D: a learner that sits an iteration out) are left out of every launch
+// of the gradient phase this way; without stragglers it is the identity.
+struct LearnerMap {
+    uint8_t idx[128];
+    void identity() { for (int i = 0; i < 128; ++i) idx[i] = (uint8_t)i; }
+};
+
 // ---- grouped GEMM  C[z] = A[z] * B[z]' (+ bias) ------------------------------
-// Group z = i*groupsD + d; operand X of group z starts at X + i*sXi + d*sXd
-// (strides in elements).
+// Group z = j*groupsD + d works on learner i = lmap.idx[j]; operand X of it starts at
+// X + i*sXi + d*sXd (strides in elements).
 struct GemmDesc {
     int precision;            // 0 fp32 operands, 1 bf16 operands
     int a_kc, b_kc;           // operand stored K-contiguous ([rows][K]) or not ([K][rows])
@@ -17,11 +25,12 @@ struct GemmDesc {
     void* C; int64_t ldc, sCi, sCd;
     const float* bias; int64_t sBiasI, sBiasD;
     int groupsI, groupsD;
+    int tile;                 // tile configuration (see gemm.hip): -1 automatic, or 0, 5, 11, 12, 13
+    LearnerMap lmap;
 };
 // Returns hipSuccess, or hipErrorInvalidValue when the operands do not meet the
 // alignment rules (rows and strides multiples of 4 elements).
 hipError_t launch_gemm(const GemmDesc& d, hipStream_t s);
-void set_gemm_variant(int v);
 
 // ---- fused mixing + SGD update ------------------------------------------------
 struct UpdateDesc {
@@ -48,7 +57,8 @@ hipError_t launch_consensus(const float* x, int64_t stride, int L, int64_t P, do
 
 // ---- LSTM gradient pieces -------------------------------------------------------
 struct StageDesc {             // copy / cast the minibatches into the workspace
-    int L, precision;
+    int L, precision;          // L: learners of this launch (entries of lmap)
+    LearnerMap lmap;
     int64_t rows;              // T*B
     int I, ldx;                // feature dim and padded row stride of the staged copy
     const float* feats[128];
@@ -64,7 +74,9 @@ hipError_t launch_pad_rows_bf16(const float* src, int64_t sS, bf16_t* dst, int64
 
 struct RecDesc {               // one time step of one layer, all learners and directions
     int precision;
-    int L, D, B, H, T;
+    int L, D, B, H, T;         // L: learners of this launch (entries of lmap)
+    LearnerMap lmap;
+    int direct;                // 0: never use the direct-to-LDS kernels (tuning)
     int step;                  // processing step 0..T-1 (frame = step, or T-1-step for d = 1)
     // forward: gates buffer holds W_x x + b on entry, the activated gates on exit
     float* gates; int64_t sGi;           // [L][T*B][D*4H] fp32
@@ -83,10 +95,17 @@ struct RecDesc {               // one time step of one layer, all learners and d
 int rec_backward_batch_tiles(int B);
 hipError_t launch_rec_forward(const RecDesc& d, hipStream_t s);
 hipError_t launch_rec_backward(const RecDesc& d, hipStream_t s);
-void set_rec_dma(int on);
+
+// Bits of the device-side status word of a handle (0 = fine).
+constexpr uint32_t kStatusBadLabel = 1u;       // a label outside [0, classes) was met (and clamped)
+constexpr uint32_t kStatusWaitExpired = 2u;    // a bounded wait between workgroups ran out
 
 struct SoftmaxDesc {
-    int precision, L;
+    int precision, L;          // L: learners of this launch (entries of lmap)
+    LearnerMap lmap;
+    int L_all;                 // all learners of the handle (loss[] has this many entries)
+    uint32_t active_bits[4];   // bit i: learner i takes part; the loss of the others is reported as 0
+    uint32_t* status;          // device status word: kStatusBadLabel is or-ed in
     int64_t rows; int C;
     const float* logits; int64_t sLi;    // [L][rows][C]
     const int32_t* y; int64_t sYi;
@@ -96,8 +115,10 @@ struct SoftmaxDesc {
 };
 hipError_t launch_softmax_ce(const SoftmaxDesc& d, hipStream_t s);
 
-// out[z][n] = sum_m in[z][m][n]   (bias gradients)
+// out[z][n] = sum_m in[z][m][n]   (bias gradients), z = lmap.idx[0..L)
 hipError_t launch_colsum(int precision, const void* in, int64_t ld, int64_t sIi, int64_t rows, int N,
-                         float* out, int64_t sOi, int L, hipStream_t s);
+                         float* out, int64_t sOi, int L, const LearnerMap& lmap, hipStream_t s);
+// dst[z][0..n) = 0 for z = lmap.idx[0..L)  (a fill kernel, not a memset node: safe under stream capture)
+hipError_t launch_zero(float* dst, int64_t sDi, int64_t n, int L, const LearnerMap& lmap, hipStream_t s);
 
 }  // namespace adpsgd

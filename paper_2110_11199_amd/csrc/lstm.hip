@@ -205,7 +205,7 @@ __global__ __launch_bounds__(256) void rec_forward_kernel(RecDesc p) {
     typedef GemmCore<T, KcSrc<T>, GateSrc<T>, WM, WN, 1, 4, VB> Core;
     __shared__ __attribute__((aligned(16))) char lds[Core::LDS_BYTES];
     const int D = p.D, H = p.H, B = p.B;
-    const int li = blockIdx.x / D, d = blockIdx.x % D;      // groups on x: the tiles of one (learner, direction) share an XCD and its L2
+    const int li = p.lmap.idx[blockIdx.x / D], d = blockIdx.x % D;      // groups on x: the tiles of one (learner, direction) share an XCD and its L2
     const int t = d == 0 ? p.step : p.T - 1 - p.step;
     const int tp = d == 0 ? t - 1 : t + 1;
     const int u0 = blockIdx.y * (32 * WN), b0 = blockIdx.z * (32 * WM);
@@ -230,7 +230,7 @@ __global__ __launch_bounds__(256) void rec_backward_kernel(RecDesc p) {
     typedef GemmCore<T, KcSrc<T>, McSrc<T>, WM, WN, 1, FN, VB> Core;
     __shared__ __attribute__((aligned(16))) char lds[Core::LDS_BYTES];
     const int D = p.D, H = p.H, B = p.B;
-    const int li = blockIdx.x / D, d = blockIdx.x % D;      // groups on x: the tiles of one (learner, direction) share an XCD and its L2
+    const int li = p.lmap.idx[blockIdx.x / D], d = blockIdx.x % D;      // groups on x: the tiles of one (learner, direction) share an XCD and its L2
     const int t = d == 0 ? p.T - 1 - p.step : p.step;     // reverse of the forward processing order
     const int tn = d == 0 ? t + 1 : t - 1;                 // frame handled by the previous launch
     const int tp = d == 0 ? t - 1 : t + 1;                 // frame the forward pass processed before t
@@ -267,7 +267,7 @@ __global__ __launch_bounds__(256) void rec_forward_dma_kernel(RecDesc p) {
     typedef GemmDma<T, KcSrc<T>, GateSrc<T>, WM, WN, 1, 4, SB, NS> Core;
     __shared__ __attribute__((aligned(1024))) char lds[Core::LDS_BYTES];
     const int D = p.D, H = p.H, B = p.B;
-    const int li = blockIdx.x / D, d = blockIdx.x % D;      // groups on x: the tiles of one (learner, direction) share an XCD and its L2
+    const int li = p.lmap.idx[blockIdx.x / D], d = blockIdx.x % D;      // groups on x: the tiles of one (learner, direction) share an XCD and its L2
     const int t = d == 0 ? p.step : p.T - 1 - p.step;
     const int tp = d == 0 ? t - 1 : t + 1;
     const int u0 = blockIdx.y * (32 * WN), b0 = blockIdx.z * (32 * WM);
@@ -294,7 +294,7 @@ __global__ __launch_bounds__(64 * WM * WN) void rec_backward_dma_kernel(RecDesc 
     typedef GemmDma<T, KcSrc<T>, McSrc<T>, WM, WN, 1, FN, SB, NS> Core;
     __shared__ __attribute__((aligned(1024))) char lds[Core::LDS_BYTES];
     const int D = p.D, H = p.H, B = p.B;
-    const int li = blockIdx.x / D, d = blockIdx.x % D;      // groups on x: the tiles of one (learner, direction) share an XCD and its L2
+    const int li = p.lmap.idx[blockIdx.x / D], d = blockIdx.x % D;      // groups on x: the tiles of one (learner, direction) share an XCD and its L2
     const int t = d == 0 ? p.T - 1 - p.step : p.step;
     const int tn = d == 0 ? t + 1 : t - 1;
     const int tp = d == 0 ? t - 1 : t + 1;
@@ -352,16 +352,13 @@ static hipError_t bwd_t(const RecDesc& d, hipStream_t s) {
 int rec_backward_batch_tiles(int B) { return B > 64 ? (B + 127) / 128 : B > 32 ? (B + 63) / 64 : (B + 31) / 32; }
 
 static bool rec_ok(const RecDesc& d) {
-    return d.L >= 1 && d.D >= 1 && d.D <= 2 && d.B >= 1 && d.H >= 4 && d.H % 4 == 0 && d.T >= 1 &&
+    return d.L >= 1 && d.L <= 128 && d.D >= 1 && d.D <= 2 && d.B >= 1 && d.H >= 4 && d.H % 4 == 0 && d.T >= 1 &&
            d.step >= 0 && d.step < d.T;
 }
 
-static int g_rec_dma = 1;    // tuning knob: 0 disables the direct-to-LDS kernels
-void set_rec_dma(int on) { g_rec_dma = on; }
-
 static bool dma_ok(const RecDesc& d) {
     // whole stages, and 16-byte aligned rows of every operand the direct loads touch
-    return g_rec_dma && d.precision == 1 && d.H % 64 == 0 && d.B > 32 && (uintptr_t)d.wh % 16 == 0 && d.sWi % 8 == 0 &&
+    return d.direct && d.precision == 1 && d.H % 64 == 0 && d.B > 32 && (uintptr_t)d.wh % 16 == 0 && d.sWi % 8 == 0 &&
            d.sWd % 8 == 0 && (uintptr_t)d.y % 16 == 0 && d.sYi % 8 == 0 && (uintptr_t)d.da % 16 == 0 && d.sDAi % 8 == 0;
 }
 

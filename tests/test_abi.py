@@ -46,7 +46,7 @@ def test_config_validation_and_workspace_size():
     n = Bd.adpsgd_workspace_bytes(ok)
     assert n > 4 * 33380 * 4 * 2 and n % 256 == 0
     flat = Bd.make_config(64, Bd.RANDOM_RING, flat_params=135_000_000, straggler_p=0.1)
-    scratch = 16640                     # 2049 doubles of the consensus-distance reduction, rounded to 256 bytes
+    scratch = 16640 + 256               # 2049 doubles of the consensus-distance reduction, rounded to 256 bytes; the status word
     assert Bd.adpsgd_workspace_bytes(flat) == 64 * 135_000_000 * 4 + scratch
     d1d = Bd.make_config(64, Bd.D1D, flat_params=1000)
     assert Bd.adpsgd_workspace_bytes(d1d) == 2 * 64 * 1024 * 4 + scratch     # two model buffers, padded stride
@@ -58,7 +58,8 @@ def test_config_validation_and_workspace_size():
            Bd.make_config(4, 0, input_dim=39, hidden=64, layers=1, classes=100, batch=4, frames=20),
            Bd.make_config(4, 0, input_dim=40, hidden=64, layers=0, classes=100, batch=4, frames=20),
            Bd.make_config(4, 0, flat_params=8, precision=2), Bd.make_config(4, 0, flat_params=8, mix=3),
-           Bd.make_config(4, 1, flat_params=8, mix=Bd.MIX_TRI, straggler_p=0.1)]
+           Bd.make_config(4, 1, flat_params=8, mix=Bd.MIX_TRI, straggler_p=0.1),
+           Bd.make_config(1, 0, flat_params=8, mix=Bd.MIX_TRI), Bd.make_config(2, 1, flat_params=8, mix=Bd.MIX_TRI)]
     assert Bd.adpsgd_workspace_bytes(Bd.make_config(4, 0, flat_params=8, mix=Bd.MIX_TRI)) > 0     # ring neighbours, weights 1/3
     # the synchronous baseline: one model buffer, the all-learner mean by default
     assert Bd.adpsgd_workspace_bytes(Bd.make_config(64, Bd.SDPSGD, flat_params=1000)) == 64 * 1024 * 4 + scratch
@@ -74,3 +75,11 @@ def test_create_rejects_a_missing_workspace():
     with pytest.raises(Bd.AdpsgdError) as ei:
         Bd.adpsgd_create(cfg, None, 0, None)
     assert ei.value.code == Bd.ENOMEM
+
+
+def test_argument_checks_that_need_no_gpu():
+    # every rejection below happens before any HIP call
+    for call in (lambda: Bd.adpsgd_set_tuning(None, Bd.TUNE_GEMM_TILE, 12), lambda: Bd.adpsgd_status(None)):
+        with pytest.raises(Bd.AdpsgdError) as ei:
+            call()
+        assert ei.value.code == Bd.EINVAL

@@ -7,7 +7,7 @@ from tests.gpu_util import rel_err, to_bf16_bits, from_bf16_bits
 pytestmark = pytest.mark.gpu
 
 
-def _run(prec, a_k, b_k, c_elem, M, N, K, groups, bias, pad=0, seed=0):
+def _run(prec, a_k, b_k, c_elem, M, N, K, groups, bias, pad=0, seed=0, tile=-1):
     import torch
     from paper_2110_11199_amd import binding as Bd
     r = np.random.default_rng(seed)
@@ -30,7 +30,7 @@ def _run(prec, a_k, b_k, c_elem, M, N, K, groups, bias, pad=0, seed=0):
     dbias = torch.from_numpy(bv).to(dev) if bias else None
     Bd.adpsgd_gemm(prec, a_k, b_k, c_elem, M, N, K, dA.data_ptr(), lda, dA[0].numel(), dB.data_ptr(), ldb,
                    dB[0].numel(), dC.data_ptr(), ldc, M * ldc, dbias.data_ptr() if bias else None, N, groups,
-                   torch.cuda.current_stream().cuda_stream)
+                   torch.cuda.current_stream().cuda_stream, tile_config=tile)
     torch.cuda.synchronize()
     got = dC.cpu().numpy()
     if prec and c_elem:
@@ -96,13 +96,8 @@ def test_gemm_bf16_forced_large_tile_configurations(variant, a_k, b_k, K):
     # the pipelined main loops (11: 64-k stages, 12 and 13: 32-k stages) have separate code for their first
     # stages, their steady state and their last stages: 1 .. 4 and 2 .. 8 stages here, in every operand layout
     # (the automatic choice uses 11 and 13 for K-contiguous operands only, 12 for the others)
-    from paper_2110_11199_amd import binding as Bd
     print("gemm bf16 forced configuration", variant, a_k, b_k, K, flush=True)
-    Bd.adpsgd_gemm_set_variant(variant)
-    try:
-        assert _run(1, a_k, b_k, 0, 300, 264, K, 3, True, pad=8) < 2e-6
-    finally:
-        Bd.adpsgd_gemm_set_variant(-1)
+    assert _run(1, a_k, b_k, 0, 300, 264, K, 3, True, pad=8, tile=variant) < 2e-6
 
 
 def test_gemm_rejects_misaligned_rows():
@@ -112,3 +107,8 @@ def test_gemm_rejects_misaligned_rows():
     with pytest.raises(Bd.AdpsgdError) as ei:
         Bd.adpsgd_gemm(0, 1, 1, 0, 8, 8, 8, t.data_ptr(), 10, 0, t.data_ptr(), 8, 0, t.data_ptr(), 8, 0, None, 0, 1, None)
     assert ei.value.code == Bd.EINVAL
+    for bad_tile, groups in ((7, 1), (-1, 0), (-1, 129)):     # unknown tile configuration, group counts out of range
+        with pytest.raises(Bd.AdpsgdError) as ei:
+            Bd.adpsgd_gemm(0, 1, 1, 0, 8, 8, 8, t.data_ptr(), 8, 0, t.data_ptr(), 8, 0, t.data_ptr(), 8, 0, None, 0, groups, None,
+                           tile_config=bad_tile)
+        assert ei.value.code == Bd.EINVAL

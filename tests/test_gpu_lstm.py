@@ -87,20 +87,27 @@ def test_gradient_matches_oracle(shape, prec):
     eng.close()
 
 
-def _run_recurrence(shape, L, pattern, prec, steps, lr, seed=0, scale=0.1, **kw):
+def _run_recurrence(shape, L, pattern, prec, steps, lr, seed=0, scale=0.1, tune=(), drop_straggler_batches=False, **kw):
     import torch
     P = lstm.param_count(shape)
     w0 = synth.initial_model(seed, P, scale)
     eng = _engine(shape, L, pattern, prec, seed=seed, **kw)
+    for key, value in tune:
+        eng.tune(key, value)
     eng.set_params(-1, torch.from_numpy(w0).cuda())
     ora = A.Oracle(L, pattern, seed, shape=shape, w0=w0, straggler_p=kw.get("straggler_p", 0.0), mix=kw.get("mix"))
     emu = A.Oracle(L, pattern, seed, shape=shape, w0=w0, bf16_gemm=True, mix=kw.get("mix")) if prec else None
     for k in range(steps):
         b = _batches(shape, L, k, seed)
-        eng.step(_to_dev(b), lr)
+        db = _to_dev(b)
+        if drop_straggler_batches:      # a straggler's minibatch is not read: hand over no pointers for it
+            act_k = S.schedule(pattern, seed, k, L, kw.get("straggler_p", 0.0))[2]
+            db = [db[i] if act_k[i] else (None, None) for i in range(L)]
+        eng.step(db, lr)
         ora.step(b, lr)
         assert eng.schedule(k) == tuple(ora.last_schedule)
         active = ora.last_schedule[2]
+        np.testing.assert_allclose(eng.losses(), ora.last_losses, rtol=TOL[prec])      # a straggler reports 0 on both sides
         for i in range(L):
             got_x = eng.params(i).cpu().numpy()
             if active[i]:
@@ -125,6 +132,58 @@ def test_tiny_config_five_steps_fixed_ring():
 def test_random_ring_with_stragglers_small_model():
     print("random ring + stragglers", flush=True)
     _run_recurrence(Shape(12, 16, 1, 1, 0, 20, 3, 4), 6, S.RANDOM_RING, 0, 5, 0.2, seed=4, straggler_p=0.3)
+    _run_recurrence(Shape(12, 16, 1, 1, 0, 20, 3, 4), 6, S.RANDOM_RING, 0, 5, 0.2, seed=4, straggler_p=0.3,
+                    drop_straggler_batches=True)
+
+
+@pytest.mark.parametrize("prec", [0, 1])
+def test_random_ring_with_stragglers_at_a_real_size(prec):
+    # stragglers on a model whose GEMMs run on the large-tile and direct-to-LDS kernels (hidden 256, batch 96,
+    # 8 learners): the gradient phase runs on the compacted list of active learners
+    print("random ring + stragglers, hidden 256", prec, flush=True)
+    seed = 9
+    assert any(0 < sum(S.schedule(S.RANDOM_RING, seed, k, 8, 0.3)[2]) < 8 for k in range(3))
+    _run_recurrence(Shape(64, 256, 2, 1, 64, 512, 96, 5), 8, S.RANDOM_RING, prec, 3, 0.2, seed=seed, scale=0.05,
+                    straggler_p=0.3, drop_straggler_batches=True)
+
+
+def test_every_learner_a_straggler_leaves_everything_unchanged():
+    import torch
+    shape = Shape(12, 16, 1, 1, 0, 20, 3, 4)
+    L, seed, p = 3, 0, 0.97
+    ks = [k for k in range(40) if sum(S.schedule(S.FIXED_RING, seed, k, L, p)[2]) == 0]
+    assert ks and ks[0] == 0, ks[:3]     # iteration 0 has no active learner with this seed
+    eng = _engine(shape, L, S.FIXED_RING, 0, seed=seed, straggler_p=p)
+    w0 = synth.initial_model(seed, eng.P, 0.1)
+    eng.set_params(-1, torch.from_numpy(w0).cuda())
+    eng.step([(None, None)] * L, 0.5)
+    assert (eng.losses() == 0).all()
+    for i in range(L):
+        assert (eng.params(i).cpu().numpy().view(np.uint32) == w0.view(np.uint32)).all()
+    eng.close()
+
+
+def test_label_out_of_range_is_reported_not_repaired_silently():
+    import torch
+    from paper_2110_11199_amd import binding as Bd
+    shape = Shape(12, 16, 1, 1, 0, 20, 3, 4)
+    for bad in (-1, shape.classes, 1 << 30):
+        eng = _engine(shape, 2, S.FIXED_RING, 0)
+        eng.set_params(-1, torch.from_numpy(synth.initial_model(0, eng.P, 0.1)).cuda())
+        b = _batches(shape, 2, 0)
+        eng.step(_to_dev(b), 0.1)
+        eng.status()                                   # clean so far
+        b[1][1][2, 1] = bad
+        eng.step(_to_dev(b), 0.1)
+        with pytest.raises(Bd.AdpsgdError) as ei:
+            eng.losses()
+        assert ei.value.code == Bd.EINVAL and "label" in str(ei.value)
+        with pytest.raises(Bd.AdpsgdError) as ei:      # sticky: the step after the flag has reached the host is refused
+            eng.step(_to_dev(_batches(shape, 2, 1)), 0.1)
+        assert ei.value.code == Bd.EINVAL
+        with pytest.raises(Bd.AdpsgdError):
+            eng.status()
+        eng.close()
 
 
 @pytest.mark.parametrize("prec", [0, 1])
@@ -156,12 +215,37 @@ def test_forward_recurrence_in_learner_groups(groups):
     # first); forced here on a small one, 5 learners in 2 + 3, 1 + 1 + 3 and 1 + 1 + 1 + 1 + 1
     from paper_2110_11199_amd import binding as Bd
     print("forward recurrence in learner groups", groups, flush=True)
-    Bd.adpsgd_gemm_set_variant(300 + groups)
-    try:
-        for prec in (0, 1):
-            _run_recurrence(Shape(12, 64, 2, 1, 0, 20, 40, 3), 5, S.RANDOM_RING, prec, 2, 0.2, seed=7, scale=0.1)
-    finally:
-        Bd.adpsgd_gemm_set_variant(300)
+    for prec in (0, 1):
+        _run_recurrence(Shape(12, 64, 2, 1, 0, 20, 40, 3), 5, S.RANDOM_RING, prec, 2, 0.2, seed=7, scale=0.1,
+                        tune=[(Bd.TUNE_REC_FWD_GROUPS, groups)])
+
+
+def test_tuning_is_per_handle():
+    # two handles in one process: forcing the register-staged kernels on one must not change the other
+    import torch
+    from paper_2110_11199_amd import binding as Bd
+    shape = Shape(64, 64, 1, 1, 0, 64, 40, 3)
+    w0 = synth.initial_model(3, lstm.param_count(shape), 0.1)
+    b = _batches(shape, 2, 0)
+    out = []
+    for forced in (False, True, False):
+        a = _engine(shape, 2, S.FIXED_RING, 1)
+        other = _engine(shape, 2, S.FIXED_RING, 1)
+        if forced:
+            other.tune(Bd.TUNE_REC_DIRECT, 0)
+            other.tune(Bd.TUNE_GEMM_TILE, 0)
+        for e in (a, other):
+            e.set_params(-1, torch.from_numpy(w0).cuda())
+            e.step(_to_dev(b), 0.1)
+        out.append(a.grads(0).cpu().numpy().copy())
+        a.close(); other.close()
+    assert (out[0].view(np.uint32) == out[1].view(np.uint32)).all() and (out[0].view(np.uint32) == out[2].view(np.uint32)).all()
+    with pytest.raises(Bd.AdpsgdError):
+        e = _engine(shape, 2, S.FIXED_RING, 1)
+        try:
+            e.tune(Bd.TUNE_GEMM_TILE, 7)
+        finally:
+            e.close()
 
 
 def test_library_initial_model_matches_generator_spec():

@@ -19,6 +19,13 @@ def _rand(L, P, seed=0):
 def test_mixing_equals_dense_matrix_product(mix, pattern, L):
     # Eq. 2: the mixed models are the rows of T_k applied to the learners' models.
     x, g = _rand(L, 37, L)
+    if mix == S.MIX_TRI and L < 3:      # Eq. 9's circulant has three distinct positions per row
+        order, partner, active = S.schedule(pattern, 1, 0, L, 0.0)
+        with pytest.raises(ValueError):
+            S.mixing_matrix(mix, order, partner, active)
+        with pytest.raises(ValueError):
+            A.mix_update(x, g, mix, order, partner, active, 0.25)
+        return
     for k in range(4):
         p = 0.3 if mix == S.MIX_PAIR else 0.0
         order, partner, active = S.schedule(pattern, 1, k, L, p)
