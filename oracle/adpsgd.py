@@ -23,6 +23,14 @@ T = 11'/L: every learner updates its own model, then all models are averaged,
   u_j = x_j - (lr * g_j)
   x_i^{k+1} = (((u_0 + u_1) + u_2) + ...) * (1/L)      for every i,
 so all learners hold the same model after every iteration.
+
+The hybrid strategy of Section V (super-learners of S consecutive learners that
+average synchronously, joined by the asynchronous ring): the mean of every
+super-learner a first, then the ring operator on those means,
+  m_a = (((x_{aS} + x_{aS+1}) + ...) + x_{aS+S-1}) * (1/S)
+  PAIR  m = (m_a + m_b) * 0.5   (b the matched super-learner; unmatched: m = m_a)
+  TRI   m = ((m_left + m_a) + m_right) * (1/3)      (a single super-learner: m = m_a)
+  x_i^{k+1} = m - (lr * g_i)     for every learner i of super-learner a.
 """
 import numpy as np
 from . import schedule as S
@@ -37,16 +45,46 @@ def init_model(seed, P, scale):
     return out
 
 
-def mix_update(x, g, mix, order, partner, active, lr, update_first=False):
+def mix_update(x, g, mix, order, partner, active, lr, update_first=False, group_size=1):
     """One application of step 3 to x [L][P] float32 with g [L][P] float32.
     Returns the new [L][P] array; x is not modified.
     update_first: the synchronous baseline's order (local update, then the
     average of all learners); defined for the all-learner mean with nobody
-    inactive."""
+    inactive.
+    group_size: hybrid mixes only; order / partner / active then describe the
+    ring of the L / group_size super-learners."""
     x = np.asarray(x, dtype=np.float32)
     L = x.shape[0]
     lr = np.float32(lr)
     out = np.empty_like(x)
+    ring = S.ring_mix_of(mix)
+    if ring is not None:
+        Sz = int(group_size)
+        G = len(order)
+        if Sz < 1 or G * Sz != L or update_first or not all(active):
+            raise ValueError("hybrid mixing: L = G * group_size learners, nobody inactive")
+        if ring == S.MIX_TRI and G == 2:
+            raise ValueError("ring-neighbour mixing across super-learners needs at least 3 of them (or a single one)")
+        means = []
+        for a in range(G):
+            s = x[a * Sz].copy()
+            for j in range(1, Sz):
+                s = s + x[a * Sz + j]
+            means.append(s * (np.float32(1.0) / np.float32(Sz)))
+        pos = {order[p]: p for p in range(G)}
+        for a in range(G):
+            if G == 1:
+                m = means[a]
+            elif ring == S.MIX_PAIR:
+                b = partner[a]
+                m = means[a] if b == a else (means[a] + means[b]) * np.float32(0.5)
+            else:
+                p = pos[a]
+                left, right = order[(p - 1) % G], order[(p + 1) % G]
+                m = ((means[left] + means[a]) + means[right]) * (np.float32(1.0) / np.float32(3.0))
+            for i in range(a * Sz, (a + 1) * Sz):
+                out[i] = m - (lr * np.asarray(g[i], dtype=np.float32))
+        return out
     if update_first:
         if mix != S.MIX_ALL or not all(active):
             raise ValueError("update-then-average is the all-learner mean over every learner")
@@ -94,8 +132,13 @@ class Oracle:
     """L learners, model-bearing (shape given) or model-free (flat_params)."""
 
     def __init__(self, L, pattern, seed, shape=None, flat_params=0, mix=None, tau=None,
-                 straggler_p=0.0, w0=None, x0=None, bf16_gemm=False):
+                 straggler_p=0.0, w0=None, x0=None, bf16_gemm=False, group_size=1):
         self.L, self.pattern, self.seed = L, pattern, seed
+        self.group_size = int(group_size)
+        self.hybrid = S.ring_mix_of(mix) is not None
+        if self.hybrid and (self.group_size < 1 or L % self.group_size or straggler_p > 0.0 or pattern in (S.D1D, S.SDPSGD)):
+            raise ValueError("hybrid mixing: a ring pattern, L a multiple of group_size, no stragglers")
+        self.ring_size = L // self.group_size if self.hybrid else L
         self.shape = shape
         self.P = lstm.param_count(shape) if shape is not None else int(flat_params)
         self.mix = mix if mix is not None else (S.MIX_ALL if pattern in (S.D1D, S.SDPSGD) else S.MIX_PAIR)
@@ -124,8 +167,10 @@ class Oracle:
         learners, whose gradients are independent of each other (Algorithm 1: the
         learners run concurrently), over that many threads; every learner's
         arithmetic is unchanged, so the result is the same as with one."""
-        order, partner, active = S.schedule(self.pattern, self.seed, self.k, self.L, self.straggler_p)
+        order, partner, active = S.schedule(self.pattern, self.seed, self.k, self.ring_size, self.straggler_p)
         self.last_schedule = (order, partner, active)
+        if self.hybrid:      # the schedule is over super-learners; every learner computes a gradient
+            active = [1] * self.L
         if grads is None:
             at = self.gradient_point()
             grads = np.zeros((self.L, self.P), dtype=np.float32)
@@ -145,7 +190,10 @@ class Oracle:
                     one(i)
             self.last_losses = losses
         self.last_grads = grads
-        new = mix_update(self.x, grads, self.mix, order, partner, active, lr, self.update_first)
+        if self.hybrid:
+            new = mix_update(self.x, grads, self.mix, order, partner, [1] * self.ring_size, lr, False, self.group_size)
+        else:
+            new = mix_update(self.x, grads, self.mix, order, partner, active, lr, self.update_first)
         self.x_prev = self.x
         self.x = new
         self.k += 1

@@ -19,6 +19,13 @@ What it leaves open, and the reading taken here
     connected over two iterations; on the random ring the phase is 0;
   * a straggler (inactive learner) takes no part in the iteration; the learner
     it would have been matched with keeps its own model for the mixing term.
+
+Hierarchy (Section V, the hybrid strategy and its figure): consecutive blocks of
+S learners form super-learners that average synchronously among themselves, and
+the G = L/S super-learners form the asynchronous ring.  The schedule of such a
+run is the schedule above over the G super-learners; the mixing matrix is the
+ring operator over super-learners with every entry spread evenly over the S x S
+block of its two groups.
 """
 import numpy as np
 
@@ -31,6 +38,7 @@ STREAM_INIT = 3   # initial model draws
 
 FIXED_RING, RANDOM_RING, D1D, SDPSGD = 0, 1, 2, 3
 MIX_PAIR, MIX_TRI, MIX_ALL = 0, 1, 2
+MIX_HYBRID_PAIR, MIX_HYBRID_TRI = 3, 4    # synchronous mean inside super-learners, PAIR / TRI ring across them
 
 
 def mix64(z):
@@ -93,9 +101,33 @@ def schedule(pattern, seed, k, L, straggler_p=0.0):
     return order, partner, active
 
 
-def mixing_matrix(mix, order, partner, active):
+def ring_mix_of(mix):
+    """The ring operator a hybrid mix applies across super-learners (None for a plain mix)."""
+    return {MIX_HYBRID_PAIR: MIX_PAIR, MIX_HYBRID_TRI: MIX_TRI}.get(mix)
+
+
+def mixing_matrix(mix, order, partner, active, group_size=1):
     """Dense T_k (float64) such that the mixed model of learner i is
-    sum_j T[i, j] x_j  (Algorithm 1, model averaging step)."""
+    sum_j T[i, j] x_j  (Algorithm 1, model averaging step).
+
+    Hybrid mixes: order / partner / active describe the ring of the G = len(order)
+    super-learners; learner i belongs to super-learner i // group_size and the
+    result is the (G * group_size)-square matrix
+    T[i, j] = T_ring[i // S, j // S] / S  (the synchronous mean inside a
+    super-learner composed with the ring operator across super-learners)."""
+    if ring_mix_of(mix) is not None:
+        G, Sz = len(order), int(group_size)
+        if Sz < 1:
+            raise ValueError("group_size")
+        if G == 1:
+            Tg = np.ones((1, 1))
+        else:
+            Tg = mixing_matrix(ring_mix_of(mix), order, partner, active)
+        T = np.zeros((G * Sz, G * Sz))
+        for i in range(G * Sz):
+            for j in range(G * Sz):
+                T[i, j] = Tg[i // Sz, j // Sz] / Sz
+        return T
     L = len(order)
     T = np.zeros((L, L))
     if mix == MIX_ALL:

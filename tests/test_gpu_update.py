@@ -80,10 +80,11 @@ def test_consensus_distance_and_its_contraction(L, P):
     from paper_2110_11199_amd import binding as Bd
     r = np.random.default_rng(L)
     x0 = r.uniform(-1, 1, (L, P)).astype(np.float32)
-    eng = Bd.Adpsgd(Bd.make_config(L, S.FIXED_RING, flat_params=P, mix=Bd.MIX_TRI))
+    mix = S.MIX_TRI if L >= 3 else S.MIX_PAIR          # the ring-neighbour operator needs three learners
+    eng = Bd.Adpsgd(Bd.make_config(L, S.FIXED_RING, flat_params=P, mix=mix))
     for i in range(L):
         eng.set_params(i, torch.from_numpy(x0[i]).cuda())
-    ora = A.Oracle(L, S.FIXED_RING, 0, flat_params=P, x0=x0, mix=S.MIX_TRI)
+    ora = A.Oracle(L, S.FIXED_RING, 0, flat_params=P, x0=x0, mix=mix)
     zero = np.zeros((L, P), np.float32)
     gz = [torch.zeros(P, device="cuda") for _ in range(L)]
     for k in range(3):
