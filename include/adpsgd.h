@@ -77,8 +77,17 @@ typedef enum { ADPSGD_FIXED_RING = 0, ADPSGD_RANDOM_RING = 1, ADPSGD_D1D = 2, AD
  *         (x_left + x_i) + x_right in that order, then times fl(1/3); needs L >= 3
  *         (with fewer learners the three ring positions are not distinct)
  *   ALL   the global mean, T = 11'/L (allreduce, Section III-A / III-D)
+ *   HYBRID_PAIR, HYBRID_TRI   the hybrid strategy of Section V (its hierarchical ring
+ *         figure): consecutive blocks of group_size learners form super-learners that
+ *         average synchronously, m_a = (((x_{aS} + x_{aS+1}) + ...)) * fl(1/S), and the
+ *         G = L / group_size super-learners form the asynchronous ring, on whose means
+ *         the PAIR or TRI operator acts; every learner of super-learner a then takes
+ *         x_i <- m - lr * g_i.  The ring patterns only, no stragglers (a super-learner
+ *         waits for its members); L a multiple of group_size; TRI needs G >= 3 or G == 1.
+ *         The schedule (ring order, matching) is that of G ring positions.
  *   DEFAULT = PAIR for the rings, ALL for delay-by-one and the synchronous baseline. */
-typedef enum { ADPSGD_MIX_DEFAULT = -1, ADPSGD_MIX_PAIR = 0, ADPSGD_MIX_TRI = 1, ADPSGD_MIX_ALL = 2 } adpsgd_mix;
+typedef enum { ADPSGD_MIX_DEFAULT = -1, ADPSGD_MIX_PAIR = 0, ADPSGD_MIX_TRI = 1, ADPSGD_MIX_ALL = 2,
+               ADPSGD_MIX_HYBRID_PAIR = 3, ADPSGD_MIX_HYBRID_TRI = 4 } adpsgd_mix;
 /* Arithmetic of the GEMMs: fp32 operands, or bf16 operands (rounded to nearest
  * even from the fp32 master) with fp32 accumulation.  State, gates, softmax
  * and the update are fp32 in both.                                              */
@@ -114,6 +123,8 @@ typedef struct {
                                         w_0 ~ U(-a, a) (Algorithm 1, input);
                                         0: models start as zeros, set them with
                                         adpsgd_set_params                         */
+    int32_t            group_size;   /* learners per super-learner (hybrid mixes);
+                                        0 or 1 with every other mix                */
 } adpsgd_config;
 
 /* Bytes of device workspace a handle with this configuration needs.
@@ -175,12 +186,24 @@ int adpsgd_layout(adpsgd_t h, int idx, int64_t* offset, int64_t* rows, int64_t* 
 
 /* The schedule of iteration k, a pure function of (config, k): ring order,
  * matching partner (partner[i] == i: none) and active flag of each learner.
- * order, partner, active: host int32 [L] (any may be NULL).                    */
+ * order, partner, active: host int32 [L] (any may be NULL).  With a hybrid mix the
+ * ring is that of the G = L / group_size super-learners: entries 0..G-1 describe it
+ * and entries G..L-1 are set to -1.                                              */
 int adpsgd_schedule(adpsgd_t h, int64_t k, int32_t* order, int32_t* partner, int32_t* active);
 
 /* Same without a handle.  mix is not needed: the matching does not depend on it. */
 int adpsgd_schedule_of(int32_t pattern, uint64_t seed, float straggler_p, int32_t L, int64_t k,
                        int32_t* order, int32_t* partner, int32_t* active);
+
+/* Learning rate of the 1-based epoch under the schedules of the paper's experiments
+ * (Section IV): constant peak_lr up to and including epoch hold_until_epoch, multiplied
+ * by 1/sqrt(2) for every epoch after it; when warmup_epochs >= 2, the epochs 1 ..
+ * warmup_epochs rise linearly from start_lr (epoch 1) to peak_lr (epoch warmup_epochs).
+ * The single-learner baseline is (peak 0.1, no warm-up, hold 10); the 8192-segment
+ * batches use (peak 3.2, start 0.32, warm-up 10, hold 10).  Computed in double, rounded
+ * once to float.  out: host.  EINVAL for epoch < 1, warmup_epochs < 0 or a NULL out.   */
+int adpsgd_lr_at_epoch(int32_t epoch, float peak_lr, float start_lr, int32_t warmup_epochs,
+                       int32_t hold_until_epoch, float* out);
 
 /* Iterations done so far.                                                      */
 int64_t adpsgd_iteration(adpsgd_t h);
@@ -243,10 +266,18 @@ int adpsgd_gemm(int precision, int a_kmajor, int b_kmajor, int c_is_elem,
  *   ADPSGD_TUNE_GEMM_TILE        tile configuration of the time-batched GEMMs, as tile_config above
  *   ADPSGD_TUNE_REC_DIRECT       1 (default) / 0: direct-to-LDS recurrent step kernels allowed or not
  *   ADPSGD_TUNE_REC_FWD_GROUPS   learner groups the forward recurrence is run in, 0 = automatic
+ *   ADPSGD_TUNE_REC_PERSISTENT   persistent recurrent kernels (all frames of a layer in one launch, W_h held in
+ *                                registers; bf16 operands, hidden 128/256/512/1024, batch <= 128): 1 on where the
+ *                                shape allows, 0 off, -1 (default) automatic
+ *   ADPSGD_TUNE_REC_WAIT_US      bound, in microseconds, of one wait between the workgroups of a persistent
+ *                                kernel (default 2 000 000); when it runs out every workgroup returns and the
+ *                                handle's sticky error becomes ADPSGD_EHIP
  * Takes effect from the next adpsgd_step of that handle; other handles are not touched. */
 #define ADPSGD_TUNE_GEMM_TILE       0
 #define ADPSGD_TUNE_REC_DIRECT      1
 #define ADPSGD_TUNE_REC_FWD_GROUPS  2
+#define ADPSGD_TUNE_REC_PERSISTENT  3
+#define ADPSGD_TUNE_REC_WAIT_US     4
 int adpsgd_set_tuning(adpsgd_t h, int key, int value);
 
 #ifdef __cplusplus

@@ -22,7 +22,7 @@ _lib = C.CDLL(LIB_PATH)
 
 OK, EINVAL, ENOMEM, EHIP = 0, -1, -2, -3
 FIXED_RING, RANDOM_RING, D1D, SDPSGD = 0, 1, 2, 3
-MIX_DEFAULT, MIX_PAIR, MIX_TRI, MIX_ALL = -1, 0, 1, 2
+MIX_DEFAULT, MIX_PAIR, MIX_TRI, MIX_ALL, MIX_HYBRID_PAIR, MIX_HYBRID_TRI = -1, 0, 1, 2, 3, 4
 FP32, BF16_GEMM = 0, 1
 MAX_LEARNERS = 128
 
@@ -36,7 +36,7 @@ class ModelShape(C.Structure):
 class Config(C.Structure):
     _fields_ = [("L", C.c_int32), ("shape", ModelShape), ("pattern", C.c_int32), ("mix", C.c_int32),
                 ("tau", C.c_int32), ("precision", C.c_int32), ("seed", C.c_uint64),
-                ("straggler_p", C.c_float), ("init_scale", C.c_float)]
+                ("straggler_p", C.c_float), ("init_scale", C.c_float), ("group_size", C.c_int32)]
 
 
 _vp, _i64, _i32p = C.c_void_p, C.c_int64, C.POINTER(C.c_int32)
@@ -55,6 +55,7 @@ _lib.adpsgd_layout_count.argtypes = [_vp]
 _lib.adpsgd_layout.argtypes = [_vp, C.c_int, C.POINTER(_i64), C.POINTER(_i64), C.POINTER(_i64)]
 _lib.adpsgd_schedule.argtypes = [_vp, _i64, _i32p, _i32p, _i32p]
 _lib.adpsgd_schedule_of.argtypes = [C.c_int32, C.c_uint64, C.c_float, C.c_int32, _i64, _i32p, _i32p, _i32p]
+_lib.adpsgd_lr_at_epoch.argtypes = [C.c_int32, C.c_float, C.c_float, C.c_int32, C.c_int32, C.POINTER(C.c_float)]
 _lib.adpsgd_iteration.argtypes = [_vp]
 _lib.adpsgd_iteration.restype = _i64
 _lib.adpsgd_average.argtypes = [_vp, _vp]
@@ -73,8 +74,8 @@ EXPORTS = ["adpsgd_workspace_bytes", "adpsgd_create", "adpsgd_step", "adpsgd_par
            "adpsgd_grads", "adpsgd_losses", "adpsgd_param_count", "adpsgd_layout_count", "adpsgd_layout",
            "adpsgd_schedule", "adpsgd_schedule_of", "adpsgd_iteration", "adpsgd_average", "adpsgd_destroy",
            "adpsgd_last_error", "adpsgd_gemm", "adpsgd_set_profiling", "adpsgd_profile",
-           "adpsgd_set_tuning", "adpsgd_consensus", "adpsgd_status"]
-TUNE_GEMM_TILE, TUNE_REC_DIRECT, TUNE_REC_FWD_GROUPS = 0, 1, 2
+           "adpsgd_set_tuning", "adpsgd_consensus", "adpsgd_status", "adpsgd_lr_at_epoch"]
+TUNE_GEMM_TILE, TUNE_REC_DIRECT, TUNE_REC_FWD_GROUPS, TUNE_REC_PERSISTENT, TUNE_REC_WAIT_US = 0, 1, 2, 3, 4
 PHASES = ["stage_cast", "batched_gemm", "recurrent_fwd", "recurrent_bwd", "softmax_ce", "bias_colsum", "mix_update"]
 
 
@@ -95,9 +96,9 @@ def _check(rc):
 
 def make_config(L, pattern, seed=0, input_dim=0, hidden=0, layers=0, bidirectional=0, bottleneck=0,
                 classes=0, batch=0, frames=0, flat_params=0, mix=MIX_DEFAULT, tau=-1, precision=FP32,
-                straggler_p=0.0, init_scale=0.0):
+                straggler_p=0.0, init_scale=0.0, group_size=0):
     return Config(L, ModelShape(input_dim, hidden, layers, bidirectional, bottleneck, classes, batch, frames,
-                                flat_params), pattern, mix, tau, precision, seed, straggler_p, init_scale)
+                                flat_params), pattern, mix, tau, precision, seed, straggler_p, init_scale, group_size)
 
 
 def adpsgd_workspace_bytes(cfg):
@@ -158,6 +159,12 @@ def adpsgd_schedule_of(pattern, seed, straggler_p, L, k):
     o, p, a = (C.c_int32 * L)(), (C.c_int32 * L)(), (C.c_int32 * L)()
     _check(_lib.adpsgd_schedule_of(pattern, seed, straggler_p, L, k, o, p, a))
     return list(o), list(p), list(a)
+
+
+def adpsgd_lr_at_epoch(epoch, peak_lr, start_lr=0.0, warmup_epochs=0, hold_until_epoch=10):
+    out = C.c_float(0.0)
+    _check(_lib.adpsgd_lr_at_epoch(epoch, peak_lr, start_lr, warmup_epochs, hold_until_epoch, C.byref(out)))
+    return out.value
 
 
 def adpsgd_iteration(h):

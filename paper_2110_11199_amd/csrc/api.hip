@@ -100,6 +100,10 @@ struct adpsgd_handle {
     int tune_gemm_tile = -1;               // forced GEMM tile configuration, -1 = automatic
     int tune_rec_direct = 1;               // direct-to-LDS recurrent kernels allowed
     int tune_rec_fwd_groups = 0;           // learner groups of the forward recurrence, 0 = automatic
+    int tune_rec_persist = -1;             // persistent recurrent kernels: 0 off, 1 on where the shape allows, -1 automatic
+    int64_t tune_wait_us = 2000000;        // bound of one wait between the workgroups of a persistent kernel
+    int cu_count = 0;                      // compute units of the device (a persistent grid must not exceed it)
+    uint32_t* rec_counters = nullptr;      // [layers][2 passes][L * D] frame counters of the persistent kernels
     // device status word (kStatus* bits, sticky) and its pinned host mirror, refreshed by an asynchronous
     // copy at the end of every step
     uint32_t* status = nullptr;
@@ -145,6 +149,26 @@ int rec_forward_parts(const adpsgd_handle* h, int n) {
     return 1;
 }
 
+// Pairs (learner, direction) one persistent launch takes: one workgroup of 32 units per compute unit at most.
+int persist_cap(const adpsgd_handle* h) {
+    int cap = h->cu_count / (h->H / 32);
+    if (cap > 64) cap = 64;
+    if (cap >= 8) cap -= cap % 8;
+    return cap < 1 ? 1 : cap;
+}
+
+// Whether the recurrences of this handle run on the persistent kernels (all frames of a layer in one launch,
+// W_h resident in registers) instead of one launch per frame.
+bool use_persistent(const adpsgd_handle* h) {
+    if (h->flat || h->tune_rec_persist == 0 || h->cu_count < 1) return false;
+    RecDesc r{};
+    r.precision = h->prec; r.D = h->D; r.B = h->B; r.H = h->H; r.T = h->T;
+    // the alignment of the tensors follows from the layout: 256-byte aligned regions, strides that are multiples of 64
+    if (!rec_persist_supported(r, h->cu_count)) return false;
+    if (h->tune_rec_persist == 1) return true;
+    return false;       // automatic: off
+}
+
 // Turns the status bits a kernel has raised (as last copied to the host) into an error.
 int status_error(const adpsgd_handle* h) {
     const uint32_t st = h->status_host ? *h->status_host : 0u;
@@ -158,17 +182,32 @@ int status_error(const adpsgd_handle* h) {
 }
 
 bool all_by_default(int pattern) { return pattern == ADPSGD_D1D || pattern == ADPSGD_SDPSGD; }
+bool is_hybrid(int mix) { return mix == ADPSGD_MIX_HYBRID_PAIR || mix == ADPSGD_MIX_HYBRID_TRI; }
 
 int check_config(const adpsgd_config* c, std::string& why) {
     if (!c) { why = "config is NULL"; return ADPSGD_EINVAL; }
     if (c->L < 1 || c->L > ADPSGD_MAX_LEARNERS) { why = "L must be in 1..128"; return ADPSGD_EINVAL; }
     if (c->pattern < 0 || c->pattern > 3) { why = "unknown pattern"; return ADPSGD_EINVAL; }
-    if (c->mix != ADPSGD_MIX_DEFAULT && c->mix != ADPSGD_MIX_PAIR && c->mix != ADPSGD_MIX_TRI && c->mix != ADPSGD_MIX_ALL) { why = "unknown mix"; return ADPSGD_EINVAL; }
+    if (c->mix < ADPSGD_MIX_DEFAULT || c->mix > ADPSGD_MIX_HYBRID_TRI) { why = "unknown mix"; return ADPSGD_EINVAL; }
     if (c->tau < -1 || c->tau > 1) { why = "tau must be 0, 1 or -1"; return ADPSGD_EINVAL; }
     if (c->precision != ADPSGD_FP32 && c->precision != ADPSGD_BF16_GEMM) { why = "unknown precision"; return ADPSGD_EINVAL; }
     if (!(c->straggler_p >= 0.f && c->straggler_p < 1.f)) { why = "straggler_p must be in [0,1)"; return ADPSGD_EINVAL; }
     const int tau = c->tau >= 0 ? c->tau : (c->pattern == ADPSGD_D1D ? 1 : 0);
     const int mix = c->mix != ADPSGD_MIX_DEFAULT ? c->mix : (all_by_default(c->pattern) ? ADPSGD_MIX_ALL : ADPSGD_MIX_PAIR);
+    if (is_hybrid(mix)) {
+        const int S = c->group_size;
+        if (S < 1 || c->L % S != 0) { why = "hybrid mixing: L must be a multiple of group_size >= 1"; return ADPSGD_EINVAL; }
+        if (c->pattern != ADPSGD_FIXED_RING && c->pattern != ADPSGD_RANDOM_RING) {
+            why = "hybrid mixing joins the super-learners by a ring: fixed or random ring pattern only"; return ADPSGD_EINVAL;
+        }
+        if (c->straggler_p > 0.f) { why = "hybrid mixing takes no stragglers (a super-learner waits for its members)"; return ADPSGD_EINVAL; }
+        const int G = c->L / S;
+        if (mix == ADPSGD_MIX_HYBRID_TRI && G == 2) {
+            why = "ring-neighbour mixing across super-learners needs at least 3 of them (or a single one)"; return ADPSGD_EINVAL;
+        }
+    } else if (c->group_size != 0 && c->group_size != 1) {
+        why = "group_size is for the hybrid mixes only"; return ADPSGD_EINVAL;
+    }
     if (mix == ADPSGD_MIX_TRI && c->L < 3) {
         why = "ring-neighbour mixing (weights 1/3, Eq. 9) needs at least 3 learners"; return ADPSGD_EINVAL;
     }
@@ -239,6 +278,7 @@ size_t plan(adpsgd_handle* h, void* base) {
     h->params[1] = h->tau == 1 ? (float*)w.take(L * h->Ppad * 4) : h->params[0];
     h->consensus = (double*)w.take((size_t)(kConsensusBlocks + 1) * 8);     // partial sums + the result
     h->status = (uint32_t*)w.take(256);
+    if (s.flat_params == 0) h->rec_counters = (uint32_t*)w.take((size_t)s.layers * 2 * c.L * 2 * 4);
     if (!h->flat) {
         const size_t M = (size_t)h->M, DH = (size_t)h->D * h->H, G4 = DH * 4, e = (size_t)h->esz;
         h->grads = (float*)w.take(L * h->Ppad * 4);
@@ -322,7 +362,34 @@ int compute_gradients(adpsgd_handle* h, const float* at, const void* const* batc
     }
     // weights as GEMM operands: the fp32 models themselves, or their bf16 copy
     const char* wbase = (const char*)at;
-    if (int rc = mark(h, 0, prec ? (h->wx0p ? 3 : 2) : 1)) return rc;
+    const bool persist = use_persistent(h);
+    if (int rc = mark(h, 0, (prec ? (h->wx0p ? 3 : 2) : 1) + (persist ? 1 : 0))) return rc;
+    if (persist)     // frame counters of the persistent kernels start from zero (a fill kernel, not a memset node)
+        HIPCHK(launch_zero((float*)h->rec_counters, 0, (int64_t)h->layers * 2 * L * 2, 1, ident, s), "zero frame counters");
+    // the (learner, direction) pairs of the active learners, in the order the persistent launches take them
+    uint8_t pair_l[256], pair_d[256];
+    int npairs = 0;
+    for (int j = 0; j < n; ++j)
+        for (int dd = 0; dd < D; ++dd) { pair_l[npairs] = act.idx[j]; pair_d[npairs] = (uint8_t)dd; ++npairs; }
+    // all T frames of layer l for every pair: as many pairs per launch as fit one workgroup per compute unit
+    auto run_persistent = [&](const RecDesc& r, int l, bool backward) -> int {
+        const int per_pair = H / 32;
+        int cap = h->cu_count / per_pair;
+        if (cap > 64) cap = 64;
+        if (cap >= 8) cap -= cap % 8;            // whole pairs per XCD (workgroup ids go round-robin over the 8 XCDs)
+        for (int p0 = 0; p0 < npairs; p0 += cap) {
+            PersistDesc pd;
+            pd.r = r;
+            pd.ngl = npairs - p0 < cap ? npairs - p0 : cap;
+            for (int j = 0; j < 64; ++j) { pd.gl_learner[j] = j < pd.ngl ? pair_l[p0 + j] : 0; pd.gl_dir[j] = j < pd.ngl ? pair_d[p0 + j] : 0; }
+            pd.counters = h->rec_counters + ((size_t)(l * 2 + (backward ? 1 : 0)) * L * 2 + p0);
+            pd.status = h->status;
+            pd.wait_ticks = (unsigned long long)h->tune_wait_us * 100ull;
+            HIPCHK(launch_rec_persist(pd, backward, h->cu_count, s), backward ? "persistent recurrent backward" : "persistent recurrent forward");
+        }
+        return ADPSGD_OK;
+    };
+    const int persist_launches = persist ? (npairs + persist_cap(h) - 1) / persist_cap(h) : 0;
     if (prec) {
         // the update of the previous iteration has normally written this copy already
         if (!h->shadow_valid) HIPCHK(launch_cast_bf16(at, h->shadow, (int64_t)L * Pp, s), "cast weights to bf16");
@@ -376,6 +443,13 @@ int compute_gradients(adpsgd_handle* h, const float* at, const void* const* batc
         // 16 x 1024-unit workload: 10.7 -> 8.9 ms per iteration in two groups; three or four groups leave too
         // few workgroups per launch and are slower than one).
         const int parts = rec_forward_parts(h, n);
+        if (persist) {
+            // per (learner, direction): W_h once; per frame: pre-activations in, gates, c and h out, h in
+            if (int rc = mark(h, 2, persist_launches, 2.0 * B * H * 4 * H * (T - 1) * n * D,
+                              (double)n * D * (4.0 * H * H * esz + (double)T * B * H * (2 * esz + 16 + 16 + 4)))) return rc;
+            if (int rc = run_persistent(r, l, false)) return rc;
+            continue;
+        }
         // per frame and (learner, direction): W_h once, h in and out, 4 gates in and out (fp32), c in and out
         if (int rc = mark(h, 2, T * parts, 2.0 * B * H * 4 * H * (T - 1) * n * D,
                           (double)T * n * D * (4.0 * H * H * esz + (double)B * H * (2 * esz + 8 * 4 + 2 * 4)))) return rc;
@@ -475,12 +549,19 @@ int compute_gradients(adpsgd_handle* h, const float* at, const void* const* batc
         r.dc = h->dc; r.sDCi = (int64_t)B * DH;
         const int64_t dbrows = (int64_t)T * rec_backward_batch_tiles(B);
         r.dbp = h->dbp; r.sDBi = dbrows * G4;
-        // per frame and (learner, direction): W_h once, da in (4 gates) and out, dY, 4 gates, c, c', dc in and out
-        if (int rc = mark(h, 3, T, 2.0 * B * H * 4 * H * (T - 1) * n * D,
-                          (double)T * n * D * (4.0 * H * H * esz + (double)B * H * (8 * esz + 4 + 16 + 8 + 8)))) return rc;
-        for (int t = 0; t < T; ++t) {
-            r.step = t;
-            HIPCHK(launch_rec_backward(r, s), "recurrent backward step");
+        if (persist) {
+            // per (learner, direction): W_h once; per frame: da in (4 gates) and out, dY, 4 gates, c, c'
+            if (int rc = mark(h, 3, persist_launches, 2.0 * B * H * 4 * H * (T - 1) * n * D,
+                              (double)n * D * (4.0 * H * H * esz + (double)T * B * H * (8 * esz + 4 + 16 + 8)))) return rc;
+            if (int rc = run_persistent(r, l, true)) return rc;
+        } else {
+            // per frame and (learner, direction): W_h once, da in (4 gates) and out, dY, 4 gates, c, c', dc in and out
+            if (int rc = mark(h, 3, T, 2.0 * B * H * 4 * H * (T - 1) * n * D,
+                              (double)T * n * D * (4.0 * H * H * esz + (double)B * H * (8 * esz + 4 + 16 + 8 + 8)))) return rc;
+            for (int t = 0; t < T; ++t) {
+                r.step = t;
+                HIPCHK(launch_rec_backward(r, s), "recurrent backward step");
+            }
         }
         // dW_x = da' x  (both directions at once: rows of W_x are [D][4H])
         g = G();
@@ -553,6 +634,11 @@ static int create_impl(const adpsgd_config* cfg, void* dev_workspace, size_t byt
         return fail(ADPSGD_ENOMEM, "workspace too small: need " + std::to_string(need) + " bytes");
     }
     h->k = 0; h->cur = 0; h->shadow_valid = false;
+    {
+        int dev = 0, cus = 0;
+        if (hipGetDevice(&dev) == hipSuccess && hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess)
+            h->cu_count = cus;
+    }
     hipStream_t s = h->stream;
     const size_t slab = (size_t)h->L * h->Ppad * 4;
     void* mirror = nullptr;                       // pinned host word the status is copied to after every step
@@ -601,7 +687,13 @@ static int step_impl(adpsgd_t h, const void* const* batch_ptrs, float lr) {
     if (int rc = status_error(h)) return rc;
     const int L = h->L;
     int32_t order[ADPSGD_MAX_LEARNERS], partner[ADPSGD_MAX_LEARNERS], active[ADPSGD_MAX_LEARNERS];
-    make_schedule(h->cfg.pattern, h->cfg.seed, h->cfg.straggler_p, L, h->k, order, partner, active);
+    if (is_hybrid(h->mix)) {
+        // the ring is that of the super-learners; every learner takes part
+        make_schedule(h->cfg.pattern, h->cfg.seed, 0.f, L / h->cfg.group_size, h->k, order, partner, active);
+        for (int i = 0; i < L; ++i) active[i] = 1;
+    } else {
+        make_schedule(h->cfg.pattern, h->cfg.seed, h->cfg.straggler_p, L, h->k, order, partner, active);
+    }
     const int nptr = h->flat ? L : 2 * L;
     for (int i = 0; i < nptr; ++i) {
         const int li = h->flat ? i : i / 2;
@@ -612,6 +704,7 @@ static int step_impl(adpsgd_t h, const void* const* batch_ptrs, float lr) {
     UpdateDesc u{};
     u.L = L; u.mix = h->mix; u.P = h->P; u.src = xk; u.dst = xnext; u.stride = h->Ppad; u.lr = lr;
     u.update_first = h->cfg.pattern == ADPSGD_SDPSGD;
+    u.group_size = is_hybrid(h->mix) ? h->cfg.group_size : 1;
     if (h->flat) {
         for (int i = 0; i < L; ++i) u.g[i] = (const float*)batch_ptrs[i];
     } else {
@@ -711,7 +804,31 @@ int adpsgd_schedule_of(int32_t pattern, uint64_t seed, float straggler_p, int32_
 
 int adpsgd_schedule(adpsgd_t h, int64_t k, int32_t* order, int32_t* partner, int32_t* active) {
     if (!h) return fail(ADPSGD_EINVAL, "NULL handle");
+    if (is_hybrid(h->mix)) {
+        const int G = h->L / h->cfg.group_size;
+        if (int rc = adpsgd_schedule_of(h->cfg.pattern, h->cfg.seed, 0.f, G, k, order, partner, active)) return rc;
+        for (int i = G; i < h->L; ++i) {
+            if (order) order[i] = -1;
+            if (partner) partner[i] = -1;
+            if (active) active[i] = -1;
+        }
+        return ADPSGD_OK;
+    }
     return adpsgd_schedule_of(h->cfg.pattern, h->cfg.seed, h->cfg.straggler_p, h->L, k, order, partner, active);
+}
+
+int adpsgd_lr_at_epoch(int32_t epoch, float peak_lr, float start_lr, int32_t warmup_epochs, int32_t hold_until_epoch, float* out) {
+    if (!out || epoch < 1 || warmup_epochs < 0) return fail(ADPSGD_EINVAL, "epoch >= 1, warmup_epochs >= 0 and a result pointer are needed");
+    double lr;
+    if (warmup_epochs >= 2 && epoch <= warmup_epochs) {
+        lr = (double)start_lr + ((double)peak_lr - (double)start_lr) * (double)(epoch - 1) / (double)(warmup_epochs - 1);
+    } else if (epoch <= hold_until_epoch) {
+        lr = (double)peak_lr;
+    } else {
+        lr = (double)peak_lr * std::pow(std::sqrt(0.5), (double)(epoch - hold_until_epoch));
+    }
+    *out = (float)lr;
+    return ADPSGD_OK;
 }
 
 int64_t adpsgd_iteration(adpsgd_t h) { return h ? h->k : -1; }
@@ -806,6 +923,12 @@ int adpsgd_set_tuning(adpsgd_t h, int key, int value) {
         case ADPSGD_TUNE_REC_FWD_GROUPS:
             if (value < 0 || value > ADPSGD_MAX_LEARNERS) return fail(ADPSGD_EINVAL, "0 (automatic) or 1..128 groups");
             h->tune_rec_fwd_groups = value; return ADPSGD_OK;
+        case ADPSGD_TUNE_REC_PERSISTENT:
+            if (value < -1 || value > 1) return fail(ADPSGD_EINVAL, "-1 (automatic), 0 or 1");
+            h->tune_rec_persist = value; return ADPSGD_OK;
+        case ADPSGD_TUNE_REC_WAIT_US:
+            if (value < 0) return fail(ADPSGD_EINVAL, "microseconds >= 0");
+            h->tune_wait_us = value; return ADPSGD_OK;
         default: return fail(ADPSGD_EINVAL, "unknown tuning key");
     }
 }

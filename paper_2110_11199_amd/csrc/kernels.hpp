@@ -35,7 +35,10 @@ hipError_t launch_gemm(const GemmDesc& d, hipStream_t s);
 // ---- fused mixing + SGD update ------------------------------------------------
 struct UpdateDesc {
     int L;
-    int mix;                   // 0 pair, 1 ring neighbours (thirds), 2 all
+    int mix;                   // 0 pair, 1 ring neighbours (thirds), 2 all, 3 / 4 hybrid: mean inside super-learners of
+                               // group_size consecutive learners, pair / ring-neighbour operator across them (partner and
+                               // order are then over the L / group_size super-learners)
+    int group_size;
     int64_t P;                 // elements per learner
     const float* src;          // x^k, learner i at src + i*stride
     float* dst;                // x^{k+1}, learner i at dst + i*stride (may equal src)
@@ -99,6 +102,20 @@ hipError_t launch_rec_backward(const RecDesc& d, hipStream_t s);
 // Bits of the device-side status word of a handle (0 = fine).
 constexpr uint32_t kStatusBadLabel = 1u;       // a label outside [0, classes) was met (and clamped)
 constexpr uint32_t kStatusWaitExpired = 2u;    // a bounded wait between workgroups ran out
+
+// All T frames of one layer for ngl (learner, direction) pairs in one launch, W_h held in registers
+// (lstm_persist.hip).  r: the tensors of the layer (r.L, r.lmap, r.step and r.direct are not used);
+// pair j of the launch is learner gl_learner[j], direction gl_dir[j].
+struct PersistDesc {
+    RecDesc r;
+    int ngl;                             // pairs of this launch, 1..64; ngl * H/32 workgroups, at most one per compute unit
+    uint8_t gl_learner[64], gl_dir[64];
+    uint32_t* counters;                  // [ngl] device words, zero before the launch: workgroups that have finished a frame
+    uint32_t* status;                    // the handle's status word (kStatusWaitExpired is or-ed in)
+    unsigned long long wait_ticks;       // bound of one wait between workgroups, in ticks of the 100 MHz wall clock
+};
+bool rec_persist_supported(const RecDesc& d, int cu_count);
+hipError_t launch_rec_persist(const PersistDesc& p, bool backward, int cu_count, hipStream_t s);
 
 struct SoftmaxDesc {
     int precision, L;          // L: learners of this launch (entries of lmap)

@@ -290,6 +290,145 @@ __global__ __launch_bounds__(256) void tri_update_kernel(TriArgs p) {
     }
 }
 
+// ---- hybrid mixing (Section V: synchronous super-learners joined by the asynchronous ring) -----------
+// Consecutive blocks of S learners form super-learners.  The mean of every super-learner first,
+//     m_a = (((x_{aS} + x_{aS+1}) + ...) + x_{aS+S-1}) * (1/S),
+// then the ring operator on the means (pair: (m_a + m_b) * 0.5; neighbours: ((m_left + m_a) + m_right) * (1/3)),
+// then x_i <- m - (lr * g_i) for every learner i of super-learner a.  One thread owns an element index (a float4,
+// or one float on the unaligned path and the tail) of all the learners it touches and reads every model once
+// before it writes any of them, so the update is safe in place at 12 bytes per learner and element.
+struct HybridArgs {
+    const float* src; float* dst; int64_t stride; int64_t P; float lr;
+    bf16_t* shadow; int emit_input;
+    int S, G; float inv_S, third;
+    const float* g[128];
+    int16_t order[128];            // neighbours: ring order of the super-learners
+    int16_t a[64], b[64];          // pair: work item w mixes super-learners a[w], b[w] (a == b: unmatched)
+};
+
+// the same code for a float4 position and for a single float
+struct V4 { typedef float4 type; };
+struct V1 { typedef float type; };
+__device__ inline float4 hy_ld_(V4, const float* p, int64_t e) { return ldnt_(p, e); }
+__device__ inline float hy_ld_(V1, const float* p, int64_t e) { return p[e]; }
+__device__ inline void hy_st_(float* p, int64_t e, const float4& v) { stnt_(p, e, v); }
+__device__ inline void hy_st_(float* p, int64_t e, float v) { p[e] = v; }
+__device__ inline void hy_emit_(bf16_t* sh, int64_t e, const float4& v) { emit4_(sh, e, v); }
+__device__ inline void hy_emit_(bf16_t* sh, int64_t e, float v) { sh[e] = f32_to_bf16(v); }
+__device__ inline float4 hy_add_(const float4& p, const float4& q) {
+    return make_float4(__fadd_rn(p.x, q.x), __fadd_rn(p.y, q.y), __fadd_rn(p.z, q.z), __fadd_rn(p.w, q.w));
+}
+__device__ inline float hy_add_(float p, float q) { return __fadd_rn(p, q); }
+__device__ inline float4 hy_mul_(const float4& p, float c) {
+    return make_float4(__fmul_rn(p.x, c), __fmul_rn(p.y, c), __fmul_rn(p.z, c), __fmul_rn(p.w, c));
+}
+__device__ inline float hy_mul_(float p, float c) { return __fmul_rn(p, c); }
+__device__ inline float4 hy_sgd_(const float4& m, float lr, const float4& g) { return pair_new_(m, lr, g); }
+__device__ inline float hy_sgd_(float m, float lr, float g) { return sgd_(m, lr, g); }
+
+// mean of super-learner a at position e; emit: also write the bf16 copy of the models read (tau = 1)
+template <class V>
+__device__ inline typename V::type hy_mean_(const HybridArgs& p, int a, int64_t e, bool emit) {
+    const int i0 = a * p.S;
+    typename V::type s = hy_ld_(V(), p.src + i0 * p.stride, e);
+    if (emit) hy_emit_(p.shadow + i0 * p.stride, e, s);
+    for (int j = 1; j < p.S; ++j) {
+        const typename V::type v = hy_ld_(V(), p.src + (i0 + j) * p.stride, e);
+        if (emit) hy_emit_(p.shadow + (i0 + j) * p.stride, e, v);
+        s = hy_add_(s, v);
+    }
+    return hy_mul_(s, p.inv_S);
+}
+template <class V>
+__device__ inline void hy_write_(const HybridArgs& p, int a, int64_t e, const typename V::type& m, bool emit_out) {
+    for (int i = a * p.S; i < (a + 1) * p.S; ++i) {
+        const typename V::type r = hy_sgd_(m, p.lr, hy_ld_(V(), p.g[i], e));
+        hy_st_(p.dst + i * p.stride, e, r);
+        if (emit_out) hy_emit_(p.shadow + i * p.stride, e, r);
+    }
+}
+
+template <class V>
+__device__ inline void hy_pair_one_(const HybridArgs& p, int a, int b, int64_t e) {
+    const bool emit_in = p.shadow && p.emit_input, emit_out = p.shadow && !p.emit_input;
+    const typename V::type ma = hy_mean_<V>(p, a, e, emit_in);
+    if (a == b) { hy_write_<V>(p, a, e, ma, emit_out); return; }
+    const typename V::type mb = hy_mean_<V>(p, b, e, emit_in);
+    const typename V::type m = hy_mul_(hy_add_(ma, mb), 0.5f);
+    hy_write_<V>(p, a, e, m, emit_out);
+    hy_write_<V>(p, b, e, m, emit_out);
+}
+
+template <class V>
+__device__ inline void hy_tri_one_(const HybridArgs& p, int64_t e) {
+    const bool emit_in = p.shadow && p.emit_input, emit_out = p.shadow && !p.emit_input;
+    const typename V::type first = hy_mean_<V>(p, p.order[0], e, emit_in);
+    if (p.G == 1) { hy_write_<V>(p, p.order[0], e, first, emit_out); return; }
+    typename V::type prev = hy_mean_<V>(p, p.order[p.G - 1], e, false), cur = first;     // read again (and copied) as "next" below
+    for (int q = 0; q < p.G; ++q) {
+        const typename V::type next = q + 1 < p.G ? hy_mean_<V>(p, p.order[q + 1], e, emit_in) : first;
+        const typename V::type m = hy_mul_(hy_add_(hy_add_(prev, cur), next), p.third);
+        hy_write_<V>(p, p.order[q], e, m, emit_out);
+        prev = cur; cur = next;
+    }
+}
+
+template <bool VEC, bool TRI>
+__global__ __launch_bounds__(256) void hybrid_update_kernel(HybridArgs p) {
+    const int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const int a = TRI ? 0 : p.a[blockIdx.y], b = TRI ? 0 : p.b[blockIdx.y];
+    if constexpr (VEC) {
+        const int64_t n4 = p.P >> 2;
+        if (e < n4) { if constexpr (TRI) hy_tri_one_<V4>(p, e); else hy_pair_one_<V4>(p, a, b, e); }
+        if (blockIdx.x == 0 && threadIdx.x < (p.P & 3)) {
+            const int64_t t = (n4 << 2) + threadIdx.x;
+            if constexpr (TRI) hy_tri_one_<V1>(p, t); else hy_pair_one_<V1>(p, a, b, t);
+        }
+    } else {
+        if (e < p.P) { if constexpr (TRI) hy_tri_one_<V1>(p, e); else hy_pair_one_<V1>(p, a, b, e); }
+    }
+}
+
+static hipError_t launch_hybrid(const UpdateDesc& d, bool vec, hipStream_t s) {
+    const int S = d.group_size, L = d.L;
+    if (S < 1 || L % S != 0) return hipErrorInvalidValue;
+    const int G = L / S;
+    const bool tri = d.mix == 4;
+    if (tri && G == 2) return hipErrorInvalidValue;
+    for (int i = 0; i < L; ++i)
+        if (!d.active[i]) return hipErrorInvalidValue;          // super-learners average synchronously: everybody takes part
+    HybridArgs a;
+    a.src = d.src; a.dst = d.dst; a.stride = d.stride; a.P = d.P; a.lr = d.lr;
+    a.shadow = d.shadow; a.emit_input = d.emit_input;
+    a.S = S; a.G = G; a.inv_S = 1.0f / (float)S; a.third = 1.0f / 3.0f;
+    for (int i = 0; i < 128; ++i) { a.g[i] = i < L ? d.g[i] : nullptr; a.order[i] = 0; }
+    for (int i = 0; i < 64; ++i) a.a[i] = a.b[i] = 0;
+    bool seen[128] = {false};
+    for (int q = 0; q < G; ++q) {      // the ring order must be a permutation of the super-learners, the matching an involution
+        const int o = d.order[q], pq = d.partner[q];
+        if (o < 0 || o >= G || seen[o] || pq < 0 || pq >= G || d.partner[pq] != q) return hipErrorInvalidValue;
+        seen[o] = true; a.order[q] = (int16_t)o;
+    }
+    const int64_t n = vec ? ((d.P >> 2) > 0 ? (d.P >> 2) : 1) : d.P;
+    const unsigned blocks = (unsigned)((n + 255) / 256);
+    if (tri) {
+        if (vec) hipLaunchKernelGGL((hybrid_update_kernel<true, true>), dim3(blocks), dim3(256), 0, s, a);
+        else hipLaunchKernelGGL((hybrid_update_kernel<false, true>), dim3(blocks), dim3(256), 0, s, a);
+        return hipGetLastError();
+    }
+    int nw = 0;
+    for (int q = 0; q < G; ++q) {
+        const int j = d.partner[q];
+        if (j == q || q < j) {
+            if (nw >= 64) return hipErrorInvalidValue;
+            a.a[nw] = (int16_t)q; a.b[nw] = (int16_t)j; ++nw;
+        }
+    }
+    if (vec) hipLaunchKernelGGL((hybrid_update_kernel<true, false>), dim3(blocks, (unsigned)nw), dim3(256), 0, s, a);
+    else hipLaunchKernelGGL((hybrid_update_kernel<false, false>), dim3(blocks, (unsigned)nw), dim3(256), 0, s, a);
+    return hipGetLastError();
+}
+
 __global__ __launch_bounds__(256) void average_kernel(const float* x, int64_t stride, int L, int64_t P,
                                                       float inv_L, float* out) {
     const int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x;
@@ -305,6 +444,7 @@ hipError_t launch_update(const UpdateDesc& d, hipStream_t s) {
     for (int i = 0; i < d.L; ++i)
         if ((uintptr_t)d.g[i] % 16 != 0) vec = false;
     if (d.update_first && d.mix != 2) return hipErrorInvalidValue;
+    if (d.mix == 3 || d.mix == 4) return launch_hybrid(d, vec, s);
     if (d.mix == 2) {
         AllArgs a;
         a.src = d.src; a.dst = d.dst; a.stride = d.stride; a.P = d.P; a.lr = d.lr; a.L = d.L;

@@ -70,6 +70,47 @@ def test_config_validation_and_workspace_size():
         assert ei.value.code == Bd.EINVAL and Bd.adpsgd_last_error()
 
 
+def test_hybrid_mixing_configurations():
+    ok = [Bd.make_config(8, Bd.FIXED_RING, flat_params=8, mix=Bd.MIX_HYBRID_PAIR, group_size=2),
+          Bd.make_config(8, Bd.RANDOM_RING, flat_params=8, mix=Bd.MIX_HYBRID_PAIR, group_size=8),
+          Bd.make_config(12, Bd.RANDOM_RING, flat_params=8, mix=Bd.MIX_HYBRID_TRI, group_size=4),
+          Bd.make_config(12, Bd.FIXED_RING, flat_params=8, mix=Bd.MIX_HYBRID_TRI, group_size=12),
+          Bd.make_config(12, Bd.FIXED_RING, flat_params=8, mix=Bd.MIX_HYBRID_TRI, group_size=1, tau=1)]
+    for cfg in ok:
+        assert Bd.adpsgd_workspace_bytes(cfg) > 0
+    bad = [Bd.make_config(8, Bd.FIXED_RING, flat_params=8, mix=Bd.MIX_HYBRID_PAIR, group_size=3),      # 8 is not a multiple of 3
+           Bd.make_config(8, Bd.FIXED_RING, flat_params=8, mix=Bd.MIX_HYBRID_PAIR, group_size=0),
+           Bd.make_config(8, Bd.FIXED_RING, flat_params=8, mix=Bd.MIX_HYBRID_TRI, group_size=4),       # a ring of two super-learners
+           Bd.make_config(8, Bd.D1D, flat_params=8, mix=Bd.MIX_HYBRID_PAIR, group_size=2),
+           Bd.make_config(8, Bd.SDPSGD, flat_params=8, mix=Bd.MIX_HYBRID_PAIR, group_size=2),
+           Bd.make_config(8, Bd.RANDOM_RING, flat_params=8, mix=Bd.MIX_HYBRID_PAIR, group_size=2, straggler_p=0.1),
+           Bd.make_config(8, Bd.RANDOM_RING, flat_params=8, mix=Bd.MIX_PAIR, group_size=2),            # group_size without a hybrid mix
+           Bd.make_config(8, Bd.RANDOM_RING, flat_params=8, mix=5, group_size=2)]
+    for cfg in bad:
+        with pytest.raises(Bd.AdpsgdError) as ei:
+            Bd.adpsgd_workspace_bytes(cfg)
+        assert ei.value.code == Bd.EINVAL and Bd.adpsgd_last_error()
+
+
+def test_learning_rate_helper_matches_the_oracle_and_the_papers_figures():
+    from oracle import lr as LR
+    with open(os.path.join(ROOT, "tests", "golden", "lr_schedule_paper.txt")) as fh:
+        rows = [ln.split() for ln in fh if ln.strip() and not ln.startswith("#")]
+    for name, epoch, rate in rows:
+        args = (0.1, 0.0, 0, 10) if name == "baseline" else (3.2, 0.32, 10, 10)
+        got = Bd.adpsgd_lr_at_epoch(int(epoch), *args)
+        assert abs(got - float(rate)) <= 1.2e-7 * float(rate), (name, epoch, got)
+    import numpy as np
+    for epoch in range(1, 21):
+        for peak, start, warm, hold in ((0.1, 0.0, 0, 10), (3.2, 0.32, 10, 10), (1.5, 0.5, 3, 7), (0.7, 0.1, 1, 1)):
+            # float arguments reach the library as float32: feed the oracle the same rounded values
+            ref = LR.lr_at_epoch(epoch, float(np.float32(peak)), start=float(np.float32(start)), warmup_epochs=warm, hold_until=hold)
+            assert Bd.adpsgd_lr_at_epoch(epoch, peak, start, warm, hold) == np.float32(ref)
+    for bad in ((0, 0.1, 0.0, 0, 10), (1, 0.1, 0.0, -1, 10)):
+        with pytest.raises(Bd.AdpsgdError):
+            Bd.adpsgd_lr_at_epoch(*bad)
+
+
 def test_create_rejects_a_missing_workspace():
     cfg = Bd.make_config(2, 0, flat_params=8)
     with pytest.raises(Bd.AdpsgdError) as ei:

@@ -8,7 +8,7 @@ from oracle import adpsgd as A
 pytestmark = pytest.mark.gpu
 
 
-def _run(L, P, pattern, steps, p=0.0, mix=None, tau=None, seed=3, lr=0.1):
+def _run(L, P, pattern, steps, p=0.0, mix=None, tau=None, seed=3, lr=0.1, group_size=0):
     import torch
     from paper_2110_11199_amd import binding as Bd
     r = np.random.default_rng(seed)
@@ -17,16 +17,19 @@ def _run(L, P, pattern, steps, p=0.0, mix=None, tau=None, seed=3, lr=0.1):
     #                                                               them still sum below the float32 maximum)
     g = (r.standard_normal((L, P)) * 1e-3).astype(np.float32)
     cfg = Bd.make_config(L, pattern, seed=seed, flat_params=P, straggler_p=p,
-                         mix=Bd.MIX_DEFAULT if mix is None else mix, tau=-1 if tau is None else tau)
+                         mix=Bd.MIX_DEFAULT if mix is None else mix, tau=-1 if tau is None else tau, group_size=group_size)
     eng = Bd.Adpsgd(cfg)
     for i in range(L):
         eng.set_params(i, torch.from_numpy(x0[i]).cuda())
     gd = [torch.from_numpy(g[i]).cuda() for i in range(L)]
-    ora = A.Oracle(L, pattern, seed, flat_params=P, x0=x0, straggler_p=p, mix=mix, tau=tau)
+    ora = A.Oracle(L, pattern, seed, flat_params=P, x0=x0, straggler_p=p, mix=mix, tau=tau, group_size=max(group_size, 1))
+    G = L // group_size if group_size else L
     for k in range(steps):
         eng.step(gd, lr)
         ora.step(None, lr, grads=g)
-        assert eng.schedule(k) == tuple(ora.last_schedule)
+        got_s = eng.schedule(k)
+        assert tuple(v[:G] for v in got_s) == tuple(ora.last_schedule)
+        assert all(v[G:] == [-1] * (L - G) for v in got_s)
         got = np.stack([eng.params(i).cpu().numpy() for i in range(L)])
         assert (got.view(np.uint32) == ora.x.view(np.uint32)).all(), (k, np.abs(got - ora.x).max())
     eng.close()
@@ -93,6 +96,43 @@ def test_consensus_distance_and_its_contraction(L, P):
         assert abs(got - ref) <= 1e-11 * max(ref, 1e-30), (k, got, ref)      # both fp64, different summation order
         eng.step(gz, 0.0)
         ora.step(None, 0.0, grads=zero)
+    eng.close()
+
+
+@pytest.mark.parametrize("mix", [S.MIX_HYBRID_PAIR, S.MIX_HYBRID_TRI])
+@pytest.mark.parametrize("L,Sz", [(8, 2), (12, 4), (15, 3), (16, 1), (16, 16), (6, 1), (128, 2), (128, 8), (10, 2)])
+def test_hybrid_super_learner_mixing(mix, L, Sz):
+    # Section V: synchronous mean inside super-learners of Sz learners, the ring operator across them; bit-exact, in place
+    if mix == S.MIX_HYBRID_TRI and L // Sz == 2:
+        pytest.skip("a ring of two super-learners has no distinct left and right neighbour")
+    print("update hybrid", mix, L, Sz, flush=True)
+    for pattern in (S.FIXED_RING, S.RANDOM_RING):
+        _run(L, 70001 if L < 100 else 1003, pattern, 4, mix=mix, group_size=Sz)
+
+
+@pytest.mark.parametrize("P", [1, 3, 4, 1023, 100003, 1 << 20])
+def test_hybrid_super_learner_mixing_sizes_and_delay(P):
+    _run(12, P, S.RANDOM_RING, 4, mix=S.MIX_HYBRID_PAIR, group_size=3)
+    _run(12, P, S.FIXED_RING, 4, mix=S.MIX_HYBRID_TRI, group_size=3)
+    _run(12, P, S.RANDOM_RING, 3, mix=S.MIX_HYBRID_TRI, group_size=2, tau=1)      # ping-pong buffers
+    _run(12, P, S.FIXED_RING, 3, mix=S.MIX_HYBRID_PAIR, group_size=6, tau=1)
+
+
+def test_hybrid_mixing_alone_makes_every_super_learner_identical():
+    import torch
+    from paper_2110_11199_amd import binding as Bd
+    L, Sz, P = 12, 4, 10007
+    r = np.random.default_rng(5)
+    eng = Bd.Adpsgd(Bd.make_config(L, S.RANDOM_RING, flat_params=P, mix=Bd.MIX_HYBRID_TRI, group_size=Sz))
+    for i in range(L):
+        eng.set_params(i, torch.from_numpy(r.uniform(-1, 1, P).astype(np.float32)).cuda())
+    before = eng.average().cpu().numpy().astype(np.float64)
+    eng.step([torch.zeros(P, device="cuda") for _ in range(L)], 0.0)
+    for a in range(L // Sz):
+        first = eng.params(a * Sz).cpu().numpy().view(np.uint32)
+        for i in range(a * Sz + 1, (a + 1) * Sz):
+            assert (eng.params(i).cpu().numpy().view(np.uint32) == first).all()
+    assert np.abs(eng.average().cpu().numpy() - before).max() < 1e-6      # doubly stochastic: the learner average stays
     eng.close()
 
 
