@@ -219,6 +219,21 @@ int adpsgd_average(adpsgd_t h, float* dev_out);
  * value.                                                                        */
 int adpsgd_consensus(adpsgd_t h, double* host_out);
 
+/* For callers that cannot allocate (code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc): the consensus distance of adpsgd_consensus without a
+ * handle and without a workspace.  dev_x: device, L models of P floats each, model i at
+ * dev_x + i * stride (stride >= P, in floats); dev_out: device, one double (8-byte aligned),
+ * written on the stream; the call does not wait and copies nothing to the host.  Same
+ * kernels, same summation order and so the same value, bit for bit, as adpsgd_consensus.
+ * The per-workgroup partial sums (2048 doubles, 16 KB) live in a device array inside the
+ * library, one copy per GPU, held until the process ends; the call allocates nothing
+ * (no hipMalloc, no hipFree, no workspace).  Limits: 1 <= L <= 128 and L * P <=
+ * ADPSGD_STATIC_MAX_ELEMENTS, otherwise ADPSGD_EINVAL.  Every call on a GPU shares that
+ * GPU's array: calls that overlap in time on one GPU (different streams or threads) race
+ * and must be serialised by the caller.  Runs on the current device.              */
+#define ADPSGD_STATIC_MAX_ELEMENTS (((int64_t)1) << 34)
+int adpsgd_consensus_static(const float* dev_x, int64_t stride, int32_t L, int64_t P, double* dev_out, void* hip_stream);
+
 /* Per-phase GPU time of a step, taken with HIP events recorded on the handle's
  * stream at every change of phase (no host synchronisation inside the step).
  * Phases: 0 minibatch staging + bf16 weight copy, 1 time-batched GEMMs,

@@ -60,6 +60,7 @@ _lib.adpsgd_iteration.argtypes = [_vp]
 _lib.adpsgd_iteration.restype = _i64
 _lib.adpsgd_average.argtypes = [_vp, _vp]
 _lib.adpsgd_consensus.argtypes = [_vp, C.POINTER(C.c_double)]
+_lib.adpsgd_consensus_static.argtypes = [_vp, _i64, C.c_int32, _i64, _vp, _vp]
 _lib.adpsgd_set_profiling.argtypes = [_vp, C.c_int]
 _lib.adpsgd_profile.argtypes = [_vp, C.POINTER(C.c_float), _i32p, C.POINTER(C.c_double), C.POINTER(C.c_double)]
 _lib.adpsgd_destroy.argtypes = [_vp]
@@ -74,7 +75,8 @@ EXPORTS = ["adpsgd_workspace_bytes", "adpsgd_create", "adpsgd_step", "adpsgd_par
            "adpsgd_grads", "adpsgd_losses", "adpsgd_param_count", "adpsgd_layout_count", "adpsgd_layout",
            "adpsgd_schedule", "adpsgd_schedule_of", "adpsgd_iteration", "adpsgd_average", "adpsgd_destroy",
            "adpsgd_last_error", "adpsgd_gemm", "adpsgd_set_profiling", "adpsgd_profile",
-           "adpsgd_set_tuning", "adpsgd_consensus", "adpsgd_status", "adpsgd_lr_at_epoch"]
+           "adpsgd_set_tuning", "adpsgd_consensus", "adpsgd_status", "adpsgd_consensus_static", "adpsgd_lr_at_epoch"]
+STATIC_MAX_ELEMENTS = 1 << 34
 TUNE_GEMM_TILE, TUNE_REC_DIRECT, TUNE_REC_FWD_GROUPS, TUNE_REC_PERSISTENT, TUNE_REC_WAIT_US = 0, 1, 2, 3, 4
 PHASES = ["stage_cast", "batched_gemm", "recurrent_fwd", "recurrent_bwd", "softmax_ce", "bias_colsum", "mix_update"]
 
@@ -179,6 +181,10 @@ def adpsgd_consensus(h):
     out = C.c_double(0.0)
     _check(_lib.adpsgd_consensus(h, C.byref(out)))
     return out.value
+
+
+def adpsgd_consensus_static(dev_x_ptr, stride, L, P, dev_out_ptr, stream_ptr):
+    _check(_lib.adpsgd_consensus_static(dev_x_ptr, stride, L, P, dev_out_ptr, stream_ptr))
 
 
 def adpsgd_set_profiling(h, enable):

@@ -848,6 +848,17 @@ int adpsgd_consensus(adpsgd_t h, double* host_out) {
     return ADPSGD_OK;
 }
 
+int adpsgd_consensus_static(const float* dev_x, int64_t stride, int32_t L, int64_t P, double* dev_out, void* hip_stream) {
+    if (!dev_x || !dev_out) return fail(ADPSGD_EINVAL, "NULL argument");
+    if (L < 1 || L > ADPSGD_MAX_LEARNERS) return fail(ADPSGD_EINVAL, "L must be in 1..128");
+    if (P < 1 || stride < P) return fail(ADPSGD_EINVAL, "P must be >= 1 and stride >= P");
+    if ((uintptr_t)dev_out % 8 != 0 || (uintptr_t)dev_x % 4 != 0) return fail(ADPSGD_EINVAL, "misaligned pointer");
+    if (P > ADPSGD_STATIC_MAX_ELEMENTS / L)
+        return fail(ADPSGD_EINVAL, "input beyond the maximum of the allocation-free entry point: L * P must not exceed 2^34 elements");
+    HIPCHK(launch_consensus_static(dev_x, stride, L, P, dev_out, (hipStream_t)hip_stream), "consensus distance (static scratch)");
+    return ADPSGD_OK;
+}
+
 int adpsgd_set_profiling(adpsgd_t h, int enable) {
     if (!h) return fail(ADPSGD_EINVAL, "NULL handle");
     h->prof.on = enable != 0;

@@ -57,6 +57,9 @@ hipError_t launch_average(const float* x, int64_t stride, int L, int64_t P, floa
 // out[0] = sum_i sum_e (x_i[e] - mean_i x_i[e])^2 in fp64; partial: kConsensusBlocks doubles of scratch
 constexpr int kConsensusBlocks = 2048;
 hipError_t launch_consensus(const float* x, int64_t stride, int L, int64_t P, double* partial, double* out, hipStream_t s);
+// the same with the partial sums in a device array owned by the library (one per GPU, shared by all calls on it)
+constexpr int kMaxDevices = 64;
+hipError_t launch_consensus_static(const float* x, int64_t stride, int L, int64_t P, double* out, hipStream_t s);
 
 // ---- LSTM gradient pieces -------------------------------------------------------
 struct StageDesc {             // copy / cast the minibatches into the workspace

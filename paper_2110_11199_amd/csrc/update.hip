@@ -11,6 +11,7 @@
 //     x_i <- m - (lr * g_i)
 // Synchronous baseline (Section III-A, Algorithm 2), the same operations in the other order:
 //     u_j = x_j - (lr * g_j);   x_i <- (((u_0 + u_1) + ...)) * (1/L) for every i
+#include <mutex>
 #include "kernels.hpp"
 
 namespace adpsgd {
@@ -552,6 +553,42 @@ hipError_t launch_consensus(const float* x, int64_t stride, int L, int64_t P, do
     if (blocks > kConsensusBlocks) blocks = kConsensusBlocks;
     hipLaunchKernelGGL(consensus_partial_kernel, dim3((unsigned)blocks), dim3(256), 0, s, x, stride, L, P, partial);
     hipLaunchKernelGGL(consensus_final_kernel, dim3(1), dim3(256), 0, s, partial, (int)blocks, out);
+    return hipGetLastError();
+}
+
+// ---- the same reduction for callers that cannot allocate ----------------------------------------
+// The per-workgroup partial sums live in a file-scope device array instead of caller-provided memory.
+// Every GPU holds its own copy of the array at its own address: the address is looked up once per device,
+// with that device current, and only that address (never the array's name, which is a host-side stand-in
+// in host code) is handed to kernels.  All calls on one GPU share the array: calls that overlap on one GPU
+// race.  Nothing in it has to start at zero (a call writes every partial sum it later reads).
+static __device__ __align__(256) double scratch[kConsensusBlocks];
+
+static std::mutex g_scratch_mutex;
+static double* g_scratch_ptr[kMaxDevices] = {nullptr};
+
+hipError_t launch_consensus_static(const float* x, int64_t stride, int L, int64_t P, double* out, hipStream_t s) {
+    if (L < 1 || P < 1) return hipErrorInvalidValue;
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    double* ptr = nullptr;
+    {
+        std::lock_guard<std::mutex> lock(g_scratch_mutex);
+        if (!g_scratch_ptr[dev]) {
+            void* p = nullptr;
+            e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+            if (e != hipSuccess) return e;
+            if (!p) return hipErrorInvalidSymbol;
+            g_scratch_ptr[dev] = (double*)p;
+        }
+        ptr = g_scratch_ptr[dev];
+    }
+    int64_t blocks = (P + 255) / 256;
+    if (blocks > kConsensusBlocks) blocks = kConsensusBlocks;
+    hipLaunchKernelGGL(consensus_partial_kernel, dim3((unsigned)blocks), dim3(256), 0, s, x, stride, L, P, ptr);
+    hipLaunchKernelGGL(consensus_final_kernel, dim3(1), dim3(256), 0, s, (const double*)ptr, (int)blocks, out);
     return hipGetLastError();
 }
 

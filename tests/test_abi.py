@@ -124,3 +124,10 @@ def test_argument_checks_that_need_no_gpu():
         with pytest.raises(Bd.AdpsgdError) as ei:
             call()
         assert ei.value.code == Bd.EINVAL
+    fake = 0x10000      # never dereferenced: the size checks come first
+    for ptr, stride, L, P, out in ((None, 8, 2, 8, fake), (fake, 8, 2, 8, None), (fake, 8, 0, 8, fake), (fake, 8, 129, 8, fake),
+                                   (fake, 4, 2, 8, fake), (fake, 8, 2, 0, fake), (fake, 8, 2, 8, fake + 4),
+                                   (fake, 1 << 40, 128, (Bd.STATIC_MAX_ELEMENTS >> 7) + 1, fake)):
+        with pytest.raises(Bd.AdpsgdError) as ei:
+            Bd.adpsgd_consensus_static(ptr, stride, L, P, out, None)
+        assert ei.value.code == Bd.EINVAL and Bd.adpsgd_last_error()
