@@ -52,7 +52,7 @@ __device__ inline bool wait_for_(const PersistDesc& p, uint32_t* cnt, uint32_t t
             }
             __builtin_amdgcn_s_sleep(1);
         }
-        __atomic_thread_fence(__ATOMIC_ACQUIRE);      // device scope: what the other workgroups stored before they arrived
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");   // device scope: what the other workgroups stored before they arrived
         *flag_lds = ok;
     }
     __syncthreads();
@@ -61,11 +61,27 @@ __device__ inline bool wait_for_(const PersistDesc& p, uint32_t* cnt, uint32_t t
     return ok;
 }
 
+// Tuning aid: wall-clock stamp number k of frame s, taken by thread 0 of workgroup 0 when a trace buffer is given.
+__device__ inline void stamp_(const PersistDesc& p, int s, int k) {
+    if (p.trace && blockIdx.x == 0 && threadIdx.x == 0) p.trace[s * 8 + k] = wall_clock64();
+}
+// Index of the XCD (accelerator die, each with its own L2) this wave runs on: the XCC_ID hardware register.
+__device__ inline uint32_t xcd_id_() { return __builtin_amdgcn_s_getreg(20 | (0 << 6) | ((4 - 1) << 11)) & 15u; }
+__device__ inline void stamp_place_(const PersistDesc& p, int T) {
+    if (p.trace && threadIdx.x == 0) p.trace[T * 8 + blockIdx.x] = xcd_id_();
+}
+
 // All threads have stored their part of the frame's operand: make it visible, then count this workgroup in.
-__device__ inline void arrive_(uint32_t* cnt) {
-    __threadfence();
+// Every thread first waits until its own stores have been accepted by L2 (the vector L1 writes through), the
+// workgroup meets, and ONE thread then releases at device scope (one L2 write-back per workgroup instead of one per
+// wave: that write-back is what a release costs) and counts the workgroup in.
+__device__ inline void arrive_(uint32_t* cnt, bool write_back) {
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
-    if (threadIdx.x == 0) __hip_atomic_fetch_add(cnt, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (threadIdx.x == 0) {
+        if (write_back) __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
+        __hip_atomic_fetch_add(cnt, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
 }
 
 }  // namespace
@@ -150,13 +166,29 @@ __global__ __launch_bounds__(256, 1) void rec_forward_persist_kernel(PersistDesc
     float cst[PP];
 #pragma unroll
     for (int i = 0; i < PP; ++i) cst[i] = 0.f;
+    // The activated gates and the cell state of a frame (for the backward pass) are not stored right after they are
+    // computed: their 5 * PP stores per lane would only queue behind HBM while the wave has nothing else to issue.
+    // They stay in registers and go out one by one between the MFMAs of the next frame's K loop.
+    float gi[PP], gf[PP], gg[PP], go[PP];
+    float* pend_g = nullptr;             // base pointers of the frame whose results are pending (wave-uniform)
+    float* pend_c = nullptr;
+    auto store_pending = [&](auto j_) {  // pending store number j: gate j % 5 (4 = cell state) of position j / 5
+        constexpr int j = decltype(j_)::value, i = j / 5, q = j % 5;
+        const int ur = ucell_<MT>(wave, i);
+        if (ur + 4 * g >= B) return;
+        if constexpr (q == 4) stg_(cst[i], pend_c + (int64_t)ur * H, voff_c);
+        else stg_(q == 0 ? gi[i] : q == 1 ? gf[i] : q == 2 ? gg[i] : go[i], pend_g + (int64_t)ur * G4 + q * H, voff_g);
+    };
 
+    stamp_place_(p, T);
     load_preact(d == 0 ? 0 : T - 1);
     for (int s = 0; s < T; ++s) {
         const int t = d == 0 ? s : T - 1 - s;
         const int tp = d == 0 ? t - 1 : t + 1;
+        stamp_(p, s, 0);
         if (s > 0) {
             if (!wait_for_(p, cnt, W * (uint32_t)s, &wait_flag)) return;
+            stamp_(p, s, 1);
             a.base = per_frame_((const bf16_t*)r.y + li * r.sYi + (int64_t)tp * B * DH + (int64_t)d * H);
             unroll_<0, NS>([&](auto st) {
                 constexpr int S0 = decltype(st)::value;
@@ -185,10 +217,15 @@ __global__ __launch_bounds__(256, 1) void rec_forward_persist_kernel(PersistDesc
                     }
 #pragma unroll
                     for (int mt = 0; mt < MT; ++mt) mma_chunk<bf16_t>(acc[mt], af[c & 1][mt], wreg[kt * (KS / 16) + c]);
+                    // the previous frame's results: stores j0 .. j1-1 of the 5 * PP go out with this k-step
+                    constexpr int kidx = kt * (KS / 16) + c;
+                    constexpr int j0 = kidx * (5 * PP) / KSTEPS, j1 = (kidx + 1) * (5 * PP) / KSTEPS;
+                    unroll_<j0, j1>(store_pending);
                     __builtin_amdgcn_sched_barrier(0);
                 });
             });
         }
+        stamp_(p, s, 2);
         // swap gates between the waves: ex[gate][row][unit]
         float* ex = (float*)lds;
         __syncthreads();                 // the stage buffers are no longer read
@@ -197,7 +234,6 @@ __global__ __launch_bounds__(256, 1) void rec_forward_persist_kernel(PersistDesc
 #pragma unroll
             for (int i = 0; i < 16; ++i) ex[(wave * BM + urow_(mt, i) + 4 * g) * 32 + n] = acc[mt][i];
         __syncthreads();
-        float gi[PP], gf[PP], gg[PP], go[PP];
         uint32_t hb[PP];
 #pragma unroll
         for (int i = 0; i < PP; ++i) {
@@ -216,21 +252,17 @@ __global__ __launch_bounds__(256, 1) void rec_forward_persist_kernel(PersistDesc
             for (int i = 0; i < PP; ++i)
                 if (ucell_<MT>(wave, i) + 4 * g < B) *(bf16_t*)((char*)(yp + (int64_t)ucell_<MT>(wave, i) * DH) + voff_y) = (bf16_t)hb[i];
         }
-        if (s + 1 < T) arrive_(cnt);
-        // activated gates and the cell state, for the backward pass
-        {
-            float* gp = per_frame_(gates_u + (int64_t)t * B * G4);
-            float* cp = per_frame_(cbuf_u + (int64_t)t * B * H);
-#pragma unroll
-            for (int i = 0; i < PP; ++i) {
-                const int ur = ucell_<MT>(wave, i);
-                if (ur + 4 * g >= B) continue;
-                float* rp = gp + (int64_t)ur * G4;
-                stg_(gi[i], rp, voff_g); stg_(gf[i], rp + H, voff_g); stg_(gg[i], rp + 2 * H, voff_g); stg_(go[i], rp + 3 * H, voff_g);
-                stg_(cst[i], cp + (int64_t)ur * H, voff_c);
-            }
-        }
+        stamp_(p, s, 3);
+        if (s + 1 < T) arrive_(cnt, !p.same_xcd_release);
+        stamp_(p, s, 4);
+        // activated gates and the cell state, for the backward pass: pending until the next frame's K loop; the
+        // first frame is followed by no K loop of its own results' age (frame 0 runs none), the last by none at all
+        pend_g = per_frame_(gates_u + (int64_t)t * B * G4);
+        pend_c = per_frame_(cbuf_u + (int64_t)t * B * H);
+        if (s + 1 == T) unroll_<0, 5 * PP>(store_pending);
+        stamp_(p, s, 5);
         if (s + 1 < T) load_preact(d == 0 ? s + 1 : T - 2 - s);
+        stamp_(p, s, 6);
     }
 }
 
@@ -304,8 +336,10 @@ __global__ __launch_bounds__(256, 1) void rec_backward_persist_kernel(PersistDes
         float dh[PP];
 #pragma unroll
         for (int i = 0; i < PP; ++i) dh[i] = 0.f;
+        stamp_(p, s, 0);
         if (s > 0) {
             if (!wait_for_(p, cnt, W * (uint32_t)s, &wait_flag)) return;
+            stamp_(p, s, 1);
             f32x16_t acc[MT];
 #pragma unroll
             for (int mt = 0; mt < MT; ++mt)
@@ -341,6 +375,7 @@ __global__ __launch_bounds__(256, 1) void rec_backward_persist_kernel(PersistDes
                     __builtin_amdgcn_sched_barrier(0);
                 });
             });
+            stamp_(p, s, 2);
             // add the four waves' partial products in a fixed order
             float* red = (float*)lds;
             __syncthreads();             // every wave is done with its stage buffers
@@ -357,6 +392,7 @@ __global__ __launch_bounds__(256, 1) void rec_backward_persist_kernel(PersistDes
             }
             __syncthreads();             // red overlaps the stage buffers of the next frame
         }
+        stamp_(p, s, 3);
         // cell backward for this lane's positions
         float cs[4] = {0.f, 0.f, 0.f, 0.f};
         uint32_t pk0[PP], pk1[PP];
@@ -405,7 +441,9 @@ __global__ __launch_bounds__(256, 1) void rec_backward_persist_kernel(PersistDes
                 *(bf16_t*)(rp + 4 * H) = (bf16_t)(pk1[i] & 0xffffu); *(bf16_t*)(rp + 6 * H) = (bf16_t)(pk1[i] >> 16);
             }
         }
-        if (s + 1 < T) arrive_(cnt);
+        stamp_(p, s, 4);
+        if (s + 1 < T) arrive_(cnt, !p.same_xcd_release);
+        stamp_(p, s, 5);
         // bias gradient: column sums of da over the rows of the tile, in a fixed order (lane pair, then the waves)
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
@@ -419,6 +457,7 @@ __global__ __launch_bounds__(256, 1) void rec_backward_persist_kernel(PersistDes
             r.dbp[li * r.sDBi + (int64_t)t * G4 + (int64_t)d * 4 * H + (int64_t)q * H + u0 + col] = sum;
         }
         __syncthreads();                 // csum is rewritten in the next frame
+        stamp_(p, s, 6);
     }
 }
 
