@@ -148,6 +148,44 @@ def cpu_baseline(wl, seed=0, budget_s=12.0):
     return out
 
 
+def measured_peaks():
+    """What this device attains on the two resources the kernels are bound by (probe kernels of the library):
+    a register-only bf16 MFMA loop, and streaming passes with the read:write mixes of the update kernels."""
+    import torch
+    from paper_2110_11199_amd import binding as Bd
+    st = torch.cuda.current_stream().cuda_stream
+
+    def timed(fn, reps=5):
+        fn()
+        torch.cuda.synchronize()
+        best = None
+        for _ in range(reps):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(); fn(); e1.record()
+            torch.cuda.synchronize()
+            ms = e0.elapsed_time(e1)
+            best = ms if best is None else min(best, ms)
+        return best * 1e-3
+    blocks, iters = 1024, 4000
+    out = torch.empty(blocks * 256, dtype=torch.float32, device="cuda")
+    t = timed(lambda: Bd.adpsgd_probe_mfma(out.data_ptr(), blocks, iters, st))
+    res = {"mfma_bf16_TFLOPs": blocks * 4 * iters * 8 * 32768.0 / t / 1e12}
+    elems = 135_000_000                                 # one model of the mixing/update stress workload per stream
+    pitch = (elems * 4 + 255) // 256 * 256
+    buf = torch.zeros(64 * pitch, dtype=torch.uint8, device="cuda")
+    for name, (r, w4, w2) in (("hbm_read_GBps", (1, 0, 0)), ("hbm_copy_GBps", (1, 1, 0)),
+                              ("hbm_2read_1write_GBps", (2, 1, 0)), ("hbm_2read_1write_1bf16_GBps", (2, 1, 1)),
+                              ("hbm_2read_1write_x2_GBps", (4, 2, 0)), ("hbm_2read_1write_1bf16_x16_GBps", (32, 16, 16))):
+        t = timed(lambda: Bd.adpsgd_probe_stream(r, w4, w2, buf.data_ptr(), pitch, elems, st), reps=3)
+        res[name] = elems * (4 * r + 4 * w4 + 2 * w2) / t / 1e9
+    del buf, out
+    torch.cuda.empty_cache()
+    res["note"] = ("probe kernels of the library: register-only v_mfma_f32_32x32x16_bf16 loop; streaming passes over "
+                   "streams of 135e6 floats with the read:write mixes of the update kernels, one position of 1, 2 (x2) or 16 "
+                   "(x16) learners' streams per thread (best of 3)")
+    return res
+
+
 TRAFFIC_FILE = os.path.join(ROOT, "profiles", "hbm_traffic_cfg4_cfg5.txt")
 
 
@@ -188,6 +226,9 @@ def main():
     ap.add_argument("--workload", default="cfg4", choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5"])
     ap.add_argument("--mix-steps", type=int, default=20, help="timed steps of the cfg5 mixing/update leg (0 = skip)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-straggler-model", action="store_true",
+                    help="skip the wall-clock model of the slow-learner experiment (a few seconds)")
+    ap.add_argument("--no-peaks", action="store_true", help="skip the attained-peak probes (MFMA loop, streaming mixes)")
     ap.add_argument("--tri", action="store_true", help="also time the ring-neighbour (weights 1/3) mixing kernel on the cfg5 shape")
     ap.add_argument("--sync", action="store_true", help="also time the synchronous baseline's update-then-mean kernel on the cfg5 shape")
     ap.add_argument("--cfg3-steps", type=int, default=5, help="timed steps of the cfg3 leg (0 = skip)")
@@ -202,17 +243,22 @@ def main():
     tune = [tuple(int(v) for v in t.split(":")) for t in args.tune]
     traffic = load_traffic()
     wl = synth.WORKLOADS[args.workload]
+    peaks = None if args.no_peaks else measured_peaks()
     out = {"metric": METRIC, "unit": "frames/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
            "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "data": "synthetic"}
 
-    def hbm_roofline(prof, phases, kernel, workload, traffic_key=None):
+    def hbm_roofline(prof, phases, kernel, workload, traffic_key=None, mix_probe=None):
         ms = sum(prof[p]["ms"] for p in phases)
         nbytes = sum(prof[p]["bytes"] for p in phases)
         launches = max(sum(prof[p]["launches"] for p in phases), 1)
         gbs = nbytes / (ms * 1e-3) / 1e9 if ms > 0 else 0.0
-        return {"bound": "hbm", "achieved": gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": gbs / PEAK_HBM_GBS,
-                "traffic": traffic.get("%s/%s" % (workload, traffic_key)) if traffic_key else None, "kernel": kernel,
-                "avg_launch_ms": ms / launches, "algorithmic_bytes_per_launch": nbytes / launches}
+        r = {"bound": "hbm", "achieved": gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": gbs / PEAK_HBM_GBS,
+             "traffic": traffic.get("%s/%s" % (workload, traffic_key)) if traffic_key else None, "kernel": kernel,
+             "avg_launch_ms": ms / launches, "algorithmic_bytes_per_launch": nbytes / launches}
+        if peaks and mix_probe:      # against a pure streaming pass with the same read:write mix on this device
+            r["frac_of_attained"] = gbs / peaks[mix_probe]
+            r["attained_peak"] = {"probe": mix_probe, "GBps": peaks[mix_probe]}
+        return r
 
     if wl.flat_params:
         dt, prof, active = run_flat(wl, args.steps, args.warmup)
@@ -221,7 +267,7 @@ def main():
                     "learner_steps_per_s": active / dt,
                     "config": {"workload": wl.name, "L": wl.L, "flat_params": wl.flat_params, "pattern": "random ring",
                                "straggler_p": wl.straggler_p, "note": "model-free: no frames"},
-                    "roofline": hbm_roofline(prof, ["mix_update"], "pair_update_kernel", wl.name, "mix_update")})
+                    "roofline": hbm_roofline(prof, ["mix_update"], "pair_update_kernel", wl.name, "mix_update", "hbm_2read_1write_x2_GBps")})
         out["mix_update_GBps"] = out["roofline"]["achieved"]
     else:
         dt, prof, loss = run_model(wl, args.steps, args.warmup, tune=tune)
@@ -254,25 +300,26 @@ def main():
                          "flops_per_launch": g["work"] / max(g["launches"], 1),
                          "algorithmic_bytes_per_launch": g["bytes"] / max(g["launches"], 1)},
             "roofline_recurrent": rec,
-            "roofline_update": hbm_roofline(prof, ["mix_update"], "all_update_kernel / pair_update_kernel", wl.name, "mix_update"),
+            "roofline_update": hbm_roofline(prof, ["mix_update"], "all_update_kernel / pair_update_kernel", wl.name, "mix_update",
+                                            "hbm_2read_1write_1bf16_x16_GBps" if wl.precision else "hbm_2read_1write_x2_GBps"),
         })
         if args.mix_steps > 0:
             w5 = synth.WORKLOADS["cfg5"]
             dt5, prof5, active5 = run_flat(w5, args.mix_steps, 2)
-            r5 = hbm_roofline(prof5, ["mix_update"], "pair_update_kernel", "cfg5", "mix_update")
+            r5 = hbm_roofline(prof5, ["mix_update"], "pair_update_kernel", "cfg5", "mix_update", "hbm_2read_1write_x2_GBps")
             r5.update({"workload": "cfg5", "steps": args.mix_steps, "ms_per_step": dt5 / args.mix_steps * 1e3,
                        "learner_steps_per_s": active5 / dt5})
             out["mix_update"] = r5
             out["mix_update_GBps"] = r5["achieved"]
             if args.tri:
                 dt6, prof6, active6 = run_flat(w5, args.mix_steps, 2, variant="tri")
-                r6 = hbm_roofline(prof6, ["mix_update"], "tri_update_kernel", "cfg5")
+                r6 = hbm_roofline(prof6, ["mix_update"], "tri_update_kernel", "cfg5", None, "hbm_2read_1write_GBps")
                 r6.update({"workload": "cfg5 with ring-neighbour mixing (weights 1/3), no stragglers", "steps": args.mix_steps,
                            "ms_per_step": dt6 / args.mix_steps * 1e3, "learner_steps_per_s": active6 / dt6})
                 out["mix_update_tri"] = r6
             if args.sync:
                 dt7, prof7, active7 = run_flat(w5, args.mix_steps, 2, variant="sync")
-                r7 = hbm_roofline(prof7, ["mix_update"], "sync_update_kernel", "cfg5")
+                r7 = hbm_roofline(prof7, ["mix_update"], "sync_update_kernel", "cfg5", None, "hbm_2read_1write_GBps")
                 r7.update({"workload": "cfg5 as the synchronous baseline (update, then the mean of all 64 learners), no stragglers",
                            "steps": args.mix_steps, "ms_per_step": dt7 / args.mix_steps * 1e3, "learner_steps_per_s": active7 / dt7})
                 out["mix_update_sync"] = r7
@@ -294,9 +341,30 @@ def main():
                 "flops_per_launch": g3["work"] / max(g3["launches"], 1),
                 "phases_ms_per_step": {k: v["ms"] / args.cfg3_steps for k, v in prof3.items()},
                 "recurrent": r3,
-                "update": hbm_roofline(prof3, ["mix_update"], "all_update_kernel", "cfg3")}
+                "update": hbm_roofline(prof3, ["mix_update"], "all_update_kernel", "cfg3", None, "hbm_2read_1write_1bf16_GBps")}
+            if peaks:
+                out["roofline_cfg3"]["frac_of_attained"] = tf3 / peaks["mfma_bf16_TFLOPs"]
+        if peaks:
+            out["measured_peaks"] = peaks
+            if wl.precision:
+                out["roofline"]["frac_of_attained"] = tf / peaks["mfma_bf16_TFLOPs"]
+                out["roofline"]["attained_peak"] = {"probe": "mfma_bf16_TFLOPs", "TFLOPs": peaks["mfma_bf16_TFLOPs"]}
         if not args.no_cpu_baseline:
             out["cpu_baseline"] = cpu_baseline(wl)
+    if not args.no_straggler_model:
+        # Section IV-D: one of 16 learners 5, 10, 100 times slower; the paper's own figures (16 V100, end-to-end epochs)
+        # are quoted as context only
+        from paper_2110_11199_amd import straggler_model
+        out["straggler_model"] = {
+            "what": "wall-clock model on one GPU: idle kernels stand for the learners' gradient computations (2 ms per "
+                    "minibatch), 16 learners, model-free 4M-parameter vectors; slowdown relative to the run without a "
+                    "straggler, per iteration and per epoch (a fixed number of learner minibatches, the paper's measure)",
+            "measured": straggler_model.slowdown_table(),
+            "paper_slowdown_per_epoch_16_V100": {"fixed_ring": {"5x": 1.1, "10x": 1.1, "100x": 1.3},
+                                                 "random_ring": {"5x": 1.1, "10x": 1.1, "100x": 1.2},
+                                                 "delay_by_one": {"5x": 4.1, "10x": 8.7, "100x": 91.7}}}
+    if peaks and "measured_peaks" not in out:
+        out["measured_peaks"] = peaks
     print(json.dumps(out))
 
 

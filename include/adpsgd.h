@@ -153,6 +153,20 @@ int adpsgd_create(const adpsgd_config* cfg, void* dev_workspace, size_t bytes,
  * enqueuing work once that error has reached the host.                          */
 int adpsgd_step(adpsgd_t h, const void* const* batch_ptrs, float lr);
 
+/* The same iteration with the stragglers GIVEN by the caller instead of drawn from the seed: active: host
+ * int32 [L], 0 = learner i sits this iteration out (Section IV-D: a learner that is observed to be late; the
+ * others do not wait for it).  The ring order and the matching are those of iteration k as always; a learner
+ * matched with a straggler mixes with nobody.  A mask with a zero needs a ring pattern with pairwise mixing
+ * and tau = 0 (what straggler_p needs), otherwise ADPSGD_EINVAL.  Used by the wall-clock model of the
+ * paper's slow-learner experiment (paper_2110_11199_amd/straggler_model.py).                             */
+int adpsgd_step_masked(adpsgd_t h, const void* const* batch_ptrs, float lr, const int32_t* active);
+
+/* A kernel of one wave that does nothing for `microseconds` of wall-clock time (at most 10 000 000) and
+ * returns: stands for a learner's gradient computation on its own device in the wall-clock model of the
+ * slow-learner experiment (Section IV-D, where the slow learner is put to sleep for a set time).
+ * Asynchronous on hip_stream.                                                                            */
+int adpsgd_delay(uint64_t microseconds, void* hip_stream);
+
 /* Device pointer to learner i's current model x_i^k ([P] fp32), borrowed.  With
  * tau = 1 the two model buffers swap every iteration: query again after each
  * step.  NULL on a bad argument.                                               */
@@ -276,6 +290,22 @@ int adpsgd_gemm(int precision, int a_kmajor, int b_kmajor, int c_is_elem,
                 void* C, int64_t ldc, int64_t strideC,
                 const float* bias, int64_t strideBias,
                 int groups, int tile_config, void* hip_stream);
+
+/* Measurement probes: what the device attains on the two resources the kernels are bound by, for the
+ * benchmark to set kernel rates against an attained peak besides the published one.
+ * adpsgd_probe_mfma: a register-only loop of the bf16 MFMA instruction of the GEMM kernels; blocks workgroups
+ *   of 4 waves, iters x 8 instructions (32x32x16: 32768 flops each) per wave; dev_out: device, blocks * 256
+ *   floats (written once at the end).
+ * adpsgd_probe_stream: one streaming pass over elems positions with reads fp32 read streams, writes_f32 fp32
+ *   and writes_bf16 bf16 write streams per position (1:0:0 read only, 1:1:0 copy, 2:1:0 the pairwise update's
+ *   mix, 2:1:1 the update that also writes the bf16 model copy; 4:2:0, 4:2:2, 8:4:4, 16:8:8, 32:16:16 the same
+ *   mixes with the streams of 2 .. 16 learners owned by one thread, as in the update kernels, whose rate
+ *   falls with the number of streams a thread walks at once); the streams are consecutive slices of
+ *   dev_buf, pitch_bytes apart (dev_buf: device, 16-byte aligned, (reads + writes) * pitch_bytes long; its
+ *   contents are overwritten).  Both are asynchronous on hip_stream; EINVAL for anything else.             */
+int adpsgd_probe_mfma(float* dev_out, int blocks, int iters, void* hip_stream);
+int adpsgd_probe_stream(int reads, int writes_f32, int writes_bf16, void* dev_buf, int64_t pitch_bytes,
+                        int64_t elems, void* hip_stream);
 
 /* Tuning of ONE handle (benchmarks and tests; the defaults are the measured best):
  *   ADPSGD_TUNE_GEMM_TILE        tile configuration of the time-batched GEMMs, as tile_config above

@@ -161,13 +161,17 @@ class Oracle:
     def gradient_point(self):
         return self.x_prev if self.tau == 1 else self.x
 
-    def step(self, batches, lr, grads=None, workers=1):
+    def step(self, batches, lr, grads=None, workers=1, active=None):
         """batches: list of (feats, labels) per learner; or grads [L][P] given
         directly in model-free mode.  workers > 1 spreads the outer loop over the
         learners, whose gradients are independent of each other (Algorithm 1: the
         learners run concurrently), over that many threads; every learner's
-        arithmetic is unchanged, so the result is the same as with one."""
-        order, partner, active = S.schedule(self.pattern, self.seed, self.k, self.ring_size, self.straggler_p)
+        arithmetic is unchanged, so the result is the same as with one.
+        active: the learners that take part, given by the caller (the others are
+        the iteration's stragglers) instead of the seeded draw."""
+        if active is not None and (self.hybrid or self.tau != 0 or self.mix != S.MIX_PAIR) and not all(active):
+            raise ValueError("a learner can sit out only on a ring with pairwise mixing and tau = 0")
+        order, partner, active = S.schedule(self.pattern, self.seed, self.k, self.ring_size, self.straggler_p, active)
         self.last_schedule = (order, partner, active)
         if self.hybrid:      # the schedule is over super-learners; every learner computes a gradient
             active = [1] * self.L

@@ -79,13 +79,17 @@ def active_mask(seed, k, L, straggler_p):
     return [1 if u01(seed, STREAM_MASK, k, i) >= p else 0 for i in range(L)]
 
 
-def schedule(pattern, seed, k, L, straggler_p=0.0):
+def schedule(pattern, seed, k, L, straggler_p=0.0, active=None):
     """(order, partner, active) for iteration k.
 
     partner is the pairwise matching (an involution; partner[i] == i means that
-    learner i mixes with nobody this iteration)."""
+    learner i mixes with nobody this iteration).  active: the stragglers of the
+    iteration given by the caller (a learner that is observed to be late,
+    Section IV-D) instead of drawn with probability straggler_p."""
     order = ring_order(pattern, seed, k, L)
-    active = active_mask(seed, k, L, straggler_p)
+    active = active_mask(seed, k, L, straggler_p) if active is None else [1 if a else 0 for a in active]
+    if len(active) != L:
+        raise ValueError("one flag per learner")
     phase = (k % 2) if pattern != RANDOM_RING else 0
     partner = list(range(L))
     for m in range(L // 2):

@@ -43,6 +43,8 @@ _vp, _i64, _i32p = C.c_void_p, C.c_int64, C.POINTER(C.c_int32)
 _lib.adpsgd_workspace_bytes.argtypes = [C.POINTER(Config), C.POINTER(C.c_size_t)]
 _lib.adpsgd_create.argtypes = [C.POINTER(Config), _vp, C.c_size_t, _vp, C.POINTER(_vp)]
 _lib.adpsgd_step.argtypes = [_vp, C.POINTER(_vp), C.c_float]
+_lib.adpsgd_step_masked.argtypes = [_vp, C.POINTER(_vp), C.c_float, _i32p]
+_lib.adpsgd_delay.argtypes = [C.c_uint64, _vp]
 _lib.adpsgd_params.argtypes = [_vp, C.c_int]
 _lib.adpsgd_params.restype = _vp
 _lib.adpsgd_set_params.argtypes = [_vp, C.c_int, _vp]
@@ -69,13 +71,16 @@ _lib.adpsgd_last_error.restype = C.c_char_p
 _lib.adpsgd_gemm.argtypes = [C.c_int] * 7 + [_vp, _i64, _i64, _vp, _i64, _i64, _vp, _i64, _i64, _vp, _i64,
                                              C.c_int, C.c_int, _vp]
 _lib.adpsgd_set_tuning.argtypes = [_vp, C.c_int, C.c_int]
+_lib.adpsgd_probe_mfma.argtypes = [_vp, C.c_int, C.c_int, _vp]
+_lib.adpsgd_probe_stream.argtypes = [C.c_int, C.c_int, C.c_int, _vp, _i64, _i64, _vp]
 _lib.adpsgd_status.argtypes = [_vp]
 
 EXPORTS = ["adpsgd_workspace_bytes", "adpsgd_create", "adpsgd_step", "adpsgd_params", "adpsgd_set_params",
            "adpsgd_grads", "adpsgd_losses", "adpsgd_param_count", "adpsgd_layout_count", "adpsgd_layout",
            "adpsgd_schedule", "adpsgd_schedule_of", "adpsgd_iteration", "adpsgd_average", "adpsgd_destroy",
            "adpsgd_last_error", "adpsgd_gemm", "adpsgd_set_profiling", "adpsgd_profile",
-           "adpsgd_set_tuning", "adpsgd_consensus", "adpsgd_status", "adpsgd_consensus_static", "adpsgd_lr_at_epoch"]
+           "adpsgd_set_tuning", "adpsgd_consensus", "adpsgd_status", "adpsgd_consensus_static", "adpsgd_lr_at_epoch",
+           "adpsgd_probe_mfma", "adpsgd_probe_stream", "adpsgd_step_masked", "adpsgd_delay"]
 STATIC_MAX_ELEMENTS = 1 << 34
 TUNE_GEMM_TILE, TUNE_REC_DIRECT, TUNE_REC_FWD_GROUPS, TUNE_REC_PERSISTENT, TUNE_REC_WAIT_US = 0, 1, 2, 3, 4
 PHASES = ["stage_cast", "batched_gemm", "recurrent_fwd", "recurrent_bwd", "softmax_ce", "bias_colsum", "mix_update"]
@@ -118,6 +123,16 @@ def adpsgd_create(cfg, dev_workspace_ptr, nbytes, stream_ptr):
 def adpsgd_step(h, batch_ptrs, lr):
     arr = (_vp * len(batch_ptrs))(*batch_ptrs)
     _check(_lib.adpsgd_step(h, arr, lr))
+
+
+def adpsgd_step_masked(h, batch_ptrs, lr, active):
+    arr = (_vp * len(batch_ptrs))(*batch_ptrs)
+    act = (C.c_int32 * len(active))(*[int(a) for a in active])
+    _check(_lib.adpsgd_step_masked(h, arr, lr, act))
+
+
+def adpsgd_delay(microseconds, stream_ptr):
+    _check(_lib.adpsgd_delay(int(microseconds), stream_ptr))
 
 
 def adpsgd_params(h, i):
@@ -202,6 +217,14 @@ def adpsgd_set_tuning(h, key, value):
     _check(_lib.adpsgd_set_tuning(h, int(key), int(value)))
 
 
+def adpsgd_probe_mfma(dev_out_ptr, blocks, iters, stream_ptr):
+    _check(_lib.adpsgd_probe_mfma(dev_out_ptr, blocks, iters, stream_ptr))
+
+
+def adpsgd_probe_stream(reads, writes_f32, writes_bf16, dev_buf_ptr, pitch_bytes, elems, stream_ptr):
+    _check(_lib.adpsgd_probe_stream(reads, writes_f32, writes_bf16, dev_buf_ptr, pitch_bytes, elems, stream_ptr))
+
+
 def adpsgd_status(h):
     _check(_lib.adpsgd_status(h))
 
@@ -237,7 +260,7 @@ class Adpsgd:
         off = ptr - self.workspace.data_ptr()
         return self.workspace[off:off + 4 * n].view(self.torch.float32)
 
-    def step(self, batch_tensors, lr):
+    def step(self, batch_tensors, lr, active=None):
         """batch_tensors: model mode [(feats, labels)] per learner; flat mode [grad] per learner.
         An entry may be None (a straggler's batch is not read)."""
         ptrs = []
@@ -246,7 +269,10 @@ class Adpsgd:
                 ptrs += [b[0].data_ptr() if b[0] is not None else None, b[1].data_ptr() if b[1] is not None else None]
             else:
                 ptrs.append(b.data_ptr() if b is not None else None)
-        adpsgd_step(self.h, ptrs, lr)
+        if active is None:
+            adpsgd_step(self.h, ptrs, lr)
+        else:
+            adpsgd_step_masked(self.h, ptrs, lr, active)
 
     def params(self, i):
         return self._view(adpsgd_params(self.h, i), self.P)

@@ -684,12 +684,27 @@ int adpsgd_create(const adpsgd_config* cfg, void* dev_workspace, size_t bytes, v
     }
 }
 
-static int step_impl(adpsgd_t h, const void* const* batch_ptrs, float lr) {
+static int step_impl(adpsgd_t h, const void* const* batch_ptrs, float lr, const int32_t* given_active) {
     if (!h || !batch_ptrs) return fail(ADPSGD_EINVAL, "NULL argument");
     if (int rc = status_error(h)) return rc;
     const int L = h->L;
     int32_t order[ADPSGD_MAX_LEARNERS], partner[ADPSGD_MAX_LEARNERS], active[ADPSGD_MAX_LEARNERS];
-    if (is_hybrid(h->mix)) {
+    if (given_active) {
+        bool all = true;
+        for (int i = 0; i < L; ++i) all = all && given_active[i] != 0;
+        const bool rings = h->cfg.pattern == ADPSGD_FIXED_RING || h->cfg.pattern == ADPSGD_RANDOM_RING;
+        if (!all && (!rings || h->tau != 0 || h->mix != ADPSGD_MIX_PAIR))
+            return fail(ADPSGD_EINVAL, "a learner can sit out only on a ring pattern with pairwise mixing and tau = 0");
+        if (!is_hybrid(h->mix)) {
+            make_schedule(h->cfg.pattern, h->cfg.seed, 0.f, L, h->k, order, partner, active);
+            for (int i = 0; i < L; ++i) active[i] = given_active[i] != 0;
+            for (int i = 0; i < L; ++i)
+                if (!active[i]) { const int j = partner[i]; partner[j] = j; partner[i] = i; }
+        }
+    }
+    if (given_active && !is_hybrid(h->mix)) {
+        // schedule taken above
+    } else if (is_hybrid(h->mix)) {
         // the ring is that of the super-learners; every learner takes part
         make_schedule(h->cfg.pattern, h->cfg.seed, 0.f, L / h->cfg.group_size, h->k, order, partner, active);
         for (int i = 0; i < L; ++i) active[i] = 1;
@@ -735,9 +750,9 @@ static int step_impl(adpsgd_t h, const void* const* batch_ptrs, float lr) {
     return ADPSGD_OK;
 }
 
-int adpsgd_step(adpsgd_t h, const void* const* batch_ptrs, float lr) {
+static int step_guarded(adpsgd_t h, const void* const* batch_ptrs, float lr, const int32_t* active) {
     try {
-        return step_impl(h, batch_ptrs, lr);
+        return step_impl(h, batch_ptrs, lr, active);
     } catch (const std::bad_alloc&) {
         return fail(ADPSGD_ENOMEM, "out of host memory");
     } catch (const std::exception& ex) {
@@ -772,6 +787,19 @@ int adpsgd_losses(adpsgd_t h, float* host_out) {
     HIPCHK(hipMemcpyAsync(host_out, h->loss, (size_t)h->L * 4, hipMemcpyDeviceToHost, h->stream), "loss copy");
     HIPCHK(hipStreamSynchronize(h->stream), "stream sync");
     return status_error(h);
+}
+
+int adpsgd_step(adpsgd_t h, const void* const* batch_ptrs, float lr) { return step_guarded(h, batch_ptrs, lr, nullptr); }
+
+int adpsgd_step_masked(adpsgd_t h, const void* const* batch_ptrs, float lr, const int32_t* active) {
+    if (!active) return fail(ADPSGD_EINVAL, "active is NULL");
+    return step_guarded(h, batch_ptrs, lr, active);
+}
+
+int adpsgd_delay(uint64_t microseconds, void* hip_stream) {
+    if (microseconds > 10000000ull) return fail(ADPSGD_EINVAL, "at most 10 000 000 microseconds");
+    HIPCHK(launch_delay(microseconds * 100ull, (hipStream_t)hip_stream), "delay kernel");
+    return ADPSGD_OK;
 }
 
 int adpsgd_status(adpsgd_t h) {
@@ -920,6 +948,21 @@ int adpsgd_gemm(int precision, int a_kmajor, int b_kmajor, int c_is_elem, int M,
     hipError_t e = launch_gemm(g, (hipStream_t)hip_stream);
     if (e == hipErrorInvalidValue) return fail(ADPSGD_EINVAL, "GEMM operands violate the size/alignment rules");
     if (e != hipSuccess) return hipfail(e, "gemm launch");
+    return ADPSGD_OK;
+}
+
+int adpsgd_probe_mfma(float* dev_out, int blocks, int iters, void* hip_stream) {
+    hipError_t e = launch_mfma_peak(dev_out, blocks, iters, (hipStream_t)hip_stream);
+    if (e == hipErrorInvalidValue) return fail(ADPSGD_EINVAL, "dev_out, blocks >= 1 and iters >= 1 are needed");
+    if (e != hipSuccess) return hipfail(e, "mfma probe");
+    return ADPSGD_OK;
+}
+
+int adpsgd_probe_stream(int reads, int writes_f32, int writes_bf16, void* dev_buf, int64_t pitch_bytes, int64_t elems, void* hip_stream) {
+    hipError_t e = launch_stream_probe(reads, writes_f32, writes_bf16, dev_buf, pitch_bytes, elems, (hipStream_t)hip_stream);
+    if (e == hipErrorInvalidValue)
+        return fail(ADPSGD_EINVAL, "mix must be 1:0:0, 1:1:0, 2:1:0, 2:1:1, 4:2:0, 4:2:2, 8:4:4, 16:8:8 or 32:16:16; elems a multiple of 4; pitch >= 4 * elems, a multiple of 16");
+    if (e != hipSuccess) return hipfail(e, "stream probe");
     return ADPSGD_OK;
 }
 

@@ -122,6 +122,15 @@ struct PersistDesc {
 bool rec_persist_supported(const RecDesc& d, int cu_count);
 hipError_t launch_rec_persist(const PersistDesc& p, bool backward, int cu_count, hipStream_t s);
 
+// one wave that idles for `ticks` of the 100 MHz wall clock (the wall-clock model of the slow-learner experiment)
+hipError_t launch_delay(unsigned long long ticks, hipStream_t s);
+
+// ---- measurement probes (probe.hip) ----------------------------------------------------------------
+hipError_t launch_mfma_peak(float* out, int blocks, int iters, hipStream_t s);       // out: [blocks * 256] floats
+// reads : writes_f32 : writes_bf16 one of 1:0:0, 1:1:0, 2:1:0, 2:1:1, 4:2:0, 4:2:2, 8:4:4, 16:8:8, 32:16:16; the streams
+// are `pitch` bytes apart in buf
+hipError_t launch_stream_probe(int reads, int writes_f32, int writes_bf16, void* buf, int64_t pitch, int64_t elems, hipStream_t s);
+
 struct SoftmaxDesc {
     int precision, L;          // L: learners of this launch (entries of lmap)
     LearnerMap lmap;

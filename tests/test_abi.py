@@ -120,7 +120,10 @@ def test_create_rejects_a_missing_workspace():
 
 def test_argument_checks_that_need_no_gpu():
     # every rejection below happens before any HIP call
-    for call in (lambda: Bd.adpsgd_set_tuning(None, Bd.TUNE_GEMM_TILE, 12), lambda: Bd.adpsgd_status(None)):
+    for call in (lambda: Bd.adpsgd_set_tuning(None, Bd.TUNE_GEMM_TILE, 12), lambda: Bd.adpsgd_status(None),
+                 lambda: Bd.adpsgd_delay(10_000_001, None), lambda: Bd.adpsgd_step_masked(None, [None], 0.1, [1]),
+                 lambda: Bd.adpsgd_probe_mfma(None, 1, 1, None), lambda: Bd.adpsgd_probe_stream(3, 1, 0, 0x10000, 64, 16, None),
+                 lambda: Bd.adpsgd_probe_stream(2, 1, 0, 0x10000, 60, 16, None)):
         with pytest.raises(Bd.AdpsgdError) as ei:
             call()
         assert ei.value.code == Bd.EINVAL

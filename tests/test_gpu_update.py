@@ -136,6 +136,68 @@ def test_hybrid_mixing_alone_makes_every_super_learner_identical():
     eng.close()
 
 
+def test_given_straggler_masks_bit_exact_and_rejected_where_undefined():
+    import torch
+    from paper_2110_11199_amd import binding as Bd
+    L, P = 7, 5003
+    r = np.random.default_rng(2)
+    x0 = r.uniform(-1, 1, (L, P)).astype(np.float32)
+    g = (r.standard_normal((L, P)) * 1e-2).astype(np.float32)
+    eng = Bd.Adpsgd(Bd.make_config(L, S.RANDOM_RING, seed=9, flat_params=P))
+    for i in range(L):
+        eng.set_params(i, torch.from_numpy(x0[i]).cuda())
+    gd = [torch.from_numpy(g[i]).cuda() for i in range(L)]
+    ora = A.Oracle(L, S.RANDOM_RING, 9, flat_params=P, x0=x0)
+    for k in range(6):
+        mask = [int(v) for v in r.integers(0, 2, L)] if k != 3 else [1] * L
+        eng.step([gd[i] if mask[i] else None for i in range(L)], 0.2, active=mask)
+        ora.step(None, 0.2, grads=g, active=mask)
+        got = np.stack([eng.params(i).cpu().numpy() for i in range(L)])
+        assert (got.view(np.uint32) == ora.x.view(np.uint32)).all(), k
+    eng.close()
+    for cfg in (Bd.make_config(4, S.D1D, flat_params=8), Bd.make_config(4, S.FIXED_RING, flat_params=8, mix=Bd.MIX_TRI),
+                Bd.make_config(4, S.FIXED_RING, flat_params=8, tau=1)):
+        e = Bd.Adpsgd(cfg)
+        gz = [torch.zeros(8, device="cuda") for _ in range(4)]
+        e.step(gz, 0.1, active=[1, 1, 1, 1])          # nobody sits out: fine everywhere
+        with pytest.raises(Bd.AdpsgdError) as ei:
+            e.step(gz, 0.1, active=[1, 0, 1, 1])
+        assert ei.value.code == Bd.EINVAL
+        e.close()
+
+
+def test_slow_learner_wall_clock_model():
+    # Section IV-D: with one learner 8 times slower the ring variants go on without it, delay-by-one waits for it.
+    # The masks that were realised depend on timing; whatever they were, replaying them through the oracle must give
+    # the library's models bit for bit.
+    import torch
+    from paper_2110_11199_amd import binding as Bd, straggler_model as SM
+    L, P, iters, grad_us = 6, 20011, 12, 3000
+    base = SM.run(Bd.FIXED_RING, L, P, 1, iters, grad_us, seed=1)
+    base["engine"].close()
+    assert all(sum(m) == L for m in base["masks"])
+    per_iter = base["seconds"] / iters
+    assert per_iter > grad_us * 1e-6
+    for pattern in (Bd.FIXED_RING, Bd.RANDOM_RING):
+        r = np.random.default_rng(4)
+        x0 = r.uniform(-1, 1, (L, P)).astype(np.float32)
+        run = SM.run(pattern, L, P, 8, iters, grad_us, seed=1, x0=[torch.from_numpy(x0[i]).cuda() for i in range(L)])
+        skipped = sum(1 - m[0] for m in run["masks"])
+        assert skipped >= iters // 2                                      # the slow learner missed most iterations ...
+        assert run["seconds"] / iters < 2.0 * per_iter                    # ... and nobody waited for it
+        ora = A.Oracle(L, pattern, 1, flat_params=P, x0=x0)
+        g = np.stack([t.cpu().numpy() for t in run["grads"]])
+        for m in run["masks"]:
+            ora.step(None, 0.1, grads=g, active=m)
+        got = np.stack([run["engine"].params(i).cpu().numpy() for i in range(L)])
+        assert (got.view(np.uint32) == ora.x.view(np.uint32)).all()
+        run["engine"].close()
+    d1d = SM.run(Bd.D1D, L, P, 8, 6, grad_us, seed=1)
+    d1d["engine"].close()
+    assert all(sum(m) == L for m in d1d["masks"])
+    assert d1d["seconds"] / 6 > 6.0 * per_iter                            # every iteration took the slow learner's time
+
+
 def test_delay_by_one_with_pairwise_mixing_and_ring_with_global_mean():
     _run(6, 5001, S.D1D, 4, mix=S.MIX_PAIR)
     _run(6, 5001, S.FIXED_RING, 3, mix=S.MIX_ALL, tau=0)

@@ -176,6 +176,29 @@ def test_decay_to_consensus_at_the_learner_counts_of_the_figure(L):
     assert np.linalg.norm(S.mixing_matrix(S.MIX_ALL, order, partner, active) - U, 2) < 1e-15
 
 
+def test_given_straggler_mask_follows_the_same_unmatching_rule():
+    # a learner observed to be late (Section IV-D) instead of a drawn one: same ring order and matching, the
+    # straggler and its partner are unmatched, the matrix stays symmetric and doubly stochastic
+    L = 8
+    for pattern in (S.FIXED_RING, S.RANDOM_RING):
+        for k in range(4):
+            o0, p0, a0 = S.schedule(pattern, 7, k, L)
+            mask = [1] * L
+            mask[3] = 0
+            o1, p1, a1 = S.schedule(pattern, 7, k, L, active=mask)
+            assert o1 == o0 and a1 == mask
+            j = p0[3]
+            assert p1[3] == 3 and p1[j] == j
+            assert all(p1[i] == p0[i] for i in range(L) if i not in (3, j))
+            T = S.mixing_matrix(S.MIX_PAIR, o1, p1, a1)
+            assert np.allclose(T, T.T) and np.allclose(T.sum(axis=0), 1) and T[3, 3] == 1.0
+    # a drawn mask handed back in gives the drawn schedule
+    o, p, a = S.schedule(S.RANDOM_RING, 5, 2, L, 0.4)
+    assert S.schedule(S.RANDOM_RING, 5, 2, L, 0.0, active=a) == (o, p, a)
+    with pytest.raises(ValueError):
+        S.schedule(S.FIXED_RING, 0, 0, L, active=[1] * (L - 1))
+
+
 def test_all_matrix_is_uniform():
     order, partner, active = S.schedule(S.D1D, 0, 3, 16)
     T = S.mixing_matrix(S.MIX_ALL, order, partner, active)
