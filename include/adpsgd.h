@@ -323,6 +323,9 @@ int adpsgd_probe_stream(int reads, int writes_f32, int writes_bf16, void* dev_bu
 #define ADPSGD_TUNE_REC_FWD_GROUPS  2
 #define ADPSGD_TUNE_REC_PERSISTENT  3
 #define ADPSGD_TUNE_REC_WAIT_US     4
+#define ADPSGD_TUNE_MEAN_CHUNK      5   /* global-mean update: elements per chunk of its two-kernel form (a multiple of
+                                           1024, at most 16777216), 0 = the single-kernel form, -1 (default) = automatic
+                                           (two kernels from 4M parameters on); same results bit for bit */
 int adpsgd_set_tuning(adpsgd_t h, int key, int value);
 
 #ifdef __cplusplus

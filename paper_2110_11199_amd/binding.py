@@ -82,7 +82,7 @@ EXPORTS = ["adpsgd_workspace_bytes", "adpsgd_create", "adpsgd_step", "adpsgd_par
            "adpsgd_set_tuning", "adpsgd_consensus", "adpsgd_status", "adpsgd_consensus_static", "adpsgd_lr_at_epoch",
            "adpsgd_probe_mfma", "adpsgd_probe_stream", "adpsgd_step_masked", "adpsgd_delay"]
 STATIC_MAX_ELEMENTS = 1 << 34
-TUNE_GEMM_TILE, TUNE_REC_DIRECT, TUNE_REC_FWD_GROUPS, TUNE_REC_PERSISTENT, TUNE_REC_WAIT_US = 0, 1, 2, 3, 4
+TUNE_GEMM_TILE, TUNE_REC_DIRECT, TUNE_REC_FWD_GROUPS, TUNE_REC_PERSISTENT, TUNE_REC_WAIT_US, TUNE_MEAN_CHUNK = 0, 1, 2, 3, 4, 5
 PHASES = ["stage_cast", "batched_gemm", "recurrent_fwd", "recurrent_bwd", "softmax_ce", "bias_colsum", "mix_update"]
 
 

@@ -82,6 +82,9 @@ struct Carver {
 
 }  // namespace
 
+// Chunk of the parameter index the two-kernel global mean works on at a time (elements; the buffer holds the maximum)
+constexpr int64_t kMeanChunkMax = 16 << 20, kMeanChunkDefault = 4 << 20;   // measured best on 16 x 145M: 2M .. 6M within 3 %
+
 struct Profiler {
     bool on = false;
     std::vector<hipEvent_t> ev;        // ev[j] opens segment j; ev[j+1] closes it
@@ -104,6 +107,9 @@ struct adpsgd_handle {
     int64_t tune_wait_us = 2000000;        // bound of one wait between the workgroups of a persistent kernel
     int cu_count = 0;                      // compute units of the device (a persistent grid must not exceed it)
     uint32_t* rec_counters = nullptr;      // [layers][2 passes][L * D] frame counters of the persistent kernels
+    float* mean_buf = nullptr;             // chunk buffer of the two-kernel global mean (mix ALL)
+    int64_t mean_cap = 0;                  // its size in elements: min(kMeanChunkMax, P rounded up to 1024)
+    int64_t tune_mean_chunk = -1;          // elements per chunk; 0: the single-kernel global mean; -1: automatic
     // device status word (kStatus* bits, sticky) and its pinned host mirror, refreshed by an asynchronous
     // copy at the end of every step
     uint32_t* status = nullptr;
@@ -278,6 +284,8 @@ size_t plan(adpsgd_handle* h, void* base) {
     h->params[1] = h->tau == 1 ? (float*)w.take(L * h->Ppad * 4) : h->params[0];
     h->consensus = (double*)w.take((size_t)(kConsensusBlocks + 1) * 8);     // partial sums + the result
     h->status = (uint32_t*)w.take(256);
+    h->mean_cap = round_up(h->P, 1024) < kMeanChunkMax ? round_up(h->P, 1024) : kMeanChunkMax;
+    h->mean_buf = h->mix == ADPSGD_MIX_ALL ? (float*)w.take((size_t)h->mean_cap * 4) : nullptr;
     if (s.flat_params == 0) h->rec_counters = (uint32_t*)w.take((size_t)s.layers * 2 * c.L * 2 * 4);
     if (!h->flat) {
         const size_t M = (size_t)h->M, DH = (size_t)h->D * h->H, G4 = DH * 4, e = (size_t)h->esz;
@@ -722,6 +730,12 @@ static int step_impl(adpsgd_t h, const void* const* batch_ptrs, float lr, const 
     u.L = L; u.mix = h->mix; u.P = h->P; u.src = xk; u.dst = xnext; u.stride = h->Ppad; u.lr = lr;
     u.update_first = h->cfg.pattern == ADPSGD_SDPSGD;
     u.group_size = is_hybrid(h->mix) ? h->cfg.group_size : 1;
+    {   // two-kernel global mean: by default on models large enough for the extra launches not to matter
+        int64_t chunk = h->tune_mean_chunk >= 0 ? h->tune_mean_chunk : (h->P >= (4 << 20) ? kMeanChunkDefault : 0);
+        if (chunk > h->mean_cap) chunk = h->mean_cap;
+        u.mean_buf = chunk > 0 ? h->mean_buf : nullptr;
+        u.mean_elems = chunk;
+    }
     if (h->flat) {
         for (int i = 0; i < L; ++i) u.g[i] = (const float*)batch_ptrs[i];
     } else {
@@ -982,6 +996,10 @@ int adpsgd_set_tuning(adpsgd_t h, int key, int value) {
         case ADPSGD_TUNE_REC_PERSISTENT:
             if (value < -1 || value > 1) return fail(ADPSGD_EINVAL, "-1 (automatic), 0 or 1");
             h->tune_rec_persist = value; return ADPSGD_OK;
+        case ADPSGD_TUNE_MEAN_CHUNK:
+            if (value != 0 && value != -1 && (value < 1024 || value > kMeanChunkMax || value % 1024))
+                return fail(ADPSGD_EINVAL, "-1 (automatic), 0 (single kernel) or a multiple of 1024 elements up to 16777216");
+            h->tune_mean_chunk = value; return ADPSGD_OK;
         case ADPSGD_TUNE_REC_WAIT_US:
             if (value < 0) return fail(ADPSGD_EINVAL, "microseconds >= 0");
             h->tune_wait_us = value; return ADPSGD_OK;

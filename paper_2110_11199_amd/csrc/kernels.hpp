@@ -51,6 +51,8 @@ struct UpdateDesc {
     bf16_t* shadow;            // optional [L][stride] bf16 copy of the next gradient point, or NULL
     int emit_input;            // shadow = bf16(x^k) (tau = 1) instead of bf16(x^{k+1})
     int update_first;          // mix 2 only: average the updated models x_j - lr*g_j (synchronous baseline)
+    float* mean_buf;           // mix 2: optional buffer of mean_elems floats; when given the global mean runs chunk by
+    int64_t mean_elems;        //   chunk of that many elements in two kernels (fewer streams per thread); NULL: one kernel
 };
 hipError_t launch_update(const UpdateDesc& d, hipStream_t s);
 hipError_t launch_average(const float* x, int64_t stride, int L, int64_t P, float* out, hipStream_t s);

@@ -238,6 +238,54 @@ __global__ __launch_bounds__(256) void all_update_kernel(AllArgs p) {
     }
 }
 
+// ---- global mean in two kernels per chunk of the parameter index --------------------------------------
+// The rate of a streaming kernel on this device falls with the number of streams one thread walks at once (measured
+// with the stream probe: 6.5 TB/s with 3 streams per thread, 5.3 with 64).  The single-kernel global mean owns
+// 4 streams per learner and thread.  Split: `all_mean_kernel` reads the L models of a chunk of the index and
+// writes their mean to a small buffer (and the bf16 copies of the models read, when asked for); `all_apply_kernel`
+// then runs once per learner (grid y) with three streams per thread: the mean (from the buffer, which a chunk
+// at a time stays in the caches), the learner's gradient, the learner's new model.  Same operations in the same
+// order per element as all_update_kernel, so the results are bit-identical.
+struct AllSplitArgs {
+    AllArgs a;
+    float* mean;            // [chunk] fp32
+    int64_t e0, n4c;        // chunk start and length in float4 positions
+};
+
+__global__ __launch_bounds__(256) void all_mean_kernel(AllSplitArgs q) {
+    const AllArgs& p = q.a;
+    const int64_t c = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (c >= q.n4c) return;
+    const int64_t e = q.e0 + c;
+    float4 s = ldnt_(p.src, e);
+    const bool emit_in = p.shadow && p.emit_input;
+    if (emit_in) emit4_(p.shadow, e, s);
+#pragma unroll 8
+    for (int j = 1; j < p.L; ++j) {
+        const float4 v = ldnt_(p.src + j * p.stride, e);
+        if (emit_in) emit4_(p.shadow + j * p.stride, e, v);
+        s.x = __fadd_rn(s.x, v.x); s.y = __fadd_rn(s.y, v.y); s.z = __fadd_rn(s.z, v.z); s.w = __fadd_rn(s.w, v.w);
+    }
+    ((float4*)q.mean)[c] = make_float4(__fmul_rn(s.x, p.inv_L), __fmul_rn(s.y, p.inv_L), __fmul_rn(s.z, p.inv_L), __fmul_rn(s.w, p.inv_L));
+}
+
+__global__ __launch_bounds__(256) void all_apply_kernel(AllSplitArgs q) {
+    const AllArgs& p = q.a;
+    const int64_t c = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (c >= q.n4c) return;
+    const int64_t e = q.e0 + c;
+    const int i = blockIdx.y;
+    const float4 m = ((const float4*)q.mean)[c];
+    const float4 r = pair_new_(m, p.lr, ldnt_(p.g[i], e));
+    stnt_(p.dst + i * p.stride, e, r);
+    if (p.shadow && !p.emit_input) emit4_(p.shadow + i * p.stride, e, r);
+}
+
+// the P % 4 last elements of every learner (one thread each)
+__global__ void all_tail_kernel(AllArgs p) {
+    if (threadIdx.x < (p.P & 3)) all_scalar_(p, ((p.P >> 2) << 2) + threadIdx.x);
+}
+
 // ---- ring-neighbour mixing with weights 1/3 (the circulant operator T^f of Eq. 9, and T^r = P' T^f P) -------
 // One thread owns an element index of all learners and walks the ring order with the previous, current and
 // next model value in registers: every model is read once (the last one of the order twice), so the update
@@ -457,7 +505,19 @@ hipError_t launch_update(const UpdateDesc& d, hipStream_t s) {
                 if (!d.active[i]) return hipErrorInvalidValue;     // the baseline waits for every learner
             if (d.emit_input) return hipErrorInvalidValue;         // and has no staleness
         }
-        if (vec) {
+        if (vec && !d.update_first && d.mean_buf && d.mean_elems >= 1024 && d.L >= 4 && (d.P >> 2) > 0 &&
+            (uintptr_t)d.mean_buf % 16 == 0) {
+            const int64_t n4 = d.P >> 2, chunk4 = d.mean_elems >> 2;
+            AllSplitArgs q;
+            q.a = a; q.mean = d.mean_buf;
+            for (int64_t e0 = 0; e0 < n4; e0 += chunk4) {
+                q.e0 = e0; q.n4c = n4 - e0 < chunk4 ? n4 - e0 : chunk4;
+                const unsigned blocks = (unsigned)((q.n4c + 255) / 256);
+                hipLaunchKernelGGL(all_mean_kernel, dim3(blocks), dim3(256), 0, s, q);
+                hipLaunchKernelGGL(all_apply_kernel, dim3(blocks, (unsigned)d.L), dim3(256), 0, s, q);
+            }
+            if (d.P & 3) hipLaunchKernelGGL(all_tail_kernel, dim3(1), dim3(64), 0, s, a);
+        } else if (vec) {
             const int64_t n4 = d.P >> 2;
             const unsigned blocks = (unsigned)((n4 > 0 ? n4 : 1) + 255) / 256;
             if (d.update_first) hipLaunchKernelGGL(sync_update_kernel<true>, dim3(blocks), dim3(256), 0, s, a);

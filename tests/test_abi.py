@@ -49,7 +49,8 @@ def test_config_validation_and_workspace_size():
     scratch = 16640 + 256               # 2049 doubles of the consensus-distance reduction, rounded to 256 bytes; the status word
     assert Bd.adpsgd_workspace_bytes(flat) == 64 * 135_000_000 * 4 + scratch
     d1d = Bd.make_config(64, Bd.D1D, flat_params=1000)
-    assert Bd.adpsgd_workspace_bytes(d1d) == 2 * 64 * 1024 * 4 + scratch     # two model buffers, padded stride
+    mean = 1024 * 4                     # chunk buffer of the global-mean update: min(16M, P rounded up to 1024) floats
+    assert Bd.adpsgd_workspace_bytes(d1d) == 2 * 64 * 1024 * 4 + scratch + mean     # two model buffers, padded stride
     bad = [Bd.make_config(0, 0, flat_params=8), Bd.make_config(129, 0, flat_params=8),
            Bd.make_config(4, 4, flat_params=8), Bd.make_config(4, Bd.D1D, flat_params=8, straggler_p=0.1),
            Bd.make_config(4, Bd.SDPSGD, flat_params=8, straggler_p=0.1), Bd.make_config(4, Bd.SDPSGD, flat_params=8, tau=1),
@@ -62,7 +63,7 @@ def test_config_validation_and_workspace_size():
            Bd.make_config(1, 0, flat_params=8, mix=Bd.MIX_TRI), Bd.make_config(2, 1, flat_params=8, mix=Bd.MIX_TRI)]
     assert Bd.adpsgd_workspace_bytes(Bd.make_config(4, 0, flat_params=8, mix=Bd.MIX_TRI)) > 0     # ring neighbours, weights 1/3
     # the synchronous baseline: one model buffer, the all-learner mean by default
-    assert Bd.adpsgd_workspace_bytes(Bd.make_config(64, Bd.SDPSGD, flat_params=1000)) == 64 * 1024 * 4 + scratch
+    assert Bd.adpsgd_workspace_bytes(Bd.make_config(64, Bd.SDPSGD, flat_params=1000)) == 64 * 1024 * 4 + scratch + mean
     assert Bd.adpsgd_workspace_bytes(Bd.make_config(4, Bd.SDPSGD, flat_params=8, mix=Bd.MIX_ALL, tau=0)) > 0
     for cfg in bad:
         with pytest.raises(Bd.AdpsgdError) as ei:

@@ -8,7 +8,7 @@ from oracle import adpsgd as A
 pytestmark = pytest.mark.gpu
 
 
-def _run(L, P, pattern, steps, p=0.0, mix=None, tau=None, seed=3, lr=0.1, group_size=0):
+def _run(L, P, pattern, steps, p=0.0, mix=None, tau=None, seed=3, lr=0.1, group_size=0, tune=()):
     import torch
     from paper_2110_11199_amd import binding as Bd
     r = np.random.default_rng(seed)
@@ -19,6 +19,8 @@ def _run(L, P, pattern, steps, p=0.0, mix=None, tau=None, seed=3, lr=0.1, group_
     cfg = Bd.make_config(L, pattern, seed=seed, flat_params=P, straggler_p=p,
                          mix=Bd.MIX_DEFAULT if mix is None else mix, tau=-1 if tau is None else tau, group_size=group_size)
     eng = Bd.Adpsgd(cfg)
+    for key, value in tune:
+        eng.tune(key, value)
     for i in range(L):
         eng.set_params(i, torch.from_numpy(x0[i]).cuda())
     gd = [torch.from_numpy(g[i]).cuda() for i in range(L)]
@@ -51,6 +53,16 @@ def test_pairwise_fixed_ring(L):
 def test_delay_by_one_global_mean(L, P):
     print("update d1d", L, P, flush=True)
     _run(L, P, S.D1D, 4)
+
+
+@pytest.mark.parametrize("L,P,chunk", [(4, 70001, 1024), (16, 70003, 4096), (5, 1 << 20, 65536), (16, 4099, 16 << 20), (128, 3000, 1024)])
+def test_global_mean_in_two_kernels_per_chunk(L, P, chunk):
+    # the mean of a chunk of the index first, then one pass per learner: bit-identical to the single kernel and the oracle;
+    # ragged last chunks, P % 4 tails, chunks larger than the model, in place (tau = 0) and ping-pong (tau = 1)
+    from paper_2110_11199_amd import binding as Bd
+    print("update d1d two kernels", L, P, chunk, flush=True)
+    _run(L, P, S.D1D, 3, tune=[(Bd.TUNE_MEAN_CHUNK, chunk)])
+    _run(L, P, S.FIXED_RING, 3, mix=S.MIX_ALL, tau=0, tune=[(Bd.TUNE_MEAN_CHUNK, chunk)])
 
 
 @pytest.mark.parametrize("L", [3, 4, 5, 16, 128])
