@@ -232,6 +232,7 @@ def main():
     ap.add_argument("--tri", action="store_true", help="also time the ring-neighbour (weights 1/3) mixing kernel on the cfg5 shape")
     ap.add_argument("--sync", action="store_true", help="also time the synchronous baseline's update-then-mean kernel on the cfg5 shape")
     ap.add_argument("--cfg3-steps", type=int, default=5, help="timed steps of the cfg3 leg (0 = skip)")
+    ap.add_argument("--small-steps", type=int, default=10, help="timed steps of the cfg1 and cfg2 legs (0 = skip)")
     ap.add_argument("--tune", action="append", default=[], metavar="KEY:VALUE",
                     help="forwarded to adpsgd_set_tuning of the model handles (tuning only), e.g. 0:12")
     args = ap.parse_args()
@@ -344,6 +345,23 @@ def main():
                 "update": hbm_roofline(prof3, ["mix_update"], "all_update_kernel", "cfg3", None, "hbm_2read_1write_1bf16_GBps")}
             if peaks:
                 out["roofline_cfg3"]["frac_of_attained"] = tf3 / peaks["mfma_bf16_TFLOPs"]
+        if args.small_steps > 0:
+            # the two small fp32 configurations: a few hundred launches of microseconds each per step (launch-latency bound)
+            small = {}
+            for name in ("cfg1", "cfg2"):
+                if name == wl.name:
+                    continue
+                ws = synth.WORKLOADS[name]
+                dts, profs, _ = run_model(ws, args.small_steps, 2, tune=tune)
+                mss = dts / args.small_steps * 1e3
+                gs = profs["batched_gemm"]
+                small[name] = {"ms_per_step": mss, "frames_per_s": ws.L * ws.batch * ws.frames / (mss * 1e-3),
+                               "learner_steps_per_s": ws.L / (mss * 1e-3), "dtype": "f32", "steps": args.small_steps,
+                               "launches_per_step": sum(v["launches"] for v in profs.values()) / args.small_steps,
+                               "gemm_TFLOPs": gs["work"] / (gs["ms"] * 1e-3) / 1e12 if gs["ms"] > 0 else 0.0,
+                               "gemm_frac_of_f32_peak": (gs["work"] / (gs["ms"] * 1e-3) / 1e12 / PEAK_TFLOPS["f32"]) if gs["ms"] > 0 else 0.0,
+                               "phases_ms_per_step": {k: v["ms"] / args.small_steps for k, v in profs.items()}}
+            out["small_configs"] = small
         if peaks:
             out["measured_peaks"] = peaks
             if wl.precision:
