@@ -42,7 +42,14 @@ def _oracle_threads():
     return 4, threadpool_limits
 
 
-def _run_model_config(name, steps, seed=0):
+def _say(capsys, msg):
+    """A progress line that reaches the terminal also when pytest captures output: the long tests here would
+    otherwise be silent for minutes."""
+    with capsys.disabled():
+        print(msg, flush=True)
+
+
+def _run_model_config(name, steps, capsys, seed=0):
     import torch
     from paper_2110_11199_amd import binding as Bd
     wl = synth.WORKLOADS[name]
@@ -80,27 +87,27 @@ def _run_model_config(name, steps, seed=0):
             worst_g, worst_x = max(worst_g, eg), max(worst_x, ex)
             assert eg < tol and ex < tol, (name, k, i, eg, ex)
             assert abs(losses[i] - ora.last_losses[i]) < tol * abs(ora.last_losses[i])
-        print("%s iteration %d ok (worst so far: grad %.2e, model %.2e)" % (name, k, worst_g, worst_x), flush=True)
+        _say(capsys, "%s iteration %d ok (worst so far: grad %.2e, model %.2e)" % (name, k, worst_g, worst_x))
     eng.close()
 
 
 @pytest.mark.timeout(600)
-def test_cfg2_random_ring_fp32_all_twenty_iterations():
-    _run_model_config("cfg2", synth.WORKLOADS["cfg2"].steps)
+def test_cfg2_random_ring_fp32_all_twenty_iterations(capsys):
+    _run_model_config("cfg2", synth.WORKLOADS["cfg2"].steps, capsys)
 
 
 @pytest.mark.timeout(900)
-def test_cfg3_delay_by_one_bf16_all_twenty_iterations():
-    _run_model_config("cfg3", synth.WORKLOADS["cfg3"].steps)
+def test_cfg3_delay_by_one_bf16_all_twenty_iterations(capsys):
+    _run_model_config("cfg3", synth.WORKLOADS["cfg3"].steps, capsys)
 
 
 @pytest.mark.timeout(1500)
-def test_cfg4_delay_by_one_bf16_all_ten_iterations():
-    _run_model_config("cfg4", synth.WORKLOADS["cfg4"].steps)
+def test_cfg4_delay_by_one_bf16_all_ten_iterations(capsys):
+    _run_model_config("cfg4", synth.WORKLOADS["cfg4"].steps, capsys)
 
 
 @pytest.mark.timeout(900)
-def test_cfg5_mixing_update_stress_bit_exact():
+def test_cfg5_mixing_update_stress_bit_exact(capsys):
     import torch
     from paper_2110_11199_amd import binding as Bd
     wl = synth.WORKLOADS["cfg5"]
@@ -141,7 +148,7 @@ def test_cfg5_mixing_update_stress_bit_exact():
         if k < full_steps:
             snaps.append(models())
         if k % 10 == 9 or k < full_steps:
-            print("cfg5 iteration %d bit-exact on %d ranges" % (k, len(starts)), flush=True)
+            _say(capsys, "cfg5 iteration %d bit-exact on %d ranges" % (k, len(starts)))
     assert n_skipped > 0      # the straggler mask was exercised
     # mixing preserves the learner average; the update moves it by -lr * mean of the active gradients:
     # checked at full size through the library's own average of the final models on one range
@@ -174,8 +181,8 @@ def test_cfg5_mixing_update_stress_bit_exact():
             while len(pending) > 16:
                 bad.append(pending.pop(0).result())
             if c % 32 == 31:
-                print("cfg5 full-index check: %d of %d chunks fetched" % (c + 1, len(bounds)), flush=True)
+                _say(capsys, "cfg5 full-index check: %d of %d chunks fetched" % (c + 1, len(bounds)))
         bad += [f.result() for f in pending]
     assert not [b for b in bad if b is not None], [b for b in bad if b is not None][:5]
-    print("cfg5: all %d indices of %d learners bit-exact after iterations 0..%d" % (P, L, full_steps - 1), flush=True)
+    _say(capsys, "cfg5: all %d indices of %d learners bit-exact after iterations 0..%d" % (P, L, full_steps - 1))
     eng.close()
