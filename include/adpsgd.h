@@ -309,7 +309,9 @@ int adpsgd_probe_stream(int reads, int writes_f32, int writes_bf16, void* dev_bu
 
 /* Tuning of ONE handle (benchmarks and tests; the defaults are the measured best):
  *   ADPSGD_TUNE_GEMM_TILE        tile configuration of the time-batched GEMMs, as tile_config above
- *   ADPSGD_TUNE_REC_DIRECT       1 (default) / 0: direct-to-LDS recurrent step kernels allowed or not
+ *   ADPSGD_TUNE_REC_DIRECT       1 (default) / 0: specialised recurrent step kernels (direct-to-LDS loads for bf16 and
+ *                                batches over 32; contraction split over the waves for batches up to 32) allowed, or
+ *                                the general register-staged kernels everywhere
  *   ADPSGD_TUNE_REC_FWD_GROUPS   learner groups the forward recurrence is run in, 0 = automatic
  *   ADPSGD_TUNE_REC_PERSISTENT   persistent recurrent kernels (all frames of a layer in one launch, W_h held in
  *                                registers; bf16 operands, hidden 128/256/512/1024, batch <= 128): 1 on where the

@@ -8,7 +8,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libadpsgd.so")
-SOURCES = ["api.hip", "gemm.hip", "lstm.hip", "lstm_persist.hip", "elementwise.hip", "update.hip", "probe.hip"]
+SOURCES = ["api.hip", "gemm.hip", "lstm.hip", "lstm_persist.hip", "lstm_small.hip", "elementwise.hip", "update.hip", "probe.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=on",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

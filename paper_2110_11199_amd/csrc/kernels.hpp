@@ -84,7 +84,7 @@ struct RecDesc {               // one time step of one layer, all learners and d
     int precision;
     int L, D, B, H, T;         // L: learners of this launch (entries of lmap)
     LearnerMap lmap;
-    int direct;                // 0: never use the direct-to-LDS kernels (tuning)
+    int direct;                // 0: never use the direct-to-LDS or the small-batch kernels (tuning)
     int step;                  // processing step 0..T-1 (frame = step, or T-1-step for d = 1)
     // forward: gates buffer holds W_x x + b on entry, the activated gates on exit
     float* gates; int64_t sGi;           // [L][T*B][D*4H] fp32
@@ -103,6 +103,10 @@ struct RecDesc {               // one time step of one layer, all learners and d
 int rec_backward_batch_tiles(int B);
 hipError_t launch_rec_forward(const RecDesc& d, hipStream_t s);
 hipError_t launch_rec_backward(const RecDesc& d, hipStream_t s);
+// The same step for batches of at most 32 rows (lstm_small.hip): contraction split over the waves of a workgroup,
+// operands read straight into registers.  launch_rec_forward / launch_rec_backward use it when it applies.
+bool rec_small_supported(const RecDesc& d);
+hipError_t launch_rec_small(const RecDesc& d, bool backward, hipStream_t s);
 
 // Bits of the device-side status word of a handle (0 = fine).
 constexpr uint32_t kStatusBadLabel = 1u;       // a label outside [0, classes) was met (and clamped)

@@ -364,6 +364,7 @@ static bool dma_ok(const RecDesc& d) {
 
 hipError_t launch_rec_forward(const RecDesc& d, hipStream_t s) {
     if (!rec_ok(d)) return hipErrorInvalidValue;
+    if (rec_small_supported(d)) return launch_rec_small(d, false, s);
     if (d.precision == 0) return fwd_t<float, 16>(d, s);
     if (dma_ok(d)) {
         const unsigned groups = (unsigned)(d.L * d.D);
@@ -382,6 +383,7 @@ hipError_t launch_rec_forward(const RecDesc& d, hipStream_t s) {
 
 hipError_t launch_rec_backward(const RecDesc& d, hipStream_t s) {
     if (!rec_ok(d)) return hipErrorInvalidValue;
+    if (rec_small_supported(d)) return launch_rec_small(d, true, s);
     if (d.precision == 0) return bwd_t<float, 16>(d, s);
     if (dma_ok(d)) {
         const unsigned groups = (unsigned)(d.L * d.D);

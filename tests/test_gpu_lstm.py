@@ -56,6 +56,9 @@ SHAPES = [
     Shape(16, 128, 1, 1, 0, 40, 48, 4),       # batch 48: the 64-row recurrent tile configuration
     Shape(8, 32, 1, 0, 0, 1500, 3, 2),        # 1500 classes: softmax rows of 4 float4 per thread
     Shape(8, 32, 1, 0, 0, 5000, 3, 2),        # 5000 classes: softmax rows on 512 threads
+    Shape(16, 72, 2, 1, 0, 32, 20, 5),        # small-batch recurrent kernels: three unit tiles, the last one ragged
+    Shape(12, 20, 1, 1, 0, 24, 32, 3),        # batch 32, hidden 20: half-empty last k-chunk (fp32); staged kernels (bf16)
+    Shape(12, 264, 1, 1, 0, 20, 7, 4),        # hidden 264: more k-chunks than one pass of a workgroup's waves takes
 ]
 
 
@@ -230,6 +233,16 @@ def test_forward_recurrence_in_learner_groups(groups):
     for prec in (0, 1):
         _run_recurrence(Shape(12, 64, 2, 1, 0, 20, 40, 3), 5, S.RANDOM_RING, prec, 2, 0.2, seed=7, scale=0.1,
                         tune=[(Bd.TUNE_REC_FWD_GROUPS, groups)])
+
+
+@pytest.mark.parametrize("prec", [0, 1])
+@pytest.mark.parametrize("shape", [SHAPES[0], SHAPES[1], SHAPES[10]])
+def test_small_batches_on_the_staged_kernels_too(shape, prec):
+    # batches of at most 32 rows normally take the small-batch kernels; switched off, the register-staged
+    # kernels with their 32-row tiles run the same recurrence
+    from paper_2110_11199_amd import binding as Bd
+    print("staged kernels, small batch", shape, prec, flush=True)
+    _run_recurrence(shape, 2, S.FIXED_RING, prec, 2, 0.1, tune=((Bd.TUNE_REC_DIRECT, 0),))
 
 
 def test_tuning_is_per_handle():
