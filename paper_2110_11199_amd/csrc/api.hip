@@ -393,8 +393,6 @@ int compute_gradients(adpsgd_handle* h, const float* at, const void* const* batc
             pd.counters = h->rec_counters + ((size_t)(l * 2 + (backward ? 1 : 0)) * L * 2 + p0);
             pd.status = h->status;
             pd.wait_ticks = (unsigned long long)h->tune_wait_us * 100ull;
-            pd.trace = nullptr;
-            pd.same_xcd_release = 0;
             HIPCHK(launch_rec_persist(pd, backward, h->cu_count, s), backward ? "persistent recurrent backward" : "persistent recurrent forward");
         }
         return ADPSGD_OK;

@@ -122,8 +122,6 @@ struct PersistDesc {
     uint32_t* counters;                  // [ngl] device words, zero before the launch: workgroups that have finished a frame
     uint32_t* status;                    // the handle's status word (kStatusWaitExpired is or-ed in)
     unsigned long long wait_ticks;       // bound of one wait between workgroups, in ticks of the 100 MHz wall clock
-    unsigned long long* trace;           // tuning aid, normally NULL: [T][8] wall-clock stamps of workgroup 0's phases
-    int same_xcd_release;                // 1: skip the L2 write-back of the release when a pair's workgroups share an XCD
 };
 bool rec_persist_supported(const RecDesc& d, int cu_count);
 hipError_t launch_rec_persist(const PersistDesc& p, bool backward, int cu_count, hipStream_t s);

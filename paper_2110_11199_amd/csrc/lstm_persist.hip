@@ -61,25 +61,15 @@ __device__ inline bool wait_for_(const PersistDesc& p, uint32_t* cnt, uint32_t t
     return ok;
 }
 
-// Tuning aid: wall-clock stamp number k of frame s, taken by thread 0 of workgroup 0 when a trace buffer is given.
-__device__ inline void stamp_(const PersistDesc& p, int s, int k) {
-    if (p.trace && blockIdx.x == 0 && threadIdx.x == 0) p.trace[s * 8 + k] = wall_clock64();
-}
-// Index of the XCD (accelerator die, each with its own L2) this wave runs on: the XCC_ID hardware register.
-__device__ inline uint32_t xcd_id_() { return __builtin_amdgcn_s_getreg(20 | (0 << 6) | ((4 - 1) << 11)) & 15u; }
-__device__ inline void stamp_place_(const PersistDesc& p, int T) {
-    if (p.trace && threadIdx.x == 0) p.trace[T * 8 + blockIdx.x] = xcd_id_();
-}
-
 // All threads have stored their part of the frame's operand: make it visible, then count this workgroup in.
 // Every thread first waits until its own stores have been accepted by L2 (the vector L1 writes through), the
 // workgroup meets, and ONE thread then releases at device scope (one L2 write-back per workgroup instead of one per
 // wave: that write-back is what a release costs) and counts the workgroup in.
-__device__ inline void arrive_(uint32_t* cnt, bool write_back) {
+__device__ inline void arrive_(uint32_t* cnt) {
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
     if (threadIdx.x == 0) {
-        if (write_back) __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
         __hip_atomic_fetch_add(cnt, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
 }
@@ -180,15 +170,12 @@ __global__ __launch_bounds__(256, 1) void rec_forward_persist_kernel(PersistDesc
         else stg_(q == 0 ? gi[i] : q == 1 ? gf[i] : q == 2 ? gg[i] : go[i], pend_g + (int64_t)ur * G4 + q * H, voff_g);
     };
 
-    stamp_place_(p, T);
     load_preact(d == 0 ? 0 : T - 1);
     for (int s = 0; s < T; ++s) {
         const int t = d == 0 ? s : T - 1 - s;
         const int tp = d == 0 ? t - 1 : t + 1;
-        stamp_(p, s, 0);
         if (s > 0) {
             if (!wait_for_(p, cnt, W * (uint32_t)s, &wait_flag)) return;
-            stamp_(p, s, 1);
             a.base = per_frame_((const bf16_t*)r.y + li * r.sYi + (int64_t)tp * B * DH + (int64_t)d * H);
             unroll_<0, NS>([&](auto st) {
                 constexpr int S0 = decltype(st)::value;
@@ -225,7 +212,6 @@ __global__ __launch_bounds__(256, 1) void rec_forward_persist_kernel(PersistDesc
                 });
             });
         }
-        stamp_(p, s, 2);
         // swap gates between the waves: ex[gate][row][unit]
         float* ex = (float*)lds;
         __syncthreads();                 // the stage buffers are no longer read
@@ -252,17 +238,13 @@ __global__ __launch_bounds__(256, 1) void rec_forward_persist_kernel(PersistDesc
             for (int i = 0; i < PP; ++i)
                 if (ucell_<MT>(wave, i) + 4 * g < B) *(bf16_t*)((char*)(yp + (int64_t)ucell_<MT>(wave, i) * DH) + voff_y) = (bf16_t)hb[i];
         }
-        stamp_(p, s, 3);
-        if (s + 1 < T) arrive_(cnt, !p.same_xcd_release);
-        stamp_(p, s, 4);
+        if (s + 1 < T) arrive_(cnt);
         // activated gates and the cell state, for the backward pass: pending until the next frame's K loop; the
         // first frame is followed by no K loop of its own results' age (frame 0 runs none), the last by none at all
         pend_g = per_frame_(gates_u + (int64_t)t * B * G4);
         pend_c = per_frame_(cbuf_u + (int64_t)t * B * H);
         if (s + 1 == T) unroll_<0, 5 * PP>(store_pending);
-        stamp_(p, s, 5);
         if (s + 1 < T) load_preact(d == 0 ? s + 1 : T - 2 - s);
-        stamp_(p, s, 6);
     }
 }
 
@@ -336,10 +318,8 @@ __global__ __launch_bounds__(256, 1) void rec_backward_persist_kernel(PersistDes
         float dh[PP];
 #pragma unroll
         for (int i = 0; i < PP; ++i) dh[i] = 0.f;
-        stamp_(p, s, 0);
         if (s > 0) {
             if (!wait_for_(p, cnt, W * (uint32_t)s, &wait_flag)) return;
-            stamp_(p, s, 1);
             f32x16_t acc[MT];
 #pragma unroll
             for (int mt = 0; mt < MT; ++mt)
@@ -375,7 +355,6 @@ __global__ __launch_bounds__(256, 1) void rec_backward_persist_kernel(PersistDes
                     __builtin_amdgcn_sched_barrier(0);
                 });
             });
-            stamp_(p, s, 2);
             // add the four waves' partial products in a fixed order
             float* red = (float*)lds;
             __syncthreads();             // every wave is done with its stage buffers
@@ -392,7 +371,6 @@ __global__ __launch_bounds__(256, 1) void rec_backward_persist_kernel(PersistDes
             }
             __syncthreads();             // red overlaps the stage buffers of the next frame
         }
-        stamp_(p, s, 3);
         // cell backward for this lane's positions
         float cs[4] = {0.f, 0.f, 0.f, 0.f};
         uint32_t pk0[PP], pk1[PP];
@@ -441,9 +419,7 @@ __global__ __launch_bounds__(256, 1) void rec_backward_persist_kernel(PersistDes
                 *(bf16_t*)(rp + 4 * H) = (bf16_t)(pk1[i] & 0xffffu); *(bf16_t*)(rp + 6 * H) = (bf16_t)(pk1[i] >> 16);
             }
         }
-        stamp_(p, s, 4);
-        if (s + 1 < T) arrive_(cnt, !p.same_xcd_release);
-        stamp_(p, s, 5);
+        if (s + 1 < T) arrive_(cnt);
         // bias gradient: column sums of da over the rows of the tile, in a fixed order (lane pair, then the waves)
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
@@ -457,7 +433,6 @@ __global__ __launch_bounds__(256, 1) void rec_backward_persist_kernel(PersistDes
             r.dbp[li * r.sDBi + (int64_t)t * G4 + (int64_t)d * 4 * H + (int64_t)q * H + u0 + col] = sum;
         }
         __syncthreads();                 // csum is rewritten in the next frame
-        stamp_(p, s, 6);
     }
 }
 
