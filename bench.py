@@ -73,6 +73,41 @@ def run_model(wl, steps, warmup, seed=0, tune=()):
     return dt, prof, float(losses.mean())
 
 
+def run_model_replayed(wl, steps, seed=0, tune=()):
+    """The same iterations as run_model, two of them recorded into a HIP graph once and replayed steps / 2 times
+    (patterns whose schedule does not change with the iteration only).  Returns seconds for `steps` iterations."""
+    import torch
+    from paper_2110_11199_amd import binding as Bd, synth
+    stream = torch.cuda.Stream()
+    with torch.cuda.stream(stream):
+        eng = Bd.Adpsgd(_config(Bd, wl, seed))
+        for key, value in tune:
+            eng.tune(key, value)
+        eng.set_params(-1, torch.from_numpy(synth.initial_model(seed, eng.P, wl.init_scale)).cuda())
+        cdf = synth.zipf_cdf(wl.classes) if wl.label_dist == "zipf" else None
+        bufs = [[tuple(torch.from_numpy(a).cuda() for a in synth.batch(wl, seed, k, i, cdf)) for i in range(wl.L)]
+                for k in range(2)]
+        for k in range(2):
+            eng.step(bufs[k], wl.lr)
+        stream.synchronize()
+        eng.capture_begin()
+        for k in range(2):
+            eng.step(bufs[k], wl.lr)
+        g = eng.capture_end()
+        Bd.adpsgd_graph_replay(g)
+        stream.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps // 2):
+            Bd.adpsgd_graph_replay(g)
+        stream.synchronize()
+        dt = time.perf_counter() - t0
+        Bd.adpsgd_graph_destroy(g)
+        eng.close()
+    del eng, bufs
+    torch.cuda.empty_cache()
+    return dt * steps / (2 * (steps // 2))
+
+
 def run_flat(wl, steps, warmup, seed=0, variant=None):
     import torch
     from paper_2110_11199_amd import binding as Bd
@@ -361,6 +396,12 @@ def main():
                                "gemm_TFLOPs": gs["work"] / (gs["ms"] * 1e-3) / 1e12 if gs["ms"] > 0 else 0.0,
                                "gemm_frac_of_f32_peak": (gs["work"] / (gs["ms"] * 1e-3) / 1e12 / PEAK_TFLOPS["f32"]) if gs["ms"] > 0 else 0.0,
                                "phases_ms_per_step": {k: v["ms"] / args.small_steps for k, v in profs.items()}}
+                # the same iterations replayed from a HIP graph (two recorded once); the random ring's schedule changes
+                # every iteration, so it cannot be recorded
+                if ws.pattern != 1 and ws.straggler_p == 0.0 and args.small_steps >= 2:
+                    small[name]["graph_replay_ms_per_step"] = run_model_replayed(ws, args.small_steps, tune=tune) / args.small_steps * 1e3
+                else:
+                    small[name]["graph_replay_ms_per_step"] = None
             out["small_configs"] = small
         if peaks:
             out["measured_peaks"] = peaks

@@ -62,6 +62,7 @@ extern "C" {
 #define ADPSGD_MAX_LEARNERS 128
 
 typedef struct adpsgd_handle* adpsgd_t;   /* opaque; owned by the library (host memory) */
+typedef struct adpsgd_graph* adpsgd_graph_t;   /* opaque: a recorded sequence of iterations (host memory) */
 
 /* Communication pattern (Section III-B / III-C / III-D), or the synchronous baseline
  * SDPSGD of Section III-A (Algorithm 2): every learner updates its own model,
@@ -160,6 +161,36 @@ int adpsgd_step(adpsgd_t h, const void* const* batch_ptrs, float lr);
  * and tau = 0 (what straggler_p needs), otherwise ADPSGD_EINVAL.  Used by the wall-clock model of the
  * paper's slow-learner experiment (paper_2110_11199_amd/straggler_model.py).                             */
 int adpsgd_step_masked(adpsgd_t h, const void* const* batch_ptrs, float lr, const int32_t* active);
+
+/* HIP-graph replay of iterations, for models small enough that an iteration is a few hundred launches of
+ * microseconds each (HIP streams and graphs take the place a tracing compiler has elsewhere).
+ * adpsgd_step enqueues kernels and one 4-byte copy to pinned host memory and nothing else, so its stream work can
+ * be recorded once and replayed.
+ *   adpsgd_capture_begin(h)      puts the handle's stream into capture mode.  Until adpsgd_capture_end, calls of
+ *                                adpsgd_step / adpsgd_step_masked on h are RECORDED, not run; every other entry
+ *                                point that takes h returns ADPSGD_EINVAL.  Needs: a stream of the handle's own (not
+ *                                the null stream), a schedule that does not change with the iteration (not
+ *                                ADPSGD_RANDOM_RING, straggler_p = 0), phase profiling off, and in bf16 mode one
+ *                                iteration run before; else ADPSGD_EINVAL.
+ *   adpsgd_capture_end(h, &g)    ends the recording and puts the handle back to the iteration it stood at (nothing
+ *                                has run).  At least one iteration must have been recorded, an even number on
+ *                                ADPSGD_FIXED_RING and with tau = 1 (the matching phase and the two model buffers
+ *                                alternate): else ADPSGD_EINVAL and *g = NULL.
+ *   adpsgd_graph_replay(g)       runs the recorded iterations on the handle's stream, asynchronously, and advances
+ *                                adpsgd_iteration by their number.  A replay repeats what was recorded: the SAME
+ *                                batch pointers (refill those buffers, in stream order, before the call), the same
+ *                                learning rate, the same masks.  On the alternating patterns the handle must stand
+ *                                at an iteration of the same parity as the recording's first one (ADPSGD_EINVAL).
+ *                                Sticky errors of the handle are reported as by adpsgd_step.
+ *   adpsgd_graph_steps(g)        iterations recorded (-1 for NULL).
+ *   adpsgd_graph_destroy(g)      waits for the stream, frees the recording (host memory owned by the library).
+ * Results are those of the same adpsgd_step calls made directly, bit for bit (the same kernels in the same order).
+ * A recording belongs to its handle; after adpsgd_destroy(h) it can only be destroyed.                             */
+int adpsgd_capture_begin(adpsgd_t h);
+int adpsgd_capture_end(adpsgd_t h, adpsgd_graph_t* out);
+int adpsgd_graph_replay(adpsgd_graph_t g);
+int64_t adpsgd_graph_steps(adpsgd_graph_t g);
+void adpsgd_graph_destroy(adpsgd_graph_t g);
 
 /* A kernel of one wave that does nothing for `microseconds` of wall-clock time (at most 10 000 000) and
  * returns: stands for a learner's gradient computation on its own device in the wall-clock model of the

@@ -45,6 +45,13 @@ _lib.adpsgd_create.argtypes = [C.POINTER(Config), _vp, C.c_size_t, _vp, C.POINTE
 _lib.adpsgd_step.argtypes = [_vp, C.POINTER(_vp), C.c_float]
 _lib.adpsgd_step_masked.argtypes = [_vp, C.POINTER(_vp), C.c_float, _i32p]
 _lib.adpsgd_delay.argtypes = [C.c_uint64, _vp]
+_lib.adpsgd_capture_begin.argtypes = [_vp]
+_lib.adpsgd_capture_end.argtypes = [_vp, C.POINTER(_vp)]
+_lib.adpsgd_graph_replay.argtypes = [_vp]
+_lib.adpsgd_graph_steps.argtypes = [_vp]
+_lib.adpsgd_graph_steps.restype = _i64
+_lib.adpsgd_graph_destroy.argtypes = [_vp]
+_lib.adpsgd_graph_destroy.restype = None
 _lib.adpsgd_params.argtypes = [_vp, C.c_int]
 _lib.adpsgd_params.restype = _vp
 _lib.adpsgd_set_params.argtypes = [_vp, C.c_int, _vp]
@@ -80,7 +87,8 @@ EXPORTS = ["adpsgd_workspace_bytes", "adpsgd_create", "adpsgd_step", "adpsgd_par
            "adpsgd_schedule", "adpsgd_schedule_of", "adpsgd_iteration", "adpsgd_average", "adpsgd_destroy",
            "adpsgd_last_error", "adpsgd_gemm", "adpsgd_set_profiling", "adpsgd_profile",
            "adpsgd_set_tuning", "adpsgd_consensus", "adpsgd_status", "adpsgd_consensus_static", "adpsgd_lr_at_epoch",
-           "adpsgd_probe_mfma", "adpsgd_probe_stream", "adpsgd_step_masked", "adpsgd_delay"]
+           "adpsgd_probe_mfma", "adpsgd_probe_stream", "adpsgd_step_masked", "adpsgd_delay",
+           "adpsgd_capture_begin", "adpsgd_capture_end", "adpsgd_graph_replay", "adpsgd_graph_steps", "adpsgd_graph_destroy"]
 STATIC_MAX_ELEMENTS = 1 << 34
 TUNE_GEMM_TILE, TUNE_REC_DIRECT, TUNE_REC_FWD_GROUPS, TUNE_REC_PERSISTENT, TUNE_REC_WAIT_US, TUNE_MEAN_CHUNK = 0, 1, 2, 3, 4, 5
 PHASES = ["stage_cast", "batched_gemm", "recurrent_fwd", "recurrent_bwd", "softmax_ce", "bias_colsum", "mix_update"]
@@ -133,6 +141,28 @@ def adpsgd_step_masked(h, batch_ptrs, lr, active):
 
 def adpsgd_delay(microseconds, stream_ptr):
     _check(_lib.adpsgd_delay(int(microseconds), stream_ptr))
+
+
+def adpsgd_capture_begin(h):
+    _check(_lib.adpsgd_capture_begin(h))
+
+
+def adpsgd_capture_end(h):
+    g = _vp()
+    _check(_lib.adpsgd_capture_end(h, C.byref(g)))
+    return g
+
+
+def adpsgd_graph_replay(g):
+    _check(_lib.adpsgd_graph_replay(g))
+
+
+def adpsgd_graph_steps(g):
+    return _lib.adpsgd_graph_steps(g)
+
+
+def adpsgd_graph_destroy(g):
+    _lib.adpsgd_graph_destroy(g)
 
 
 def adpsgd_params(h, i):
@@ -303,6 +333,14 @@ class Adpsgd:
 
     def tune(self, key, value):
         adpsgd_set_tuning(self.h, key, value)
+
+    def capture_begin(self):
+        adpsgd_capture_begin(self.h)
+
+    def capture_end(self):
+        """Returns the recording; replay it with adpsgd_graph_replay, free it with adpsgd_graph_destroy
+        before close()."""
+        return adpsgd_capture_end(self.h)
 
     def close(self):
         if self.h is not None:

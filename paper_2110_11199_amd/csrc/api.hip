@@ -95,6 +95,8 @@ struct Profiler {
     double bytes[ADPSGD_PHASES];      // algorithmic HBM bytes (each operand and result once)
 };
 
+struct adpsgd_graph;
+
 struct adpsgd_handle {
     Profiler prof;
     adpsgd_config cfg;
@@ -121,6 +123,12 @@ struct adpsgd_handle {
     int64_t k;
     int cur;                               // index of the buffer holding x^k
     bool shadow_valid;                     // the bf16 copy already holds the next gradient point
+    // iterations being recorded into a HIP graph (adpsgd_capture_begin .. adpsgd_capture_end): nothing runs, and the
+    // host-side state of the handle is put back to these values when the recording ends
+    std::vector<struct adpsgd_graph*> graphs;   // recordings made on this handle that are still alive
+    bool capturing = false;
+    int64_t capture_k0 = 0;
+    int capture_cur0 = 0;
     std::vector<Tensor> tensors;           // flat layout
     std::vector<int> ix_wx, ix_wh, ix_b;   // tensor index per layer
     int ix_wp, ix_bp, ix_wo, ix_bo;
@@ -137,6 +145,15 @@ struct adpsgd_handle {
     float* cbuf;       // [layers][L][D][M][H]
     void* z; void* dz; float* logits; void* dlogits; float* dy; void* da; float* dc;
     float* row_loss; float* loss;
+};
+
+// A recorded sequence of iterations of one handle (adpsgd_capture_end), replayed by adpsgd_graph_replay.
+struct adpsgd_graph {
+    adpsgd_t owner;
+    hipGraph_t graph;
+    hipGraphExec_t exec;
+    int64_t steps;                         // iterations recorded
+    int64_t k0;                            // iteration number of the first one (its parity must match at replay)
 };
 
 namespace {
@@ -781,6 +798,7 @@ float* adpsgd_params(adpsgd_t h, int i) {
 
 int adpsgd_set_params(adpsgd_t h, int i, const float* dev_src) {
     if (!h || !dev_src || i < -1 || i >= h->L) return fail(ADPSGD_EINVAL, "bad argument");
+    if (h->capturing) return fail(ADPSGD_EINVAL, "not while iterations are being recorded (adpsgd_capture_begin)");
     const int lo = i < 0 ? 0 : i, hi = i < 0 ? h->L : i + 1;
     h->shadow_valid = false;
     for (int b = 0; b <= h->tau; ++b)
@@ -796,6 +814,7 @@ float* adpsgd_grads(adpsgd_t h, int i) {
 
 int adpsgd_losses(adpsgd_t h, float* host_out) {
     if (!h || !host_out || h->flat) return fail(ADPSGD_EINVAL, "bad argument");
+    if (h->capturing) return fail(ADPSGD_EINVAL, "not while iterations are being recorded (adpsgd_capture_begin)");
     HIPCHK(hipMemcpyAsync(host_out, h->loss, (size_t)h->L * 4, hipMemcpyDeviceToHost, h->stream), "loss copy");
     HIPCHK(hipStreamSynchronize(h->stream), "stream sync");
     return status_error(h);
@@ -808,6 +827,101 @@ int adpsgd_step_masked(adpsgd_t h, const void* const* batch_ptrs, float lr, cons
     return step_guarded(h, batch_ptrs, lr, active);
 }
 
+// ---- HIP-graph replay of iterations ----------------------------------------------------------------
+// adpsgd_step enqueues kernels and one 4-byte copy to pinned memory, nothing else (no host wait, no allocation, no
+// memset node), so its stream work can be recorded once and replayed.  What a recording fixes: the batch pointers, the
+// learning rate, and the schedule of the recorded iterations; it therefore needs a schedule that repeats (not the
+// random ring, no drawn stragglers), and on the patterns whose schedule or buffers alternate (fixed ring: the matching
+// phase; delay-by-one: the two model buffers) a whole number of periods, i.e. an even number of iterations.
+int adpsgd_capture_begin(adpsgd_t h) {
+    if (!h) return fail(ADPSGD_EINVAL, "NULL handle");
+    if (h->capturing) return fail(ADPSGD_EINVAL, "already recording");
+    if (int rc = status_error(h)) return rc;
+    if (!h->stream) return fail(ADPSGD_EINVAL, "the null stream cannot be recorded: create the handle on a stream of its own");
+    if (h->cfg.pattern == ADPSGD_RANDOM_RING || h->cfg.straggler_p > 0.f)
+        return fail(ADPSGD_EINVAL, "a recording replays the schedule of its iterations: the random ring and drawn stragglers change it every iteration");
+    if (h->prof.on) return fail(ADPSGD_EINVAL, "switch phase profiling off before recording");
+    if (!h->flat && h->prec && !h->shadow_valid)
+        return fail(ADPSGD_EINVAL, "run one iteration before recording (the bf16 copy of the models is made by the first one)");
+    HIPCHK(hipStreamBeginCapture(h->stream, hipStreamCaptureModeThreadLocal), "begin stream capture");
+    h->capturing = true;
+    h->capture_k0 = h->k;
+    h->capture_cur0 = h->cur;
+    return ADPSGD_OK;
+}
+
+int adpsgd_capture_end(adpsgd_t h, adpsgd_graph_t* out) {
+    if (!h || !out) return fail(ADPSGD_EINVAL, "NULL argument");
+    if (!h->capturing) return fail(ADPSGD_EINVAL, "not recording");
+    *out = nullptr;
+    hipGraph_t graph = nullptr;
+    const hipError_t e = hipStreamEndCapture(h->stream, &graph);
+    // nothing has run: the handle goes back to where the recording began
+    const int64_t steps = h->k - h->capture_k0;
+    h->capturing = false;
+    h->k = h->capture_k0;
+    h->cur = h->capture_cur0;
+    if (e != hipSuccess || !graph) {
+        if (graph) (void)hipGraphDestroy(graph);
+        return hipfail(e != hipSuccess ? e : hipErrorUnknown, "end stream capture");
+    }
+    const bool alternates = h->tau == 1 || h->cfg.pattern == ADPSGD_FIXED_RING;
+    if (steps < 1 || (alternates && steps % 2 != 0)) {
+        (void)hipGraphDestroy(graph);
+        return fail(ADPSGD_EINVAL, steps < 1 ? "no iteration was recorded"
+                                             : "record an even number of iterations: the fixed ring's matching and the two model "
+                                               "buffers of delay-by-one alternate from one iteration to the next");
+    }
+    hipGraphExec_t exec = nullptr;
+    const hipError_t ei = hipGraphInstantiate(&exec, graph, nullptr, nullptr, 0);
+    if (ei != hipSuccess) {
+        (void)hipGraphDestroy(graph);
+        return hipfail(ei, "graph instantiate");
+    }
+    adpsgd_graph* g = new (std::nothrow) adpsgd_graph{h, graph, exec, steps, h->capture_k0};
+    if (!g) {
+        (void)hipGraphExecDestroy(exec);
+        (void)hipGraphDestroy(graph);
+        return fail(ADPSGD_ENOMEM, "out of host memory");
+    }
+    try { h->graphs.push_back(g); } catch (...) {
+        (void)hipGraphExecDestroy(exec); (void)hipGraphDestroy(graph); delete g;
+        return fail(ADPSGD_ENOMEM, "out of host memory");
+    }
+    *out = g;
+    return ADPSGD_OK;
+}
+
+int adpsgd_graph_replay(adpsgd_graph_t g) {
+    if (!g) return fail(ADPSGD_EINVAL, "NULL graph");
+    if (!g->owner) return fail(ADPSGD_EINVAL, "the handle of this recording has been destroyed");
+    adpsgd_t h = g->owner;
+    if (h->capturing) return fail(ADPSGD_EINVAL, "not while iterations are being recorded (adpsgd_capture_begin)");
+    if (int rc = status_error(h)) return rc;
+    const bool alternates = h->tau == 1 || h->cfg.pattern == ADPSGD_FIXED_RING;
+    if (alternates && ((h->k - g->k0) % 2 != 0))
+        return fail(ADPSGD_EINVAL, "the handle stands at an iteration of the other parity than the recording's first one");
+    if (h->prof.on) return fail(ADPSGD_EINVAL, "switch phase profiling off before replaying");
+    HIPCHK(hipGraphLaunch(g->exec, h->stream), "graph launch");
+    h->k += g->steps;
+    return ADPSGD_OK;
+}
+
+int64_t adpsgd_graph_steps(adpsgd_graph_t g) { return g ? g->steps : -1; }
+
+void adpsgd_graph_destroy(adpsgd_graph_t g) {
+    if (!g) return;
+    if (g->owner) {
+        (void)hipStreamSynchronize(g->owner->stream);               // a replay may still be running
+        std::vector<adpsgd_graph*>& v = g->owner->graphs;
+        for (size_t i = 0; i < v.size(); ++i)
+            if (v[i] == g) { v.erase(v.begin() + (long)i); break; }
+    }
+    (void)hipGraphExecDestroy(g->exec);
+    (void)hipGraphDestroy(g->graph);
+    delete g;
+}
+
 int adpsgd_delay(uint64_t microseconds, void* hip_stream) {
     if (microseconds > 10000000ull) return fail(ADPSGD_EINVAL, "at most 10 000 000 microseconds");
     HIPCHK(launch_delay(microseconds * 100ull, (hipStream_t)hip_stream), "delay kernel");
@@ -816,6 +930,7 @@ int adpsgd_delay(uint64_t microseconds, void* hip_stream) {
 
 int adpsgd_status(adpsgd_t h) {
     if (!h) return fail(ADPSGD_EINVAL, "NULL handle");
+    if (h->capturing) return fail(ADPSGD_EINVAL, "not while iterations are being recorded (adpsgd_capture_begin)");
     if (!h->flat) HIPCHK(hipMemcpyAsync((void*)h->status_host, h->status, 4, hipMemcpyDeviceToHost, h->stream), "status copy");
     HIPCHK(hipStreamSynchronize(h->stream), "stream sync");
     return status_error(h);
@@ -877,12 +992,14 @@ int64_t adpsgd_iteration(adpsgd_t h) { return h ? h->k : -1; }
 
 int adpsgd_average(adpsgd_t h, float* dev_out) {
     if (!h || !dev_out) return fail(ADPSGD_EINVAL, "NULL argument");
+    if (h->capturing) return fail(ADPSGD_EINVAL, "not while iterations are being recorded (adpsgd_capture_begin)");
     HIPCHK(launch_average(h->params[h->cur], h->Ppad, h->L, h->P, dev_out, h->stream), "average");
     return ADPSGD_OK;
 }
 
 int adpsgd_consensus(adpsgd_t h, double* host_out) {
     if (!h || !host_out) return fail(ADPSGD_EINVAL, "NULL argument");
+    if (h->capturing) return fail(ADPSGD_EINVAL, "not while iterations are being recorded (adpsgd_capture_begin)");
     HIPCHK(launch_consensus(h->params[h->cur], h->Ppad, h->L, h->P, h->consensus, h->consensus + kConsensusBlocks, h->stream),
            "consensus distance");
     HIPCHK(hipMemcpyAsync(host_out, h->consensus + kConsensusBlocks, 8, hipMemcpyDeviceToHost, h->stream), "consensus copy");
@@ -903,6 +1020,7 @@ int adpsgd_consensus_static(const float* dev_x, int64_t stride, int32_t L, int64
 
 int adpsgd_set_profiling(adpsgd_t h, int enable) {
     if (!h) return fail(ADPSGD_EINVAL, "NULL handle");
+    if (h->capturing) return fail(ADPSGD_EINVAL, "not while iterations are being recorded (adpsgd_capture_begin)");
     h->prof.on = enable != 0;
     prof_reset(h);
     return ADPSGD_OK;
@@ -910,6 +1028,7 @@ int adpsgd_set_profiling(adpsgd_t h, int enable) {
 
 int adpsgd_profile(adpsgd_t h, float* host_ms, int32_t* host_launches, double* host_work, double* host_bytes) {
     if (!h) return fail(ADPSGD_EINVAL, "NULL handle");
+    if (h->capturing) return fail(ADPSGD_EINVAL, "not while iterations are being recorded (adpsgd_capture_begin)");
     Profiler& p = h->prof;
     HIPCHK(hipStreamSynchronize(h->stream), "stream sync");
     float ms[ADPSGD_PHASES] = {0};
@@ -932,7 +1051,14 @@ int adpsgd_profile(adpsgd_t h, float* host_ms, int32_t* host_launches, double* h
 
 void adpsgd_destroy(adpsgd_t h) {
     if (!h) return;
+    if (h->capturing) {                              // a recording left open: close it and drop what it holds
+        hipGraph_t graph = nullptr;
+        (void)hipStreamEndCapture(h->stream, &graph);
+        if (graph) (void)hipGraphDestroy(graph);
+        h->capturing = false;
+    }
     for (hipEvent_t e : h->prof.ev) (void)hipEventDestroy(e);
+    for (adpsgd_graph* g : h->graphs) g->owner = nullptr;   // they can still be destroyed, no longer replayed
     if (h->status_host) {
         (void)hipStreamSynchronize(h->stream);       // the last status copy may still be in flight
         (void)hipHostFree((void*)h->status_host);

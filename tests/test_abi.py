@@ -124,10 +124,13 @@ def test_argument_checks_that_need_no_gpu():
     for call in (lambda: Bd.adpsgd_set_tuning(None, Bd.TUNE_GEMM_TILE, 12), lambda: Bd.adpsgd_status(None),
                  lambda: Bd.adpsgd_delay(10_000_001, None), lambda: Bd.adpsgd_step_masked(None, [None], 0.1, [1]),
                  lambda: Bd.adpsgd_probe_mfma(None, 1, 1, None), lambda: Bd.adpsgd_probe_stream(3, 1, 0, 0x10000, 64, 16, None),
-                 lambda: Bd.adpsgd_probe_stream(2, 1, 0, 0x10000, 60, 16, None)):
+                 lambda: Bd.adpsgd_probe_stream(2, 1, 0, 0x10000, 60, 16, None),
+                 lambda: Bd.adpsgd_capture_begin(None), lambda: Bd.adpsgd_capture_end(None), lambda: Bd.adpsgd_graph_replay(None)):
         with pytest.raises(Bd.AdpsgdError) as ei:
             call()
         assert ei.value.code == Bd.EINVAL
+    assert Bd.adpsgd_graph_steps(None) == -1
+    Bd.adpsgd_graph_destroy(None)       # a no-op
     fake = 0x10000      # never dereferenced: the size checks come first
     for ptr, stride, L, P, out in ((None, 8, 2, 8, fake), (fake, 8, 2, 8, None), (fake, 8, 0, 8, fake), (fake, 8, 129, 8, fake),
                                    (fake, 4, 2, 8, fake), (fake, 8, 2, 0, fake), (fake, 8, 2, 8, fake + 4),
