@@ -249,7 +249,7 @@ def load_traffic(path=TRAFFIC_FILE):
     out = {"cfg4/batched_gemm": mean(lambda k: "::gemm_" in k),
            "cfg4/recurrent": mean(lambda k: "::rec_" in k),
            "cfg4/mix_update": mean(lambda k: "::all_update_kernel" in k),
-           "cfg5/mix_update": mean(lambda k: "::pair_update_kernel" in k)}
+           "cfg5/mix_update": mean(lambda k: "::pair_update_kernel" in k or "::pair_split_update_kernel" in k)}
     return {k: v for k, v in out.items() if v is not None}
 
 
@@ -303,7 +303,7 @@ def main():
                     "learner_steps_per_s": active / dt,
                     "config": {"workload": wl.name, "L": wl.L, "flat_params": wl.flat_params, "pattern": "random ring",
                                "straggler_p": wl.straggler_p, "note": "model-free: no frames"},
-                    "roofline": hbm_roofline(prof, ["mix_update"], "pair_update_kernel", wl.name, "mix_update", "hbm_2read_1write_x2_GBps")})
+                    "roofline": hbm_roofline(prof, ["mix_update"], "pair_split_update_kernel", wl.name, "mix_update", "hbm_2read_1write_GBps")})
         out["mix_update_GBps"] = out["roofline"]["achieved"]
     else:
         dt, prof, loss = run_model(wl, args.steps, args.warmup, tune=tune)
@@ -336,13 +336,13 @@ def main():
                          "flops_per_launch": g["work"] / max(g["launches"], 1),
                          "algorithmic_bytes_per_launch": g["bytes"] / max(g["launches"], 1)},
             "roofline_recurrent": rec,
-            "roofline_update": hbm_roofline(prof, ["mix_update"], "all_update_kernel / pair_update_kernel", wl.name, "mix_update",
+            "roofline_update": hbm_roofline(prof, ["mix_update"], "all_mean_kernel + all_apply_kernel (global mean) / pair_split_update_kernel", wl.name, "mix_update",
                                             "hbm_2read_1write_1bf16_x16_GBps" if wl.precision else "hbm_2read_1write_x2_GBps"),
         })
         if args.mix_steps > 0:
             w5 = synth.WORKLOADS["cfg5"]
             dt5, prof5, active5 = run_flat(w5, args.mix_steps, 2)
-            r5 = hbm_roofline(prof5, ["mix_update"], "pair_update_kernel", "cfg5", "mix_update", "hbm_2read_1write_x2_GBps")
+            r5 = hbm_roofline(prof5, ["mix_update"], "pair_split_update_kernel", "cfg5", "mix_update", "hbm_2read_1write_GBps")
             r5.update({"workload": "cfg5", "steps": args.mix_steps, "ms_per_step": dt5 / args.mix_steps * 1e3,
                        "learner_steps_per_s": active5 / dt5})
             out["mix_update"] = r5

@@ -112,6 +112,8 @@ struct adpsgd_handle {
     float* mean_buf = nullptr;             // chunk buffer of the two-kernel global mean (mix ALL)
     int64_t mean_cap = 0;                  // its size in elements: min(kMeanChunkMax, P rounded up to 1024)
     int64_t tune_mean_chunk = -1;          // elements per chunk; 0: the single-kernel global mean; -1: automatic
+    int tune_pair_split = -1;              // pairwise update: one member of a pair per thread (positions per workgroup), 0 off, -1 default
+    int tune_tri_segment = -1;             // ring-neighbour update: ring positions per thread (0: the whole ring), -1: default
     // device status word (kStatus* bits, sticky) and its pinned host mirror, refreshed by an asynchronous
     // copy at the end of every step
     uint32_t* status = nullptr;
@@ -745,6 +747,8 @@ static int step_impl(adpsgd_t h, const void* const* batch_ptrs, float lr, const 
     u.L = L; u.mix = h->mix; u.P = h->P; u.src = xk; u.dst = xnext; u.stride = h->Ppad; u.lr = lr;
     u.update_first = h->cfg.pattern == ADPSGD_SDPSGD;
     u.group_size = is_hybrid(h->mix) ? h->cfg.group_size : 1;
+    u.tri_segment = h->tune_tri_segment;
+    u.pair_split = h->tune_pair_split;
     {   // two-kernel global mean: by default on models large enough for the extra launches not to matter
         int64_t chunk = h->tune_mean_chunk >= 0 ? h->tune_mean_chunk : (h->P >= (4 << 20) ? kMeanChunkDefault : 0);
         if (chunk > h->mean_cap) chunk = h->mean_cap;
@@ -1124,6 +1128,13 @@ int adpsgd_set_tuning(adpsgd_t h, int key, int value) {
             if (value != 0 && value != -1 && (value < 1024 || value > kMeanChunkMax || value % 1024))
                 return fail(ADPSGD_EINVAL, "-1 (automatic), 0 (single kernel) or a multiple of 1024 elements up to 16777216");
             h->tune_mean_chunk = value; return ADPSGD_OK;
+        case ADPSGD_TUNE_PAIR_SPLIT:
+            if (value != -1 && value != 0 && value != 64 && value != 128) return fail(ADPSGD_EINVAL, "-1 (default), 0, 64 or 128");
+            h->tune_pair_split = value; return ADPSGD_OK;
+        case ADPSGD_TUNE_TRI_SEGMENT:
+            if (value != -1 && value != 0 && value != 1 && value != 2 && value != 4 && value != 8)
+                return fail(ADPSGD_EINVAL, "-1 (default), 0 (one thread walks the whole ring), 1, 2, 4 or 8 ring positions per thread");
+            h->tune_tri_segment = value; return ADPSGD_OK;
         case ADPSGD_TUNE_REC_WAIT_US:
             if (value < 0) return fail(ADPSGD_EINVAL, "microseconds >= 0");
             h->tune_wait_us = value; return ADPSGD_OK;

@@ -87,17 +87,17 @@ __global__ __launch_bounds__(256) void pair_update_kernel(PairArgs p) {
     bf16_t* shb = p.shadow ? p.shadow + b * p.stride : nullptr;
     if constexpr (VEC) {
         const int64_t n4 = p.P >> 2;
-        const int64_t base = (int64_t)blockIdx.x * (256 * kUnroll) + threadIdx.x;
+        const int64_t base = (int64_t)blockIdx.x * (blockDim.x * kUnroll) + threadIdx.x;
         if (a == b) {
             float4 x[kUnroll], g[kUnroll];
 #pragma unroll
             for (int u = 0; u < kUnroll; ++u) {
-                const int64_t e = base + u * 256;
+                const int64_t e = base + u * blockDim.x;
                 if (e < n4) { x[u] = ldnt_(xa, e); g[u] = ldnt_(ga, e); }
             }
 #pragma unroll
             for (int u = 0; u < kUnroll; ++u) {
-                const int64_t e = base + u * 256;
+                const int64_t e = base + u * blockDim.x;
                 if (e < n4) {
                     const float4 r = pair_new_(x[u], lr, g[u]);
                     stnt_(oa, e, r);
@@ -108,7 +108,7 @@ __global__ __launch_bounds__(256) void pair_update_kernel(PairArgs p) {
             float4 x[kUnroll], y[kUnroll], g[kUnroll], h[kUnroll];
 #pragma unroll
             for (int u = 0; u < kUnroll; ++u) {
-                const int64_t e = base + u * 256;
+                const int64_t e = base + u * blockDim.x;
                 if (e < n4) {
                     x[u] = ldnt_(xa, e); y[u] = ldnt_(xb, e);
                     g[u] = ldnt_(ga, e); h[u] = ldnt_(gb, e);
@@ -116,7 +116,7 @@ __global__ __launch_bounds__(256) void pair_update_kernel(PairArgs p) {
             }
 #pragma unroll
             for (int u = 0; u < kUnroll; ++u) {
-                const int64_t e = base + u * 256;
+                const int64_t e = base + u * blockDim.x;
                 if (e < n4) {
                     const float4 m = half_sum_(x[u], y[u]);
                     const float4 ra = pair_new_(m, lr, g[u]), rb = pair_new_(m, lr, h[u]);
@@ -132,14 +132,49 @@ __global__ __launch_bounds__(256) void pair_update_kernel(PairArgs p) {
             pair_scalar_(xa, xb, ga, gb, oa, ob, sha, shb, a == b, p.emit_input, lr, e);
         }
     } else {
-        const int64_t base = (int64_t)blockIdx.x * (256 * kUnroll) + threadIdx.x;
+        const int64_t base = (int64_t)blockIdx.x * (blockDim.x * kUnroll) + threadIdx.x;
 #pragma unroll
         for (int u = 0; u < kUnroll; ++u) {
-            const int64_t e = base + u * 256;
+            const int64_t e = base + u * blockDim.x;
             if (e >= p.P) continue;
             pair_scalar_(xa, xb, ga, gb, oa, ob, sha, shb, a == b, p.emit_input, lr, e);
         }
     }
+}
+
+// The same pairwise update with ONE member of a pair per thread: a workgroup of NX positions x 2 members; a thread
+// reads its member's model and gradient (two streams, 1 KB contiguous per wave and stream), hands the model to its
+// partner thread through LDS, and writes its member's result after the workgroup's barrier, i.e. after both models
+// of these positions have been read: safe in place like the two-member form, same operations (the pair sum is
+// commutative), bit-identical results.  For a work item without a partner (a == b) the two halves of the workgroup
+// take adjacent positions of the one learner (and the workgroups past its end have nothing to do).
+template <int NX>
+__global__ __launch_bounds__(2 * NX) void pair_split_update_kernel(PairArgs p) {
+    __shared__ float4 other[2 * NX];
+    const int w = blockIdx.y, member = threadIdx.y, tx = threadIdx.x;
+    const int a = p.a[w], b = p.b[w];
+    const bool solo = a == b;
+    const int i = member ? b : a;
+    const int64_t n4 = p.P >> 2;
+    // a pair: both halves of the workgroup at the same NX positions; no partner: the halves at adjacent ones
+    const int64_t e = solo ? (int64_t)blockIdx.x * (2 * NX) + member * NX + tx : (int64_t)blockIdx.x * NX + tx;
+    const bool ok = e < n4;
+    float4 x = make_float4(0.f, 0.f, 0.f, 0.f), g = x;
+    if (ok) { x = ldnt_(p.src + i * p.stride, e); g = ldnt_(p.g[i], e); }
+    other[member * NX + tx] = x;
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    if (ok) {
+        const float4 m = solo ? x : half_sum_(x, other[(1 - member) * NX + tx]);
+        const float4 r = pair_new_(m, p.lr, g);
+        stnt_(p.dst + i * p.stride, e, r);
+        if (p.shadow) emit4_(p.shadow + i * p.stride, e, p.emit_input ? x : r);
+    }
+    // tail (P % 4 elements): one thread handles both members of an element
+    if (blockIdx.x == 0 && member == 0 && tx < (p.P & 3))
+        pair_scalar_(p.src + a * p.stride, p.src + b * p.stride, p.g[a], p.g[b], p.dst + a * p.stride, p.dst + b * p.stride,
+                     p.shadow ? p.shadow + a * p.stride : nullptr, p.shadow ? p.shadow + b * p.stride : nullptr, solo,
+                     p.emit_input, p.lr, (n4 << 2) + tx);
 }
 
 struct AllArgs {
@@ -254,7 +289,7 @@ struct AllSplitArgs {
 
 __global__ __launch_bounds__(256) void all_mean_kernel(AllSplitArgs q) {
     const AllArgs& p = q.a;
-    const int64_t c = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const int64_t c = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (c >= q.n4c) return;
     const int64_t e = q.e0 + c;
     float4 s = ldnt_(p.src, e);
@@ -271,7 +306,7 @@ __global__ __launch_bounds__(256) void all_mean_kernel(AllSplitArgs q) {
 
 __global__ __launch_bounds__(256) void all_apply_kernel(AllSplitArgs q) {
     const AllArgs& p = q.a;
-    const int64_t c = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const int64_t c = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (c >= q.n4c) return;
     const int64_t e = q.e0 + c;
     const int i = blockIdx.y;
@@ -337,6 +372,67 @@ __global__ __launch_bounds__(256) void tri_update_kernel(TriArgs p) {
     } else {
         if (e < p.P) tri_scalar_(p, e);
     }
+}
+
+// The same operator with the ring cut into segments of SEG positions.  A workgroup of blockDim.x element positions
+// x blockDim.y segments covers all L learners of its element positions; a thread owns one segment at one position:
+// it reads its SEG models and gradients (2 SEG streams instead of 2 L: the rate of a streaming kernel on this
+// device falls with the number of streams a thread walks at once), hands the first and last model of its segment to
+// the neighbouring segments through LDS, and writes its SEG results after the workgroup's barrier, i.e. after every
+// model of these positions has been read: safe in place like the single walk, the same 12 bytes per learner and
+// element (no model is read twice), the same operations per element, bit-identical results.
+template <int SEG>
+__global__ __launch_bounds__(1024) void tri_seg_update_kernel(TriArgs p) {
+    __shared__ float4 edge[2 * 1024];                            // [first | last][segment][position]
+    const int tx = threadIdx.x, sy = threadIdx.y, nx = blockDim.x, ns = blockDim.y;
+    const int64_t e = (int64_t)blockIdx.x * nx + tx;
+    const bool ok = e < (p.P >> 2);
+    const int q0 = sy * SEG;
+    float4 x[SEG], g[SEG];
+    float4 lastv = make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+    for (int j = 0; j < SEG; ++j) {
+        if (ok && q0 + j < p.L) {
+            const int i = p.order[q0 + j];
+            x[j] = ldnt_(p.src + i * p.stride, e);
+            g[j] = ldnt_(p.g[i], e);
+            lastv = x[j];
+        }
+    }
+    if (ok) { edge[sy * nx + tx] = x[0]; edge[(ns + sy) * nx + tx] = lastv; }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");             // every model of this thread is in registers ...
+    __syncthreads();                                             // ... and so is every other thread's: writing may begin
+    if (!ok) return;
+    float4 prev = edge[(ns + (sy + ns - 1) % ns) * nx + tx];
+    const float4 after = edge[((sy + 1) % ns) * nx + tx];
+#pragma unroll
+    for (int j = 0; j < SEG; ++j) {
+        if (q0 + j >= p.L) break;
+        const int i = p.order[q0 + j];
+        float4 next = after;
+        if (j + 1 < SEG && q0 + j + 1 < p.L) next = x[j + 1 < SEG ? j + 1 : j];
+        const float4 m = make_float4(tri_mean_(prev.x, x[j].x, next.x, p.third), tri_mean_(prev.y, x[j].y, next.y, p.third),
+                                     tri_mean_(prev.z, x[j].z, next.z, p.third), tri_mean_(prev.w, x[j].w, next.w, p.third));
+        const float4 r = pair_new_(m, p.lr, g[j]);
+        stnt_(p.dst + i * p.stride, e, r);
+        if (p.shadow) emit4_(p.shadow + i * p.stride, e, p.emit_input ? x[j] : r);
+        prev = x[j];
+    }
+}
+
+// the P % 4 last elements of every learner (one thread each walks the whole ring)
+__global__ void tri_tail_kernel(TriArgs p) {
+    if (threadIdx.x < (p.P & 3)) tri_scalar_(p, ((p.P >> 2) << 2) + threadIdx.x);
+}
+
+template <int SEG>
+static void launch_tri_seg(const TriArgs& a, hipStream_t s) {
+    const int ns = (a.L + SEG - 1) / SEG;                        // at most 128 segments (L <= 128)
+    int nx = 64;
+    while (nx * ns > 512 && nx > 8) nx >>= 1;
+    const int64_t n4 = a.P >> 2;
+    hipLaunchKernelGGL(tri_seg_update_kernel<SEG>, dim3((unsigned)((n4 + nx - 1) / nx)), dim3((unsigned)nx, (unsigned)ns), 0, s, a);
+    if (a.P & 3) hipLaunchKernelGGL(tri_tail_kernel, dim3(1), dim3(64), 0, s, a);
 }
 
 // ---- hybrid mixing (Section V: synchronous super-learners joined by the asynchronous ring) -----------
@@ -512,6 +608,7 @@ hipError_t launch_update(const UpdateDesc& d, hipStream_t s) {
             q.a = a; q.mean = d.mean_buf;
             for (int64_t e0 = 0; e0 < n4; e0 += chunk4) {
                 q.e0 = e0; q.n4c = n4 - e0 < chunk4 ? n4 - e0 : chunk4;
+                // (workgroups of 64 or 128 threads instead of 256 change nothing here: 5.8 - 6.0 TB/s in all nine combinations)
                 const unsigned blocks = (unsigned)((q.n4c + 255) / 256);
                 hipLaunchKernelGGL(all_mean_kernel, dim3(blocks), dim3(256), 0, s, q);
                 hipLaunchKernelGGL(all_apply_kernel, dim3(blocks, (unsigned)d.L), dim3(256), 0, s, q);
@@ -541,7 +638,16 @@ hipError_t launch_update(const UpdateDesc& d, hipStream_t s) {
             if (d.order[i] < 0 || d.order[i] >= d.L || seen[d.order[i]]) return hipErrorInvalidValue;
             seen[d.order[i]] = true;
         }
-        if (vec) {
+        // Two ring positions per thread are the measured best on large models (64 x 135M: 5.0 -> 5.4-5.5 TB/s, 16 x 145M:
+        // 5.5 -> 6.1; one position 5.2 / 5.8, four 5.4 / 5.0, eight 4.9 / 3.3); on small ones the single walk's fewer,
+        // larger workgroups are as fast or faster.
+        const int seg = d.tri_segment < 0 ? ((d.P >= (4 << 20) && d.L >= 4) ? 2 : 0) : d.tri_segment;
+        if (vec && (d.P >> 2) > 0 && seg >= 1 && d.L > seg) {
+            if (seg == 1) launch_tri_seg<1>(a, s);
+            else if (seg >= 8) launch_tri_seg<8>(a, s);
+            else if (seg >= 4) launch_tri_seg<4>(a, s);
+            else launch_tri_seg<2>(a, s);
+        } else if (vec) {
             const int64_t n4 = d.P >> 2;
             hipLaunchKernelGGL(tri_update_kernel<true>, dim3((unsigned)(((n4 > 0 ? n4 : 1) + 255) / 256)), dim3(256), 0, s, a);
         } else {
@@ -562,6 +668,18 @@ hipError_t launch_update(const UpdateDesc& d, hipStream_t s) {
     }
     a.nwork = n;
     if (n == 0) return hipSuccess;
+    // One member per thread in workgroups of 64 positions x 2 members is the measured best on large models (64 x 135M,
+    // random ring, 10 % stragglers: 5.9 -> 6.3 TB/s; 16 x 145M: 5.9 -> 6.6; 128 positions 6.15 / 6.3, 32: 6.1 / 6.45,
+    // 256: 6.0 / 6.25; the two-member kernel in workgroups of 64 threads 6.1 / 6.3).
+    const int split = d.pair_split < 0 ? (d.P >= (1 << 20) ? 64 : 0) : d.pair_split;
+    if (vec && split > 0 && (d.P >> 2) > 0) {
+        const int64_t n4 = d.P >> 2;
+        if (split == 128)
+            hipLaunchKernelGGL(pair_split_update_kernel<128>, dim3((unsigned)((n4 + 127) / 128), (unsigned)n), dim3(128, 2), 0, s, a);
+        else
+            hipLaunchKernelGGL(pair_split_update_kernel<64>, dim3((unsigned)((n4 + 63) / 64), (unsigned)n), dim3(64, 2), 0, s, a);
+        return hipGetLastError();
+    }
     if (vec) {
         const int64_t n4 = d.P >> 2;
         const int64_t per = 256 * kUnroll;

@@ -43,6 +43,23 @@ def test_pairwise_random_ring_with_stragglers(P):
     _run(8, P, S.RANDOM_RING, 6, p=0.3)
 
 
+@pytest.mark.parametrize("split", [0, 64, 128])
+@pytest.mark.parametrize("L,P,p", [(8, 1, 0.3), (8, 3, 0.0), (8, 4, 0.3), (7, 1023, 0.3), (2, 70001, 0.0), (64, 20003, 0.2), (128, 1000, 0.1)])
+def test_pairwise_update_with_one_or_both_members_of_a_pair_per_thread(L, P, p, split):
+    # both forms of the pairwise kernel (a thread owns both members of a pair, or one and gets the partner's model through
+    # LDS), forced: unmatched learners, stragglers, P % 4 tails, fewer than four elements, in place and ping-pong (tau = 1)
+    from paper_2110_11199_amd import binding as Bd
+    print("update pair split", L, P, p, split, flush=True)
+    _run(L, P, S.RANDOM_RING, 4, p=p, tune=[(Bd.TUNE_PAIR_SPLIT, split)])
+    _run(L, P, S.FIXED_RING, 3, tune=[(Bd.TUNE_PAIR_SPLIT, split)])
+    _run(L, P, S.D1D, 3, mix=S.MIX_PAIR, tune=[(Bd.TUNE_PAIR_SPLIT, split)])
+
+
+def test_pairwise_update_at_a_size_that_takes_the_split_form_by_default():
+    print("update pair, 6 x (1M + 1) elements", flush=True)
+    _run(6, (1 << 20) + 1, S.RANDOM_RING, 3, p=0.2)
+
+
 @pytest.mark.parametrize("L", [1, 2, 3, 5, 64])
 def test_pairwise_fixed_ring(L):
     print("update fixed L", L, flush=True)
@@ -77,6 +94,23 @@ def test_ring_neighbour_thirds(L, pattern):
 def test_ring_neighbour_thirds_sizes_and_delay(P):
     _run(7, P, S.RANDOM_RING, 4, mix=S.MIX_TRI)
     _run(7, P, S.D1D, 3, mix=S.MIX_TRI)              # tau = 1: ping-pong buffers
+
+
+@pytest.mark.parametrize("seg", [1, 2, 4, 8])
+@pytest.mark.parametrize("L,P", [(3, 70001), (5, 4099), (16, 70003), (64, 20001), (128, 1003), (13, 2)])
+def test_ring_neighbour_thirds_with_the_ring_in_segments(L, P, seg):
+    # a thread owns `seg` ring positions, a workgroup the whole ring of its element positions: segments that do not
+    # divide the ring, rings shorter than a segment (falls back to the single walk), P % 4 tails, fewer than four
+    # elements, in place (tau = 0) and ping-pong (tau = 1); bit-exact against the oracle like the single walk
+    from paper_2110_11199_amd import binding as Bd
+    print("update tri segments", L, P, seg, flush=True)
+    _run(L, P, S.RANDOM_RING, 3, mix=S.MIX_TRI, tune=[(Bd.TUNE_TRI_SEGMENT, seg)])
+    _run(L, P, S.D1D, 2, mix=S.MIX_TRI, tune=[(Bd.TUNE_TRI_SEGMENT, seg)])
+
+
+def test_ring_neighbour_thirds_at_a_size_that_takes_the_segmented_walk_by_default():
+    print("update tri, 4 x (4M + 3) elements", flush=True)
+    _run(4, (4 << 20) + 3, S.RANDOM_RING, 2, mix=S.MIX_TRI)
 
 
 def test_ring_neighbour_thirds_rejects_stragglers_and_rings_of_fewer_than_three():
