@@ -608,7 +608,8 @@ hipError_t launch_update(const UpdateDesc& d, hipStream_t s) {
             q.a = a; q.mean = d.mean_buf;
             for (int64_t e0 = 0; e0 < n4; e0 += chunk4) {
                 q.e0 = e0; q.n4c = n4 - e0 < chunk4 ? n4 - e0 : chunk4;
-                // (workgroups of 64 or 128 threads instead of 256 change nothing here: 5.8 - 6.0 TB/s in all nine combinations)
+                // (workgroups of 64 or 128 threads instead of 256 change nothing here: 5.8 - 6.0 TB/s in all nine combinations;
+                // a mean kernel with one (position, learner) per thread and the sum through LDS is slower: 5.1 - 5.8)
                 const unsigned blocks = (unsigned)((q.n4c + 255) / 256);
                 hipLaunchKernelGGL(all_mean_kernel, dim3(blocks), dim3(256), 0, s, q);
                 hipLaunchKernelGGL(all_apply_kernel, dim3(blocks, (unsigned)d.L), dim3(256), 0, s, q);
