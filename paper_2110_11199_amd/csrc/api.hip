@@ -574,7 +574,8 @@ int compute_gradients(adpsgd_handle* h, const float* at, const void* const* batc
         r.dy = h->dy; r.sDYi = M * DH;
         r.da = h->da; r.sDAi = M * G4;
         r.dc = h->dc; r.sDCi = (int64_t)B * DH;
-        const int64_t dbrows = (int64_t)T * rec_backward_batch_tiles(B);
+        // rows of partial bias sums per learner: one per frame and batch tile (the persistent kernel writes one per frame)
+        const int64_t dbrows = persist ? (int64_t)T : (int64_t)T * rec_backward_batch_tiles(B);
         r.dbp = h->dbp; r.sDBi = dbrows * G4;
         if (persist) {
             // per (learner, direction): W_h once; per frame: da in (4 gates) and out, dY, 4 gates, c, c'
