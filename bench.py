@@ -246,9 +246,18 @@ def load_traffic(path=TRAFFIC_FILE):
         sel = [(n, b) for name, n, b in rows if pred(name)]
         cnt = sum(n for n, _ in sel)
         return sum(n * b for n, b in sel) / cnt if cnt else None
+    def count(pred):
+        return sum(n for name, n, _ in rows if pred(name))
+    # the global-mean update runs as two kernels per chunk of the index: bytes per iteration = (mean + apply) x chunks,
+    # the chunks per iteration being their dispatches per softmax dispatch (one per iteration) in the profiled run
+    upd = mean(lambda k: "::all_update_kernel" in k)
+    b_mean, b_apply = mean(lambda k: "::all_mean_kernel" in k), mean(lambda k: "::all_apply_kernel" in k)
+    its = count(lambda k: "::softmax_ce" in k)
+    if upd is None and b_mean is not None and b_apply is not None and its:
+        upd = (b_mean + b_apply) * count(lambda k: "::all_mean_kernel" in k) / its
     out = {"cfg4/batched_gemm": mean(lambda k: "::gemm_" in k),
            "cfg4/recurrent": mean(lambda k: "::rec_" in k),
-           "cfg4/mix_update": mean(lambda k: "::all_update_kernel" in k),
+           "cfg4/mix_update": upd,
            "cfg5/mix_update": mean(lambda k: "::pair_update_kernel" in k or "::pair_split_update_kernel" in k)}
     return {k: v for k, v in out.items() if v is not None}
 
