@@ -180,6 +180,12 @@ def cpu_baseline(wl, seed=0, budget_s=12.0):
         out["one_thread"] = {"value": nb * wl.frames / dt1, "unit": "frames/s", "cores": 1,
                              "sample": "gradient of the first %d of the %d segments of learner 0's minibatch (%.1f s, "
                                        "BLAS pinned to one thread)" % (nb, wl.batch, dt1)}
+    try:                                      # which host the figures are from
+        with open("/proc/cpuinfo") as fh:
+            names = [ln.split(":", 1)[1].strip() for ln in fh if ln.startswith("model name")]
+        out["cpu_model"] = names[0] if names else None
+    except OSError:
+        out["cpu_model"] = None
     return out
 
 
