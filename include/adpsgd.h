@@ -367,6 +367,9 @@ int adpsgd_probe_stream(int reads, int writes_f32, int writes_bf16, void* dev_bu
                                            many element positions x 2 members (the partner's model comes through LDS), 0 =
                                            both members per thread, -1 = default (64 from 1M parameters on); same results
                                            bit for bit */
+#define ADPSGD_TUNE_SYNC_SEGMENT    8   /* update of the synchronous baseline (ADPSGD_SDPSGD): learners one thread owns, 2, 4 or
+                                           8 (the sum then runs through the segments of a workgroup in learner order), 0 =
+                                           all learners of a position in one thread, -1 = default; same results bit for bit */
 int adpsgd_set_tuning(adpsgd_t h, int key, int value);
 
 #ifdef __cplusplus

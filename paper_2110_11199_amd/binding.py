@@ -91,7 +91,7 @@ EXPORTS = ["adpsgd_workspace_bytes", "adpsgd_create", "adpsgd_step", "adpsgd_par
            "adpsgd_capture_begin", "adpsgd_capture_end", "adpsgd_graph_replay", "adpsgd_graph_steps", "adpsgd_graph_destroy"]
 STATIC_MAX_ELEMENTS = 1 << 34
 TUNE_GEMM_TILE, TUNE_REC_DIRECT, TUNE_REC_FWD_GROUPS, TUNE_REC_PERSISTENT, TUNE_REC_WAIT_US, TUNE_MEAN_CHUNK = 0, 1, 2, 3, 4, 5
-TUNE_TRI_SEGMENT, TUNE_PAIR_SPLIT = 6, 7
+TUNE_TRI_SEGMENT, TUNE_PAIR_SPLIT, TUNE_SYNC_SEGMENT = 6, 7, 8
 PHASES = ["stage_cast", "batched_gemm", "recurrent_fwd", "recurrent_bwd", "softmax_ce", "bias_colsum", "mix_update"]
 
 

@@ -113,6 +113,7 @@ struct adpsgd_handle {
     int64_t mean_cap = 0;                  // its size in elements: min(kMeanChunkMax, P rounded up to 1024)
     int64_t tune_mean_chunk = -1;          // elements per chunk; 0: the single-kernel global mean; -1: automatic
     int tune_pair_split = -1;              // pairwise update: one member of a pair per thread (positions per workgroup), 0 off, -1 default
+    int tune_sync_segment = -1;            // synchronous baseline: learners per thread of the update (0: all of them), -1: default
     int tune_tri_segment = -1;             // ring-neighbour update: ring positions per thread (0: the whole ring), -1: default
     // device status word (kStatus* bits, sticky) and its pinned host mirror, refreshed by an asynchronous
     // copy at the end of every step
@@ -749,6 +750,7 @@ static int step_impl(adpsgd_t h, const void* const* batch_ptrs, float lr, const 
     u.update_first = h->cfg.pattern == ADPSGD_SDPSGD;
     u.group_size = is_hybrid(h->mix) ? h->cfg.group_size : 1;
     u.tri_segment = h->tune_tri_segment;
+    u.sync_segment = h->tune_sync_segment;
     u.pair_split = h->tune_pair_split;
     {   // two-kernel global mean: by default on models large enough for the extra launches not to matter
         int64_t chunk = h->tune_mean_chunk >= 0 ? h->tune_mean_chunk : (h->P >= (4 << 20) ? kMeanChunkDefault : 0);
@@ -1132,6 +1134,10 @@ int adpsgd_set_tuning(adpsgd_t h, int key, int value) {
         case ADPSGD_TUNE_PAIR_SPLIT:
             if (value != -1 && value != 0 && value != 64 && value != 128) return fail(ADPSGD_EINVAL, "-1 (default), 0, 64 or 128");
             h->tune_pair_split = value; return ADPSGD_OK;
+        case ADPSGD_TUNE_SYNC_SEGMENT:
+            if (value != -1 && value != 0 && value != 2 && value != 4 && value != 8)
+                return fail(ADPSGD_EINVAL, "-1 (default), 0 (one thread owns all learners of a position), 2, 4 or 8 learners per thread");
+            h->tune_sync_segment = value; return ADPSGD_OK;
         case ADPSGD_TUNE_TRI_SEGMENT:
             if (value != -1 && value != 0 && value != 1 && value != 2 && value != 4 && value != 8)
                 return fail(ADPSGD_EINVAL, "-1 (default), 0 (one thread walks the whole ring), 1, 2, 4 or 8 ring positions per thread");

@@ -53,6 +53,7 @@ struct UpdateDesc {
     int update_first;          // mix 2 only: average the updated models x_j - lr*g_j (synchronous baseline)
     int pair_split;            // mix 0: 64 / 128 = one member of a pair per thread in workgroups of that many positions (models
                                // exchanged through LDS), 0 = both members per thread, -1 = default
+    int sync_segment;          // synchronous baseline: learners per thread (2, 4 or 8), 0: one thread owns all learners of a position, -1: default
     int tri_segment;           // mix 1: ring positions per thread (2, 4 or 8), 0: one thread walks the whole ring, -1: default
     float* mean_buf;           // mix 2: optional buffer of mean_elems floats; when given the global mean runs chunk by
     int64_t mean_elems;        //   chunk of that many elements in two kernels (fewer streams per thread); NULL: one kernel

@@ -113,6 +113,22 @@ def test_ring_neighbour_thirds_at_a_size_that_takes_the_segmented_walk_by_defaul
     _run(4, (4 << 20) + 3, S.RANDOM_RING, 2, mix=S.MIX_TRI)
 
 
+@pytest.mark.parametrize("seg", [2, 4, 8])
+@pytest.mark.parametrize("L,P", [(3, 70001), (5, 4099), (16, 70003), (64, 20001), (128, 1003), (13, 2)])
+def test_synchronous_baseline_update_with_the_learners_in_segments(L, P, seg):
+    # the sum of the updated models runs through the segments of a workgroup in learner order: the same additions in the
+    # same order as one thread per position, bit-exact against the oracle; segments that do not divide L, L <= seg
+    # (falls back), P % 4 tails, fewer than four elements
+    from paper_2110_11199_amd import binding as Bd
+    print("update sync segments", L, P, seg, flush=True)
+    _run(L, P, S.SDPSGD, 3, tune=[(Bd.TUNE_SYNC_SEGMENT, seg)])
+
+
+def test_synchronous_baseline_update_at_a_size_that_takes_the_segments_by_default():
+    print("update sync, 4 x (4M + 1) elements", flush=True)
+    _run(4, (4 << 20) + 1, S.SDPSGD, 2)
+
+
 def test_ring_neighbour_thirds_rejects_stragglers_and_rings_of_fewer_than_three():
     from paper_2110_11199_amd import binding as Bd
     for cfg in (Bd.make_config(4, S.RANDOM_RING, flat_params=16, straggler_p=0.1, mix=Bd.MIX_TRI),
