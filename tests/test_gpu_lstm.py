@@ -224,6 +224,23 @@ def test_synchronous_baseline_small_model(prec):
     assert ora.update_first and ora.consensus() == 0.0
 
 
+@pytest.mark.parametrize("case", ["pair", "tri", "tri_d1d", "sync"])
+def test_segmented_update_kernels_write_the_bf16_copy_of_a_small_model(case):
+    # the update kernels that large models take by default (one member of a pair per thread; the ring or the learners in
+    # segments), forced on a small bf16 model: the bf16 copy of the next gradient point they write feeds the next iteration
+    from paper_2110_11199_amd import binding as Bd
+    print("segmented update kernels, bf16 model", case, flush=True)
+    shape = Shape(12, 32, 2, 1, 0, 52, 5, 7)
+    if case == "pair":
+        _run_recurrence(shape, 5, S.RANDOM_RING, 1, 3, 0.1, tune=((Bd.TUNE_PAIR_SPLIT, 64),), straggler_p=0.2)
+    elif case == "tri":
+        _run_recurrence(shape, 5, S.RANDOM_RING, 1, 3, 0.1, tune=((Bd.TUNE_TRI_SEGMENT, 2),), mix=S.MIX_TRI)
+    elif case == "tri_d1d":
+        _run_recurrence(shape, 5, S.D1D, 1, 3, 0.1, tune=((Bd.TUNE_TRI_SEGMENT, 2),), mix=S.MIX_TRI)
+    else:
+        _run_recurrence(shape, 5, S.SDPSGD, 1, 3, 0.1, tune=((Bd.TUNE_SYNC_SEGMENT, 2),))
+
+
 @pytest.mark.parametrize("groups", [2, 3, 5])
 def test_forward_recurrence_in_learner_groups(groups):
     # large models run the forward recurrence group of learners by group of learners (all frames of a group
