@@ -359,7 +359,7 @@ int adpsgd_probe_stream(int reads, int writes_f32, int writes_bf16, void* dev_bu
 #define ADPSGD_TUNE_MEAN_CHUNK      5   /* global-mean update: elements per chunk of its two-kernel form (a multiple of
                                            1024, at most 16777216), 0 = the single-kernel form, -1 (default) = automatic
                                            (two kernels from 4M parameters on); same results bit for bit */
-#define ADPSGD_TUNE_TRI_SEGMENT     6   /* ring-neighbour update (ADPSGD_MIX_TRI): ring positions one thread owns, 2, 4 or 8
+#define ADPSGD_TUNE_TRI_SEGMENT     6   /* ring-neighbour update (ADPSGD_MIX_TRI): ring positions one thread owns, 1, 2, 4 or 8
                                            (a workgroup then covers the ring of its element positions and the update stays
                                            safe in place), 0 = one thread walks the whole ring, -1 = default; same results
                                            bit for bit */
